@@ -1,0 +1,345 @@
+"""Pins for the CPU oracle: closed forms, invariants, library routines and exact
+brute force, none of which retype the oracle's own formula in the same arithmetic.
+
+What each pin would catch is noted beside it."""
+import decimal
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2311_00257_amd import synth, workloads
+
+F32 = np.float32
+
+
+def f32(x):
+    return float(np.float32(x))
+
+
+# --------------------------------------------------------------------------- shard range
+def test_shard_range_golden(golden_dir):
+    rows = [l.split() for l in open(os.path.join(golden_dir, "shard_ranges.txt")) if l.strip() and l[0] != "#"]
+    assert len(rows) == 5
+    for cfg, phi, factor, rank, begin, end in (map(int, r) for r in rows):
+        w = workloads.get(cfg)
+        assert (w.total_elems, w.shard_factor, w.rank) == (phi, factor, rank)
+        assert oracle.shard_range(phi, factor, rank) == (begin, end)
+
+
+def test_shard_range_tiny_by_hand():
+    # 10 elements over 3 ranks: 4 + 3 + 3
+    assert [oracle.shard_range(10, 3, r) for r in range(3)] == [(0, 4), (4, 7), (7, 10)]
+    assert oracle.shard_range(12345, 1, 0) == (0, 12345)          # factor 1 = Full-Replica
+    assert [oracle.shard_range(2, 4, r) for r in range(4)] == [(0, 1), (1, 2), (2, 2), (2, 2)]
+
+
+@pytest.mark.parametrize("total,s", [(0, 1), (1, 1), (7, 7), (1000, 7), (2**40 + 13, 48), (32528943616, 1024)])
+def test_shard_range_partitions(total, s):
+    # numpy's array_split uses the same "first rem chunks get one more" convention
+    prev = 0
+    sizes = []
+    for r in range(s):
+        b, e = oracle.shard_range(total, s, r)
+        assert b == prev and e >= b
+        prev = e
+        sizes.append(e - b)
+    assert prev == total and max(sizes) - min(sizes) <= 1
+    assert sizes == sorted(sizes, reverse=True)
+    if total <= 1000:
+        assert sizes == [len(c) for c in np.array_split(np.arange(total), s)]
+
+
+# --------------------------------------------------------------------------- reduce
+def _rand_bf16(rng, n, sigma=1.0):
+    x = (rng.standard_normal(n) * sigma).astype(F32)
+    return (x.view(np.uint32) >> 16).astype(np.uint16)
+
+
+def test_reduce_k1_is_exact_widening():
+    bits = np.arange(0, 65536, dtype=np.uint16)
+    bits = bits[np.isfinite(synth.bf16_bits_to_f32(bits))]
+    G = oracle.reduce([bits])
+    assert np.array_equal(G, synth.bf16_bits_to_f32(bits).astype(np.float64))
+
+
+def test_reduce_identical_partials_give_k_times_g():
+    rng = np.random.default_rng(1)
+    g = _rand_bf16(rng, 1000, 1e-3)
+    gv = synth.bf16_bits_to_f32(g).astype(np.float64)
+    for k in (1, 2, 3, 8, 16, 32):
+        assert np.array_equal(oracle.reduce([g] * k), k * gv)      # a mean instead of a sum fails here
+
+
+def test_reduce_matches_exact_rationals_and_is_order_free():
+    rng = np.random.default_rng(2)
+    parts = [_rand_bf16(rng, 64, 10.0 ** rng.integers(-6, 3)) for _ in range(7)]
+    G = oracle.reduce(parts)
+    G_perm = oracle.reduce(parts[::-1])
+    for i in range(64):
+        exact = sum(Fraction(float(synth.bf16_bits_to_f32(p[i:i + 1])[0])) for p in parts)
+        assert Fraction(G[i]) == exact
+    assert np.array_equal(G, G_perm)
+
+
+def test_reduce_threads_same():
+    rng = np.random.default_rng(3)
+    parts = [_rand_bf16(rng, 10007) for _ in range(3)]
+    assert np.array_equal(oracle.reduce(parts, threads=1), oracle.reduce(parts, threads=5))
+
+
+# --------------------------------------------------------------------------- squared norm, clip
+def test_sqnorm_constant_closed_form():
+    # k partials all equal to c: S = n (k c)^2 exactly
+    n, k, c = 4096, 8, 0.375
+    bits = np.full(n, oracle.bf16_rne(c), dtype=np.uint16)
+    assert oracle.sqnorm(oracle.reduce([bits] * k)) == n * (k * c) ** 2
+
+
+def test_sqnorm_matches_library_sums():
+    rng = np.random.default_rng(4)
+    G = rng.standard_normal(200001) * 1e-3
+    S = oracle.sqnorm(G)
+    assert S == pytest.approx(math.fsum((G * G).tolist()), rel=1e-15)   # exactly rounded library sum
+    assert S == pytest.approx(float(np.dot(G, G)), rel=1e-12)
+    assert math.sqrt(S) == pytest.approx(float(np.linalg.norm(G)), rel=1e-12)
+    assert oracle.sqnorm(G, threads=4) == pytest.approx(S, rel=1e-15)
+    assert oracle.sqnorm(np.zeros(0)) == 0.0
+
+
+def test_sqnorm_expected_value_of_synthetic_grads():
+    # E[S] = n k sigma^2 Var(table): a statistical pin on reduce+sqnorm together
+    w = workloads.get(0)
+    n = 1 << 18
+    parts = [synth.fill_bf16(w.key(synth.TENSOR_PARTIAL0 + j), 0, n, w.sigma_grad) for j in range(w.k)]
+    S = oracle.sqnorm(oracle.reduce(parts))
+    assert S == pytest.approx(n * w.k * w.sigma_grad ** 2, rel=0.02)
+
+
+def test_clip_scale_rules():
+    # below the threshold the scale is exactly 1
+    assert oracle.clip_scale(0.25, 1.0) == 1.0
+    assert oracle.clip_scale(0.0, 1.0) == 1.0
+    assert oracle.clip_scale(1e12, 0.0) == 1.0 and oracle.clip_scale(1e12, -1.0) == 1.0   # clipping off
+    # above it the clipped norm is c * norm / (norm + eps) <= c
+    S, c = 10.0, 1.0
+    sc = oracle.clip_scale(S, c)
+    norm = math.sqrt(S)
+    assert sc == pytest.approx(c / (norm + f32(1e-6)), rel=1e-15)
+    assert sc == pytest.approx(0.3162276660168695, rel=1e-9)
+    assert sc * norm <= c
+    # norm exactly at the threshold: c/(c+eps) < 1
+    assert oracle.clip_scale(1.0, 1.0) == pytest.approx(1.0 / (1.0 + f32(1e-6)), rel=1e-15)
+    # threshold scales linearly
+    assert oracle.clip_scale(S, 2.0) == pytest.approx(2.0 / (norm + f32(1e-6)), rel=1e-15)
+
+
+# --------------------------------------------------------------------------- AdamW
+HP = dict(lr=3e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
+
+
+def test_adamw_first_step_closed_form():
+    # m = v = 0, t = 1, wd = 0: v_hat = g^2 so the update is lr g / (|g| + eps); rational, done exactly
+    g = np.array([3e-3, -3e-3, 2.0 ** -8, 0.0, -17.0, 1e-7])
+    p = np.array([0.5, -0.25, 0.0, 1.0, 3.0, -2.0], dtype=F32)
+    z = np.zeros(6, dtype=F32)
+    hp = dict(HP, weight_decay=0.0)
+    p1, m1, v1 = oracle.adamw(g, 1.0, p, z, z, step=1, **hp)
+    lr, eps, b1, b2 = (Fraction(f32(hp[x])) for x in ("lr", "eps", "beta1", "beta2"))
+    for i in range(6):
+        gi = Fraction(float(g[i]))
+        want = Fraction(float(p[i])) - lr * gi / (abs(gi) + eps)
+        assert p1[i] == pytest.approx(float(want), rel=1e-14, abs=1e-18)
+        assert m1[i] == pytest.approx(float((1 - b1) * gi), rel=1e-15)
+        assert v1[i] == pytest.approx(float((1 - b2) * gi * gi), rel=1e-15)
+    # the decimal value quoted for lr 3e-4, g 3e-3 (ideal decimal hyper-parameters): 2.999990000033e-4
+    assert abs(p1[0] - 0.5) == pytest.approx(2.999990000033e-4, rel=1e-7)
+    assert p1[0] < 0.5 < p1[1] + 0.75 and p1[1] > -0.25     # the step opposes the gradient's sign
+
+
+def test_adamw_zero_lr_leaves_params_bit_identical():
+    rng = np.random.default_rng(5)
+    n = 1000
+    G = rng.standard_normal(n)
+    p = (rng.standard_normal(n) * 0.02).astype(F32)
+    m = (rng.standard_normal(n) * 1e-4).astype(F32)
+    v = np.abs(rng.standard_normal(n) * 1e-6).astype(F32)
+    for wd in (0.0, 0.1):
+        p1, m1, v1 = oracle.adamw(G, 0.5, p, m, v, step=7, **dict(HP, lr=0.0, weight_decay=wd))
+        assert np.array_equal(p1, p.astype(np.float64))
+        assert not np.array_equal(m1, m.astype(np.float64)) and not np.array_equal(v1, v.astype(np.float64))
+
+
+def test_adamw_zero_grad_zero_m_is_pure_decay():
+    p = np.array([1.0, -2.0, 0.5], dtype=F32)
+    v = np.array([1e-6, 4.0, 0.0], dtype=F32)
+    z = np.zeros(3, dtype=F32)
+    p1, m1, v1 = oracle.adamw(np.zeros(3), 1.0, p, z, v, step=3, **HP)
+    lr, wd, b2 = f32(HP["lr"]), f32(HP["weight_decay"]), f32(HP["beta2"])
+    assert np.allclose(p1, p.astype(np.float64) * (1 - lr * wd), rtol=1e-15, atol=0)
+    assert np.all(m1 == 0) and np.allclose(v1, b2 * v.astype(np.float64), rtol=1e-15)
+
+
+def test_adamw_zero_betas_is_sign_descent():
+    # beta1 = beta2 = 0: m' = g', v' = g'^2, bias corrections are 1, update = lr g/(|g|+eps)
+    G = np.array([0.25, -4.0, 1e-3])
+    p = np.array([1.0, 1.0, 1.0], dtype=F32)
+    junk = np.array([9.0, 9.0, 9.0], dtype=F32)
+    hp = dict(HP, beta1=0.0, beta2=0.0, weight_decay=0.0)
+    p1, m1, v1 = oracle.adamw(G, 2.0, p, junk, junk, step=5, **hp)
+    g = 2.0 * G
+    assert np.array_equal(m1, g) and np.array_equal(v1, g * g)
+    assert np.allclose(p1, 1.0 - f32(hp["lr"]) * g / (np.abs(g) + f32(hp["eps"])), rtol=1e-15)
+
+
+def _decimal_step(parts, p, m, v, hp, t, max_norm, clip_eps):
+    """The whole step in 60-digit decimal arithmetic: an independent brute force."""
+    D = decimal.Decimal
+    decimal.getcontext().prec = 60
+    k, n = len(parts), len(p)
+    G = [sum(D(float(parts[j][i])) for j in range(k)) for i in range(n)]
+    S = sum(x * x for x in G)
+    scale = min(D(1), D(f32(max_norm)) / (S.sqrt() + D(f32(clip_eps)))) if max_norm > 0 else D(1)
+    lr, b1, b2, eps, wd = (D(f32(hp[x])) for x in ("lr", "beta1", "beta2", "eps", "weight_decay"))
+    out = []
+    for i in range(n):
+        g = scale * G[i]
+        m1 = b1 * D(float(m[i])) + (1 - b1) * g
+        v1 = b2 * D(float(v[i])) + (1 - b2) * g * g
+        u = (m1 / (1 - b1 ** t)) / ((v1 / (1 - b2 ** t)).sqrt() + eps)
+        p1 = D(float(p[i])) - lr * (u + wd * D(float(p[i])))
+        out.append((float(g), float(m1), float(v1), float(p1)))
+    return float(S), float(scale), out
+
+
+def test_worked_example_against_decimal_brute_force():
+    # k=2, n=3, every input exactly representable in bf16/fp32
+    g0 = np.array([0.5, -1.0, 2.0], dtype=F32)
+    g1 = np.array([0.5, 1.0, 1.0], dtype=F32)
+    parts = [(g.view(np.uint32) >> 16).astype(np.uint16) for g in (g0, g1)]
+    p = np.array([1.0, -0.5, 0.25], dtype=F32)
+    m = np.array([0.0, 0.125, -0.25], dtype=F32)
+    v = np.array([0.0, 0.0625, 1.0], dtype=F32)
+    hp = dict(lr=0.125, beta1=0.5, beta2=0.75, eps=1e-8, weight_decay=0.25)
+    r = oracle.step(parts, p, m, v, step=2, max_norm=1.0, clip_eps=1e-6, **hp)
+    S, scale, rows = _decimal_step([g0, g1], p, m, v, hp, 2, 1.0, 1e-6)
+    assert list(r["G"]) == [1.0, 0.0, 3.0] and r["sqnorm"] == 10.0 == S
+    assert r["scale"] == pytest.approx(scale, rel=1e-15)
+    for i, (g, m1, v1, p1) in enumerate(rows):
+        assert r["m"][i] == pytest.approx(m1, rel=1e-14, abs=1e-300)
+        assert r["v"][i] == pytest.approx(v1, rel=1e-14)
+        assert r["p"][i] == pytest.approx(p1, rel=1e-14)
+    # hand-checkable landmarks: element 1 has g' = 0, so m' = 0.5*0.125, v' = 0.75*0.0625
+    assert r["m"][1] == 0.0625 and r["v"][1] == 0.046875
+    assert r["p"][0] == pytest.approx(0.8585103666506315, rel=1e-12)
+    assert [int(b) for b in r["p_bf16"]] == [0x3F5C, 0xBF04, 0x3E50]
+
+
+def _torch_reference(parts_f64, p, m, v, hp, t, max_norm):
+    """torch.optim.AdamW + clip_grad_norm_ in float64 on the CPU: a library routine."""
+    import torch
+
+    param = torch.nn.Parameter(torch.tensor(p.astype(np.float64)))
+    param.grad = torch.tensor(sum(parts_f64))
+    opt = torch.optim.AdamW([param], lr=f32(hp["lr"]), betas=(f32(hp["beta1"]), f32(hp["beta2"])),
+                            eps=f32(hp["eps"]), weight_decay=f32(hp["weight_decay"]), foreach=False)
+    opt.state[param] = dict(step=torch.tensor(float(t - 1)), exp_avg=torch.tensor(m.astype(np.float64)),
+                            exp_avg_sq=torch.tensor(v.astype(np.float64)))
+    if max_norm > 0:
+        torch.nn.utils.clip_grad_norm_([param], max_norm=f32(max_norm))
+    opt.step()
+    st = opt.state[param]
+    return param.detach().numpy(), st["exp_avg"].numpy(), st["exp_avg_sq"].numpy()
+
+
+@pytest.mark.parametrize("max_norm,t", [(0.125, 10), (1e9, 10), (0.0, 1), (0.125, 1000)])
+def test_step_matches_torch_adamw_float64(max_norm, t):
+    # a slice of workload 0: real distributions; its norm is ~0.32, so clipping is active at
+    # max_norm 0.125 and inactive at 1e9 or when switched off (0)
+    w = workloads.get(0)
+    n, off = 50_000, 12_345
+    parts = [synth.fill_bf16(w.key(synth.TENSOR_PARTIAL0 + j), off, n, w.sigma_grad) for j in range(w.k)]
+    p = synth.fill_f32(w.key(synth.TENSOR_MASTER), off, n, w.sigma_param)
+    m = synth.fill_f32(w.key(synth.TENSOR_EXP_AVG), off, n, w.sigma_m)
+    v = synth.fill_f32(w.key(synth.TENSOR_EXP_AVG_SQ), off, n, w.scale_v, absolute=True)
+    hp = dict(lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps, weight_decay=w.weight_decay)
+    r = oracle.step(parts, p, m, v, step=t, max_norm=max_norm, clip_eps=w.clip_eps, **hp)
+    if max_norm == 0.125:
+        assert r["scale"] < 0.5
+    else:
+        assert r["scale"] == 1.0
+    pt, mt, vt = _torch_reference([synth.bf16_bits_to_f32(x).astype(np.float64) for x in parts], p, m, v, hp, t, max_norm)
+    # torch folds the decay as p(1 - lr wd) - lr u, equal in exact arithmetic, so compare at
+    # double rounding level relative to the operands (|p| and the step size lr)
+    assert np.max(np.abs(r["p"] - pt) / (np.abs(p) + f32(w.lr))) < 1e-13
+    assert np.max(np.abs(r["m"] - mt)) < 1e-15 * np.max(np.abs(mt)) * 10
+    assert np.allclose(r["v"], vt, rtol=1e-12, atol=0)
+
+
+# --------------------------------------------------------------------------- cast
+def test_cast_golden_vectors(golden_dir):
+    rows = [l.split() for l in open(os.path.join(golden_dir, "bf16_rne_vectors.txt")) if l.strip() and l[0] != "#"]
+    assert len(rows) >= 15
+    src = np.array([int(r[0], 16) for r in rows], dtype=np.uint32).view(F32)
+    want = [int(r[1], 16) for r in rows]
+    assert [int(x) for x in oracle.cast(src)] == want
+
+
+def test_cast_exhaustive_high_halves_against_torch():
+    import torch
+
+    hi = np.arange(65536, dtype=np.uint32) << 16
+    lows = np.array([0x0000, 0x0001, 0x7FFF, 0x8000, 0x8001, 0xFFFF], dtype=np.uint32)
+    bits = (hi[:, None] | lows[None, :]).reshape(-1)
+    x = bits.view(F32)
+    got = oracle.cast(x)
+    ref = torch.from_numpy(x.copy()).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    nan = np.isnan(x)
+    assert np.array_equal(got[~nan], ref[~nan])          # bit-exact on every non-NaN input
+    g_nan = got[nan]
+    assert np.all((g_nan & 0x7FFF) == 0x7FC0)            # NaN stays a quiet NaN ...
+    assert np.array_equal(g_nan >> 15, (bits[nan] >> 31).astype(np.uint16))   # ... with its sign
+
+
+def test_cast_random_against_torch_and_roundtrip():
+    import torch
+
+    rng = np.random.default_rng(6)
+    x = (rng.standard_normal(300_000) * 10.0 ** rng.integers(-30, 30, 300_000)).astype(F32)
+    got = oracle.cast(x)
+    ref = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(got, ref)
+    back = synth.bf16_bits_to_f32(got)
+    # bf16 spacing at |back|: 2^(e-7) for |back| in [2^e, 2^(e+1)), 2^-133 below 2^-126
+    e = np.frexp(np.maximum(np.abs(back), np.float32(2.0 ** -126)).astype(np.float64))[1] - 1
+    half_ulp = np.ldexp(1.0, e - 8)
+    assert np.all(np.abs(back.astype(np.float64) - x) <= half_ulp)       # the nearest bf16 value
+    assert np.array_equal(oracle.cast(back), got)        # idempotent on bf16 values
+    assert np.array_equal(oracle.cast(x, threads=3), got)
+
+
+# --------------------------------------------------------------------------- synthetic inputs
+def test_synth_is_stateless_and_sliceable():
+    key = synth.stream_key(20231101, synth.TENSOR_MASTER)
+    a = synth.fill_f32(key, 1000, 5000, 0.02)
+    b = synth.fill_f32(key, 3000, 100, 0.02)
+    assert np.array_equal(a[2000:2100], b)
+    idx = np.array([2**40 + 7, 5, 2**33], dtype=np.uint64)
+    assert np.array_equal(synth.f32_at(key, idx, 0.02),
+                          np.array([synth.fill_f32(key, int(i), 1, 0.02)[0] for i in idx]))
+    assert synth.stream_key(1, 0) != synth.stream_key(1, 1) != synth.stream_key(2, 0)
+    g = synth.fill_bf16(key, 0, 4096, 1e-3)
+    assert np.all(np.abs(synth.bf16_bits_to_f32(g)) < 5e-3)
+    v = synth.fill_f32(key, 0, 4096, 1e-6, absolute=True)
+    assert np.all(v >= 0)
+
+
+def test_synth_distribution():
+    t = synth.normal_table()
+    assert t.shape == (65536,) and np.all(np.diff(t) > 0) and t[0] == -t[-1]
+    assert float(np.var(t.astype(np.float64))) == pytest.approx(1.0, abs=2e-3)
+    x = synth.fill_f32(synth.stream_key(7, 0), 0, 1 << 20, 1.0)
+    assert abs(float(x.mean())) < 5e-3 and float(x.std()) == pytest.approx(1.0, abs=5e-3)
