@@ -1,0 +1,158 @@
+/*
+ * amsp.h: C ABI of the per-GPU model-state step of a ZeRO-style data-parallel rank.
+ *
+ * One rank owns a contiguous flat shard of the model states: bf16 parameters P, bf16
+ * gradients G and the fp32 optimizer states OS (master copy, first and second Adam
+ * moments): 2 + 2 + 12 bytes per parameter (Section II-C, "ZeRO"; Section IV-D).  Between
+ * "the partial gradients have arrived" and "the updated bf16 shard is ready to ship" the
+ * rank does, on its Phi/s elements (Section IV-C.2):
+ *
+ *   1. reduce      sum the k partial bf16 gradient buffers in fp32: the arithmetic half of
+ *                  the ReduceScatter / AllReduce-then-select of Sections II-C and IV-C;
+ *   2. sqnorm      squared L2 norm of the reduced gradient, for global-norm clipping
+ *                  (not in the paper; the usual rule  scale = min(1, c/(||g|| + clip_eps)));
+ *   3. AdamW       update fp32 master/m/v in place (Adam under mixed precision, Section II-C);
+ *   4. cast        round the updated master to bf16: the payload the AllGather / Broadcast of
+ *                  Section IV-C.2 ships.
+ *
+ * amsp_adamw_step_shard fuses 1 + 3 + 4 in one streaming pass (2k + 26 bytes per element).
+ *
+ * Conventions, for every function below
+ *   - Returns an int status: AMSP_OK (0) or a negative AMSP_E* code.  Never throws, aborts,
+ *     allocates or frees.  On an error nothing has been enqueued and outputs are untouched.
+ *   - "device" pointers are HIP device memory valid on the current device; "host" pointers
+ *     are ordinary host memory read during the call only.  The caller owns every buffer.
+ *   - Every data pointer addresses the FIRST element of the range to process (the caller
+ *     applies its shard or bucket offset); element i of every buffer is the same model-state
+ *     element.  Buffers must not overlap, except that master/m/v are updated in place.
+ *   - Pointers need only natural alignment (2 B bf16, 4 B fp32, 8 B double).  When all
+ *     streams of a call reach 16-byte alignment at the same element index the kernels use
+ *     128-bit accesses; otherwise a slower element-wise path gives the same results.
+ *   - bf16 values are passed as uint16_t bit patterns.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is
+ *     enqueued and the call returns without waiting; amsp_shard_range alone is synchronous.
+ *   - `bucket_elems` (Section IV-C.2: gradients are synchronised in buckets of size U; here
+ *     counted in elements): 0 processes [0,n) in one launch; U > 0 processes the buckets
+ *     [bU, min((b+1)U, n)) in order, one launch each, as they would arrive.
+ *   - n == 0 is valid: AMSP_OK, nothing launched (amsp_grad_sqnorm still writes 0 when
+ *     accumulate == 0).
+ *   - The reduction order over j = 0..k-1 is fixed and fp32, identical in every entry point,
+ *     so the gradient seen by the norm, the separate reduce and the fused step is bitwise
+ *     the same.  All results are deterministic run to run.
+ */
+#ifndef AMSP_H
+#define AMSP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    AMSP_OK = 0,
+    AMSP_EINVAL = -1,     /* bad k / shard factor / rank / hyper-parameter */
+    AMSP_ENULL = -2,      /* a required pointer is NULL */
+    AMSP_EALIGN = -3,     /* a pointer is not aligned to its element size */
+    AMSP_EWORKSPACE = -4, /* workspace smaller than amsp_workspace_bytes() */
+    AMSP_EDEVICE = -5     /* a HIP call failed */
+};
+
+#define AMSP_MAX_K 32u
+
+/* Static description of a status code; never NULL. */
+const char *amsp_status_string(int status);
+
+/* Bytes of device workspace amsp_grad_sqnorm needs (a fixed, small number). */
+size_t amsp_workspace_bytes(void);
+
+/*
+ * Rank `rank`'s range [*begin, *end) of a flat buffer of `total_elems` elements split evenly
+ * over `shard_factor` ranks (Section IV-B: sharding factor s, 1 = Full-Replica; Section IV-C.2:
+ * each GPU updates Phi/s_os parameters, split evenly).  The first total_elems % shard_factor
+ * ranks get one element more; ranges are contiguous, disjoint and cover [0, total_elems).
+ * Host only, pure.  begin/end: host, written on success.
+ * Errors: AMSP_EINVAL if shard_factor == 0 or rank >= shard_factor; AMSP_ENULL.
+ */
+int amsp_shard_range(uint64_t total_elems, uint32_t shard_factor, uint32_t rank,
+                     uint64_t *begin, uint64_t *end);
+
+/*
+ * Step 1 alone: grad_out[i] (=|+=) sum_{j<k} partials[j][i], in fp32, j ascending.
+ *   partials    host array of k device pointers, each bf16[n]
+ *   k           1..AMSP_MAX_K
+ *   grad_out    device fp32[n]
+ *   accumulate  0: overwrite; 1: add the sum to what grad_out holds (gradient accumulation
+ *               over micro-batches, Section IV-C.3)
+ */
+int amsp_reduce_grad_shard(const uint16_t *const *partials, uint32_t k, uint64_t n,
+                           uint64_t bucket_elems, float *grad_out, int accumulate, void *stream);
+
+/*
+ * Step 2: *d_sqnorm (=|+=) sum_i g[i]^2 with g the reduced gradient, accumulated in fp64 in a
+ * fixed order.  The cross-rank sum of these scalars (one 8-byte all-reduce) is the caller's.
+ *   k >= 1      g is recomputed from `partials` exactly as in step 1 (grad_f32 ignored)
+ *   k == 0      g is read from grad_f32, device fp32[n] (partials ignored)
+ *   d_sqnorm    device double, written when the enqueued work completes
+ *   accumulate  0: overwrite; 1: add to the value already there (in bucket order)
+ *   workspace   device, >= amsp_workspace_bytes(), 8-byte aligned; contents need no
+ *               initialisation and are clobbered; calls sharing a workspace must be ordered
+ *               on one stream
+ */
+int amsp_grad_sqnorm(const uint16_t *const *partials, uint32_t k, const float *grad_f32,
+                     uint64_t n, uint64_t bucket_elems, double *d_sqnorm, int accumulate,
+                     void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Hyper-parameters of one AdamW step.  With g' = scale * g:
+ *   m <- beta1 m + (1 - beta1) g'
+ *   v <- beta2 v + (1 - beta2) g'^2
+ *   p <- p - lr ( (m / (1 - beta1^step)) / (sqrt(v / (1 - beta2^step)) + eps) + weight_decay p )
+ * scale:
+ *   d_total_sqnorm != NULL: read on the device when the kernel runs,
+ *       scale = max_norm > 0 ? min(1, max_norm / (sqrt(*d_total_sqnorm) + clip_eps)) : 1
+ *       (no host synchronisation between the norm pass and the update), times grad_scale;
+ *   d_total_sqnorm == NULL: scale = grad_scale (max_norm and clip_eps unused).
+ * grad_scale is where a caller folds 1/(number of micro-batches or ranks) or a loss scale.
+ */
+typedef struct amsp_adamw_hparams {
+    float lr;
+    float beta1;
+    float beta2;
+    float eps;
+    float weight_decay;
+    uint32_t step;                /* t >= 1: index of the update being applied */
+    float max_norm;               /* <= 0: no clipping */
+    float clip_eps;               /* conventionally 1e-6 */
+    const double *d_total_sqnorm; /* device, may be NULL */
+    float grad_scale;             /* 1.0f for none */
+} amsp_adamw_hparams;
+
+/*
+ * Steps 1 + 3 + 4 fused: one pass that reduces the partials, updates master/m/v in place and
+ * writes the bf16 parameters.
+ *   k >= 1          gradient = fp32 sum of `partials` (as step 1); grad_f32 ignored
+ *   k == 0          gradient read from grad_f32, device fp32[n]
+ *   master, exp_avg, exp_avg_sq   device fp32[n], read and written in place
+ *   param_bf16_out  device bf16[n], or NULL to skip step 4
+ *   hp              host, read during the call
+ * Errors: AMSP_EINVAL for k > AMSP_MAX_K, step == 0, non-finite lr/beta/eps/weight_decay/
+ * clip_eps/grad_scale, beta outside [0,1), eps < 0; AMSP_ENULL; AMSP_EALIGN; AMSP_EDEVICE.
+ */
+int amsp_adamw_step_shard(const uint16_t *const *partials, uint32_t k, const float *grad_f32,
+                          uint64_t n, uint64_t bucket_elems,
+                          float *master, float *exp_avg, float *exp_avg_sq,
+                          uint16_t *param_bf16_out, const amsp_adamw_hparams *hp, void *stream);
+
+/*
+ * Step 4 alone: param_bf16_out[i] = bf16(master[i]), round to nearest even on the bit pattern;
+ * NaN -> quiet NaN with the sign kept (0x7FC0 | sign), +-Inf kept, finite overflow -> +-Inf,
+ * subnormals rounded, not flushed.  master: device fp32[n]; param_bf16_out: device bf16[n].
+ */
+int amsp_cast_param_shard(const float *master, uint16_t *param_bf16_out, uint64_t n, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AMSP_H */

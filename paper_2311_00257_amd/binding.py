@@ -1,0 +1,157 @@
+"""ctypes binding of the C-ABI library ``libamsp.so`` (declared in ``include/amsp.h``).
+
+Argument marshalling only: every function has the name and meaning of its C counterpart,
+takes torch device tensors (or raw integer addresses) where C takes device pointers, and
+raises :class:`AmspError` on a non-zero status.  torch supplies device memory and the
+stream; all arithmetic runs in the HIP kernels.  There is no fallback: if the library has
+not been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import dataclasses
+import os
+from typing import Optional, Sequence
+
+from . import build as _build
+
+AMSP_OK, AMSP_EINVAL, AMSP_ENULL, AMSP_EALIGN, AMSP_EWORKSPACE, AMSP_EDEVICE = 0, -1, -2, -3, -4, -5
+AMSP_MAX_K = 32
+
+EXPORTS = ("amsp_status_string", "amsp_workspace_bytes", "amsp_shard_range", "amsp_reduce_grad_shard",
+           "amsp_grad_sqnorm", "amsp_adamw_step_shard", "amsp_cast_param_shard")
+
+
+class AmspError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s: status %d (%s)" % (where, status, amsp_status_string(status)))
+
+
+class _Hparams(ctypes.Structure):
+    _fields_ = [("lr", ctypes.c_float), ("beta1", ctypes.c_float), ("beta2", ctypes.c_float),
+                ("eps", ctypes.c_float), ("weight_decay", ctypes.c_float), ("step", ctypes.c_uint32),
+                ("max_norm", ctypes.c_float), ("clip_eps", ctypes.c_float),
+                ("d_total_sqnorm", ctypes.c_void_p), ("grad_scale", ctypes.c_float)]
+
+
+@dataclasses.dataclass
+class AdamWHparams:
+    """Mirror of ``amsp_adamw_hparams``; ``d_total_sqnorm`` is a device double tensor or None."""
+    lr: float
+    beta1: float
+    beta2: float
+    eps: float
+    weight_decay: float
+    step: int
+    max_norm: float = 0.0
+    clip_eps: float = 1e-6
+    d_total_sqnorm: object = None
+    grad_scale: float = 1.0
+
+
+_lib = None
+
+
+def load() -> ctypes.CDLL:
+    """Load ``libamsp.so`` from the package directory; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_build.LIB_AMSP):
+            raise RuntimeError("libamsp.so is not built: run `python -m paper_2311_00257_amd.build` "
+                               "(there is no CPU fallback)")
+        lib = ctypes.CDLL(_build.LIB_AMSP)
+        u64, u32, vp, ci = ctypes.c_uint64, ctypes.c_uint32, ctypes.c_void_p, ctypes.c_int
+        lib.amsp_status_string.argtypes = [ci]
+        lib.amsp_status_string.restype = ctypes.c_char_p
+        lib.amsp_workspace_bytes.argtypes = []
+        lib.amsp_workspace_bytes.restype = ctypes.c_size_t
+        lib.amsp_shard_range.argtypes = [u64, u32, u32, ctypes.POINTER(u64), ctypes.POINTER(u64)]
+        lib.amsp_reduce_grad_shard.argtypes = [vp, u32, u64, u64, vp, ci, vp]
+        lib.amsp_grad_sqnorm.argtypes = [vp, u32, vp, u64, u64, vp, ci, vp, ctypes.c_size_t, vp]
+        lib.amsp_adamw_step_shard.argtypes = [vp, u32, vp, u64, u64, vp, vp, vp, vp, ctypes.POINTER(_Hparams), vp]
+        lib.amsp_cast_param_shard.argtypes = [vp, vp, u64, vp]
+        for name in EXPORTS[2:]:
+            getattr(lib, name).restype = ci
+        _lib = lib
+    return _lib
+
+
+def _ptr(x) -> Optional[int]:
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    return x.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+
+        return torch.cuda.current_stream().cuda_stream or None
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None
+
+
+def _partials(partials: Optional[Sequence]):
+    if partials is None:
+        return None, 0
+    k = len(partials)
+    arr = (ctypes.c_void_p * max(k, 1))(*[_ptr(p) for p in partials])
+    return arr, k
+
+
+def _check(status: int, where: str) -> None:
+    if status != AMSP_OK:
+        raise AmspError(status, where)
+
+
+def amsp_status_string(status: int) -> str:
+    return load().amsp_status_string(status).decode()
+
+
+def amsp_workspace_bytes() -> int:
+    return int(load().amsp_workspace_bytes())
+
+
+def amsp_shard_range(total_elems: int, shard_factor: int, rank: int):
+    b, e = ctypes.c_uint64(), ctypes.c_uint64()
+    _check(load().amsp_shard_range(total_elems, shard_factor, rank, ctypes.byref(b), ctypes.byref(e)),
+           "amsp_shard_range")
+    return b.value, e.value
+
+
+def amsp_reduce_grad_shard(partials, n: int, grad_out, bucket_elems: int = 0, accumulate: bool = False,
+                           stream=None) -> None:
+    arr, k = _partials(partials)
+    _check(load().amsp_reduce_grad_shard(arr, k, n, bucket_elems, _ptr(grad_out), int(accumulate), _stream(stream)),
+           "amsp_reduce_grad_shard")
+
+
+def amsp_grad_sqnorm(partials, grad_f32, n: int, d_sqnorm, workspace, bucket_elems: int = 0,
+                     accumulate: bool = False, stream=None, workspace_bytes: Optional[int] = None) -> None:
+    arr, k = _partials(partials)
+    if workspace_bytes is None:
+        workspace_bytes = 0 if workspace is None or isinstance(workspace, int) else workspace.numel() * workspace.element_size()
+    _check(load().amsp_grad_sqnorm(arr, k, _ptr(grad_f32), n, bucket_elems, _ptr(d_sqnorm), int(accumulate),
+                                   _ptr(workspace), workspace_bytes, _stream(stream)), "amsp_grad_sqnorm")
+
+
+def amsp_adamw_step_shard(partials, grad_f32, n: int, master, exp_avg, exp_avg_sq, param_bf16_out,
+                          hp: AdamWHparams, bucket_elems: int = 0, stream=None) -> None:
+    arr, k = _partials(partials)
+    c = None
+    if hp is not None:
+        c = _Hparams(hp.lr, hp.beta1, hp.beta2, hp.eps, hp.weight_decay, hp.step, hp.max_norm, hp.clip_eps,
+                     _ptr(hp.d_total_sqnorm), hp.grad_scale)
+    _check(load().amsp_adamw_step_shard(arr, k, _ptr(grad_f32), n, bucket_elems, _ptr(master), _ptr(exp_avg),
+                                        _ptr(exp_avg_sq), _ptr(param_bf16_out),
+                                        ctypes.byref(c) if c is not None else None, _stream(stream)),
+           "amsp_adamw_step_shard")
+
+
+def amsp_cast_param_shard(master, param_bf16_out, n: int, stream=None) -> None:
+    _check(load().amsp_cast_param_shard(_ptr(master), _ptr(param_bf16_out), n, _stream(stream)),
+           "amsp_cast_param_shard")

@@ -2,8 +2,10 @@
 
 A stateless, counter-based generator: element ``i`` of tensor ``tensor_id`` under
 ``seed`` is a pure function of those three integers, so any element of a 100 GB
-state can be regenerated on the host without storing it, and the device fill
-kernels (``csrc/synth_fill.hip``) produce the same bits.
+state can be regenerated on the host without storing it.  Three implementations give the
+same bits: the numpy formulas here (``*_at``, any index set), the plain-C contiguous fills
+(``csrc/synth_host.c``, used by ``fill_*``) and the device fill kernels
+(``csrc/synth_fill.hip``).
 
 Recipe per element:
   1. ``h = splitmix64(key + i * GOLDEN)`` where ``key`` depends on (seed, tensor_id)
@@ -88,16 +90,58 @@ def bf16_at(key: int, indices: np.ndarray, sigma: float) -> np.ndarray:
     return (x.view(np.uint32) >> np.uint32(16)).astype(np.uint16)
 
 
-def fill_f32(key: int, index0: int, n: int, sigma: float, absolute: bool = False) -> np.ndarray:
-    """fp32[n] for global indices index0 .. index0+n-1."""
-    idx = np.arange(index0, index0 + n, dtype=np.uint64)
-    return f32_at(key, idx, sigma, absolute)
+_host_lib = None
 
 
-def fill_bf16(key: int, index0: int, n: int, sigma: float) -> np.ndarray:
-    """bf16[n] (as uint16) for global indices index0 .. index0+n-1."""
-    idx = np.arange(index0, index0 + n, dtype=np.uint64)
-    return bf16_at(key, idx, sigma)
+def _host():
+    """The C implementation of the contiguous fills (csrc/synth_host.c), built on first use."""
+    global _host_lib
+    if _host_lib is None:
+        import ctypes
+
+        from . import build
+
+        lib = ctypes.CDLL(build.build_host_synth())
+        u64, vp = ctypes.c_uint64, ctypes.c_void_p
+        lib.amsp_synth_host_f32.argtypes = [vp, u64, u64, u64, vp, ctypes.c_float, ctypes.c_int]
+        lib.amsp_synth_host_f32.restype = None
+        lib.amsp_synth_host_bf16.argtypes = [vp, u64, u64, u64, vp, ctypes.c_float]
+        lib.amsp_synth_host_bf16.restype = None
+        _host_lib = lib
+    return _host_lib
+
+
+def _parallel(n: int, threads: int, fn) -> None:
+    threads = max(1, min(threads, max(1, n // 65536)))
+    if threads == 1:
+        fn(0, n)
+        return
+    from concurrent.futures import ThreadPoolExecutor
+
+    edges = [n * c // threads for c in range(threads + 1)]
+    with ThreadPoolExecutor(threads) as ex:
+        list(ex.map(lambda c: fn(edges[c], edges[c + 1]), range(threads)))
+
+
+def fill_f32(key: int, index0: int, n: int, sigma: float, absolute: bool = False, out=None,
+             threads: int = 1) -> np.ndarray:
+    """fp32[n] for global indices index0 .. index0+n-1 (into ``out[:n]`` when given)."""
+    out = np.empty(n, dtype=np.float32) if out is None else out[:n]
+    assert out.dtype == np.float32 and out.flags.c_contiguous
+    lib, table = _host(), normal_table()
+    _parallel(n, threads, lambda lo, hi: lib.amsp_synth_host_f32(
+        out.ctypes.data + 4 * lo, hi - lo, key, index0 + lo, table.ctypes.data, sigma, int(absolute)))
+    return out
+
+
+def fill_bf16(key: int, index0: int, n: int, sigma: float, out=None, threads: int = 1) -> np.ndarray:
+    """bf16[n] (as uint16) for global indices index0 .. index0+n-1 (into ``out[:n]`` when given)."""
+    out = np.empty(n, dtype=np.uint16) if out is None else out[:n]
+    assert out.dtype == np.uint16 and out.flags.c_contiguous
+    lib, table = _host(), normal_table()
+    _parallel(n, threads, lambda lo, hi: lib.amsp_synth_host_bf16(
+        out.ctypes.data + 2 * lo, hi - lo, key, index0 + lo, table.ctypes.data, sigma))
+    return out
 
 
 def bf16_bits_to_f32(bits: np.ndarray) -> np.ndarray:

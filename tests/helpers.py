@@ -1,0 +1,123 @@
+"""Shared plumbing of the GPU parity tests: seeded inputs on host and device, and the
+comparison rules.  No arithmetic of the step lives here; expected values come from
+``oracle`` only."""
+from __future__ import annotations
+
+import dataclasses
+
+import numpy as np
+
+from paper_2311_00257_amd import synth, workloads
+
+REL_TOL = 1e-5          # stated bar: fp32 master/m/v and the gradient norm within 1e-5 relative
+
+
+def hparams_of(w: workloads.Workload, **over):
+    hp = dict(lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps, weight_decay=w.weight_decay, step=w.step,
+              max_norm=w.max_norm, clip_eps=w.clip_eps)
+    hp.update(over)
+    return hp
+
+
+@dataclasses.dataclass
+class HostInputs:
+    partials: list          # k uint16 arrays (bf16 patterns)
+    p: np.ndarray
+    m: np.ndarray
+    v: np.ndarray
+
+
+def host_inputs(w: workloads.Workload, index0: int, n: int, k=None, threads: int = 4) -> HostInputs:
+    """The workload's streams for global indices index0 .. index0+n-1."""
+    k = w.k if k is None else k
+    parts = [synth.fill_bf16(w.key(synth.TENSOR_PARTIAL0 + j), index0, n, w.sigma_grad, threads=threads)
+             for j in range(k)]
+    return HostInputs(parts,
+                      synth.fill_f32(w.key(synth.TENSOR_MASTER), index0, n, w.sigma_param, threads=threads),
+                      synth.fill_f32(w.key(synth.TENSOR_EXP_AVG), index0, n, w.sigma_m, threads=threads),
+                      synth.fill_f32(w.key(synth.TENSOR_EXP_AVG_SQ), index0, n, w.scale_v, absolute=True,
+                                     threads=threads))
+
+
+def to_dev_bf16(bits: np.ndarray, pad_front: int = 0):
+    """uint16 patterns -> device int16 tensor; with pad_front > 0 the data starts that many
+    elements into a fresh allocation (to shift its alignment)."""
+    import torch
+
+    buf = torch.empty(pad_front + bits.size, dtype=torch.int16, device="cuda")
+    view = buf[pad_front:]
+    view.copy_(torch.from_numpy(bits.view(np.int16)))
+    return view
+
+
+def to_dev_f32(x: np.ndarray, pad_front: int = 0):
+    import torch
+
+    buf = torch.empty(pad_front + x.size, dtype=torch.float32, device="cuda")
+    view = buf[pad_front:]
+    view.copy_(torch.from_numpy(x))
+    return view
+
+
+def dev_bits(t) -> np.ndarray:
+    """2-byte device tensor -> uint16 patterns on the host."""
+    import torch
+
+    return t.view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def rel_err_scaled(got: np.ndarray, want: np.ndarray, floor: np.ndarray) -> np.ndarray:
+    """|got - want| / max(|want|, floor): relative error with the denominator kept from
+    collapsing where the true value is small only because its operands cancelled."""
+    den = np.maximum(np.abs(want), floor)
+    den = np.where(den == 0, 1.0, den)
+    return np.abs(got.astype(np.float64) - want) / den
+
+
+def check_state(got_p, got_m, got_v, ref: dict, inp_p, inp_m, hp: dict, tol: float = REL_TOL):
+    """fp32 master/m/v against the oracle's doubles.  The floor of each denominator is the
+    largest operand of the final addition: |p| and the applied step for the master,
+    beta1 |m| and (1-beta1)|g'| for the first moment; the second moment has no cancellation."""
+    b1 = float(np.float32(hp["beta1"]))
+    gs = np.abs(ref["scale"] * ref["G"])
+    floor_p = np.maximum(np.abs(inp_p.astype(np.float64)), np.abs(ref["p"] - inp_p))
+    floor_m = np.maximum(b1 * np.abs(inp_m.astype(np.float64)), (1 - b1) * gs)
+    ep = rel_err_scaled(got_p, ref["p"], floor_p)
+    em = rel_err_scaled(got_m, ref["m"], floor_m)
+    ev = rel_err_scaled(got_v, ref["v"], np.zeros(1))
+    stats = dict(max_p=float(ep.max(initial=0)), max_m=float(em.max(initial=0)), max_v=float(ev.max(initial=0)))
+    # the strict element-wise figure, reported for audit
+    with np.errstate(divide="ignore", invalid="ignore"):
+        strict = np.abs(got_p.astype(np.float64) - ref["p"]) / np.abs(ref["p"])
+    stats["strict_max_p"] = float(np.nanmax(strict)) if strict.size else 0.0
+    stats["strict_over_tol_p"] = int(np.sum(strict > tol))
+    assert stats["max_p"] <= tol and stats["max_m"] <= tol and stats["max_v"] <= tol, stats
+    return stats
+
+
+def _bf16_neighbours(bits: np.ndarray):
+    f = synth.bf16_bits_to_f32(bits).astype(np.float64)
+    return f
+
+
+def check_bf16(got_bits: np.ndarray, ref: dict, tol: float = REL_TOL) -> int:
+    """bf16 parameters: identical to bf16(fp32(p')) of the oracle, except that where the
+    oracle's double p' lies within `tol` (relative) of the midpoint of two adjacent bf16
+    values the other neighbour is accepted (a difference of exactly one bf16 step).
+    Returns the number of such mismatches."""
+    want = ref["p_bf16"]
+    bad = np.nonzero(got_bits != want)[0]
+    if bad.size == 0:
+        return 0
+    g = synth.bf16_bits_to_f32(got_bits[bad]).astype(np.float64)
+    w = synth.bf16_bits_to_f32(want[bad]).astype(np.float64)
+    # adjacent patterns (same sign): magnitudes differ by one in the integer encoding;
+    # +0 / -0 cannot be told apart by a rounding boundary, so they never qualify
+    step = np.abs((got_bits[bad] & 0x7FFF).astype(np.int64) - (want[bad] & 0x7FFF).astype(np.int64))
+    same_sign = (got_bits[bad] >> 15) == (want[bad] >> 15)
+    mid = 0.5 * (g + w)
+    near = np.abs(ref["p"][bad] - mid) <= tol * np.abs(ref["p"][bad])
+    ok = (step == 1) & same_sign & near
+    assert np.all(ok), "bf16 mismatches away from a rounding boundary: %d of %d (first index %d)" % (
+        int(np.sum(~ok)), bad.size, int(bad[np.argmin(ok)]))
+    return int(bad.size)

@@ -1,0 +1,124 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every function the header
+declares, and its host-side logic (shard ranges, argument validation) behaves as
+documented.  Nothing here launches device work."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2311_00257_amd import binding as B
+from paper_2311_00257_amd import build, workloads
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _built():
+    if not build.built():
+        build.build_all(verbose=False)
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "amsp.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(amsp_[a-z0-9_]+)\s*\(", header))
+    assert {"amsp_shard_range", "amsp_reduce_grad_shard", "amsp_grad_sqnorm", "amsp_adamw_step_shard",
+            "amsp_cast_param_shard"} <= declared
+    lib = B.load()
+    for name in sorted(declared):
+        assert hasattr(lib, name), name
+    assert declared == set(B.EXPORTS)
+    synth_lib = ctypes.CDLL(build.LIB_SYNTH)
+    assert hasattr(synth_lib, "amsp_synth_fill_f32") and hasattr(synth_lib, "amsp_synth_fill_bf16")
+
+
+def test_hparams_struct_layout_matches_header():
+    # float x5, uint32, float x2, pointer (8-aligned), float, tail padding
+    assert B._Hparams.d_total_sqnorm.offset == 32
+    assert B._Hparams.grad_scale.offset == 40
+    assert ctypes.sizeof(B._Hparams) == 48
+
+
+def test_status_strings_and_workspace():
+    for code in (0, -1, -2, -3, -4, -5):
+        assert B.amsp_status_string(code) and "unknown" not in B.amsp_status_string(code)
+    assert "unknown" in B.amsp_status_string(-99)
+    assert B.amsp_workspace_bytes() >= 8 and B.amsp_workspace_bytes() % 8 == 0
+
+
+def test_shard_range_bit_exact_against_oracle():
+    rng = np.random.default_rng(0)
+    cases = [(w.total_elems, w.shard_factor, w.rank) for w in workloads.WORKLOADS]
+    cases += [(10, 3, r) for r in range(3)] + [(2, 4, r) for r in range(4)] + [(0, 5, 2), (2**64 - 1, 1000, 999)]
+    cases += [(int(rng.integers(0, 2**50)), int(s), int(rng.integers(0, s))) for s in rng.integers(1, 100000, 2000)]
+    for total, s, r in cases:
+        assert B.amsp_shard_range(total, s, r) == oracle.shard_range(total, s, r)
+
+
+def test_shard_range_errors():
+    for args in ((10, 0, 0), (10, 4, 4), (10, 4, 5)):
+        with pytest.raises(B.AmspError) as ei:
+            B.amsp_shard_range(*args)
+        assert ei.value.status == B.AMSP_EINVAL
+    b = ctypes.c_uint64()
+    assert B.load().amsp_shard_range(10, 2, 0, None, ctypes.byref(b)) == B.AMSP_ENULL
+
+
+HP = dict(lr=1e-3, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.0, step=1)
+
+
+def _status(fn, *a, **kw):
+    with pytest.raises(B.AmspError) as ei:
+        fn(*a, stream=0, **kw)
+    return ei.value.status
+
+
+def test_argument_validation_without_device():
+    """All of these must be rejected on the host before any HIP call (fake addresses)."""
+    A = 0x10000   # a 16-byte aligned fake address, never dereferenced
+    assert _status(B.amsp_cast_param_shard, 0, A, 8) == B.AMSP_ENULL
+    assert _status(B.amsp_cast_param_shard, A, 0, 8) == B.AMSP_ENULL
+    assert _status(B.amsp_cast_param_shard, A + 2, A, 8) == B.AMSP_EALIGN
+    assert _status(B.amsp_cast_param_shard, A, A + 1, 8) == B.AMSP_EALIGN
+    B.amsp_cast_param_shard(0, 0, 0, stream=0)                      # n == 0: fine, nothing to do
+
+    assert _status(B.amsp_reduce_grad_shard, [], 8, A) == B.AMSP_EINVAL
+    assert _status(B.amsp_reduce_grad_shard, [A] * 33, 8, A) == B.AMSP_EINVAL
+    assert _status(B.amsp_reduce_grad_shard, [A, 0], 8, A) == B.AMSP_ENULL
+    assert _status(B.amsp_reduce_grad_shard, [A, A + 1], 8, A) == B.AMSP_EALIGN
+    assert _status(B.amsp_reduce_grad_shard, [A], 8, 0) == B.AMSP_ENULL
+    assert _status(B.amsp_reduce_grad_shard, [A], 8, A + 2) == B.AMSP_EALIGN
+    B.amsp_reduce_grad_shard([A], 0, 0, stream=0)
+
+    ws = B.amsp_workspace_bytes()
+    assert _status(B.amsp_grad_sqnorm, [A], None, 8, 0, A, workspace_bytes=ws) == B.AMSP_ENULL
+    assert _status(B.amsp_grad_sqnorm, [A], None, 8, A, 0, workspace_bytes=ws) == B.AMSP_ENULL
+    assert _status(B.amsp_grad_sqnorm, [A], None, 8, A + 4, A, workspace_bytes=ws) == B.AMSP_EALIGN
+    assert _status(B.amsp_grad_sqnorm, [A], None, 8, A, A, workspace_bytes=ws - 1) == B.AMSP_EWORKSPACE
+    assert _status(B.amsp_grad_sqnorm, None, None, 8, A, A, workspace_bytes=ws) == B.AMSP_ENULL
+    assert _status(B.amsp_grad_sqnorm, None, A + 2, 8, A, A, workspace_bytes=ws) == B.AMSP_EALIGN
+    assert _status(B.amsp_grad_sqnorm, [A] * 40, None, 8, A, A, workspace_bytes=ws) == B.AMSP_EINVAL
+
+    hp = B.AdamWHparams(**HP)
+    assert _status(B.amsp_adamw_step_shard, [A], None, 8, A, A, A, A, None) == B.AMSP_ENULL
+    assert _status(B.amsp_adamw_step_shard, [A], None, 8, 0, A, A, A, hp) == B.AMSP_ENULL
+    assert _status(B.amsp_adamw_step_shard, None, None, 8, A, A, A, A, hp) == B.AMSP_ENULL
+    assert _status(B.amsp_adamw_step_shard, [A], None, 8, A, A + 2, A, A, hp) == B.AMSP_EALIGN
+    assert _status(B.amsp_adamw_step_shard, [A], None, 8, A, A, A, A + 1, hp) == B.AMSP_EALIGN
+    for bad in (dict(step=0), dict(lr=float("inf")), dict(beta1=1.0), dict(beta2=-0.1), dict(eps=-1e-8),
+                dict(weight_decay=float("nan")), dict(max_norm=float("nan")), dict(grad_scale=float("inf"))):
+        assert _status(B.amsp_adamw_step_shard, [A], None, 8, A, A, A, A,
+                       B.AdamWHparams(**dict(HP, **bad))) == B.AMSP_EINVAL
+    B.amsp_adamw_step_shard([A], None, 0, 0, 0, 0, 0, hp, stream=0)      # n == 0
+
+
+def test_product_package_never_imports_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2311_00257_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".c", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in text and "from oracle" not in text and "amsp_oracle" not in text, f

@@ -1,0 +1,353 @@
+"""GPU parity: every C-ABI entry point against the CPU oracle, element by element, on the
+same seeded inputs.  Sizes span several 2048-element block tiles plus ragged heads and
+tails; offsets shift the 16-byte phase of the streams."""
+import numpy as np
+import pytest
+
+import helpers as H
+import oracle
+from paper_2311_00257_amd import synth, workloads
+
+pytestmark = pytest.mark.gpu
+
+SIZES = [1, 7, 8, 9, 15, 16, 17, 63, 64, 65, 2047, 2048, 2049, 5 * 2048 + 13, 100_003]
+
+
+@pytest.fixture(scope="module")
+def B():
+    import torch
+
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    from paper_2311_00257_amd import binding
+
+    binding.load()
+    return binding
+
+
+@pytest.fixture(scope="module")
+def torch_mod():
+    import torch
+
+    return torch
+
+
+def _sync():
+    import torch
+
+    torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------ input generator
+def test_device_generator_matches_host(torch_mod):
+    from paper_2311_00257_amd import synth_device
+
+    torch = torch_mod
+    w = workloads.get(1)
+    for index0 in (0, 12345, 2**33 + 5, 2**40 + 1):
+        n = 70_001
+        a = torch.empty(n, dtype=torch.float32, device="cuda")
+        synth_device.fill_f32(a, w.key(synth.TENSOR_MASTER), index0, w.sigma_param)
+        assert np.array_equal(a.cpu().numpy(), synth.fill_f32(w.key(synth.TENSOR_MASTER), index0, n, w.sigma_param))
+        synth_device.fill_f32(a, w.key(synth.TENSOR_EXP_AVG_SQ), index0, w.scale_v, absolute=True)
+        assert np.array_equal(a.cpu().numpy(),
+                              synth.fill_f32(w.key(synth.TENSOR_EXP_AVG_SQ), index0, n, w.scale_v, absolute=True))
+        g = torch.empty(n, dtype=torch.int16, device="cuda")
+        synth_device.fill_bf16(g, w.key(synth.TENSOR_PARTIAL0 + 3), index0, w.sigma_grad)
+        assert np.array_equal(H.dev_bits(g), synth.fill_bf16(w.key(synth.TENSOR_PARTIAL0 + 3), index0, n, w.sigma_grad))
+
+
+# ------------------------------------------------------------------ shard range
+def test_shard_range_matches_oracle(B):
+    rng = np.random.default_rng(11)
+    cases = [(w.total_elems, w.shard_factor, w.rank) for w in workloads.WORKLOADS]
+    cases += [(int(rng.integers(0, 2**45)), int(s), int(rng.integers(0, s))) for s in rng.integers(1, 5000, 200)]
+    cases += [(5, 8, r) for r in range(8)] + [(2**64 - 1, 7, 6), (2**64 - 1, 1, 0)]
+    for total, s, r in cases:
+        assert B.amsp_shard_range(total, s, r) == oracle.shard_range(total, s, r)
+
+
+# ------------------------------------------------------------------ cast
+def test_cast_exhaustive_patterns(B, torch_mod):
+    hi = np.arange(65536, dtype=np.uint32) << 16
+    lows = np.array([0x0000, 0x0001, 0x7FFF, 0x8000, 0x8001, 0xFFFF], dtype=np.uint32)
+    x = (hi[:, None] | lows[None, :]).reshape(-1).view(np.float32)
+    d = H.to_dev_f32(x)
+    out = torch_mod.zeros(x.size, dtype=torch_mod.int16, device="cuda")
+    B.amsp_cast_param_shard(d, out, x.size)
+    assert np.array_equal(H.dev_bits(out), oracle.cast(x))      # bit-exact, NaN payloads included
+
+
+@pytest.mark.parametrize("n", SIZES)
+@pytest.mark.parametrize("shift", [0, 1, 3, 4])
+def test_cast_sizes_and_phases(B, torch_mod, n, shift):
+    w = workloads.get(0)
+    x = synth.fill_f32(w.key(synth.TENSOR_MASTER), 1000, n, w.sigma_param)
+    d = H.to_dev_f32(x, pad_front=shift)                 # both streams shifted alike: common phase
+    guard = 16
+    out = torch_mod.full((shift + n + guard,), 0x5A5A, dtype=torch_mod.int16, device="cuda")
+    B.amsp_cast_param_shard(d, out[shift:], n)
+    got = H.dev_bits(out)
+    assert np.array_equal(got[shift:shift + n], oracle.cast(x))
+    assert np.all(got[:shift] == 0x5A5A) and np.all(got[shift + n:] == 0x5A5A)     # nothing outside the range
+
+
+def test_cast_streams_without_common_phase(B, torch_mod):
+    n = 10_000
+    x = synth.fill_f32(1, 0, n, 1.0)
+    d = H.to_dev_f32(x, pad_front=1)                     # fp32 stream 4 bytes off, bf16 stream aligned
+    out = torch_mod.zeros(n, dtype=torch_mod.int16, device="cuda")
+    B.amsp_cast_param_shard(d, out, n)
+    assert np.array_equal(H.dev_bits(out), oracle.cast(x))
+
+
+# ------------------------------------------------------------------ reduce
+@pytest.mark.parametrize("k", [1, 2, 3, 4, 5, 8, 16, 32])
+def test_reduce_against_oracle(B, torch_mod, k):
+    w = workloads.get(3)
+    for n, shift in ((100_003, 0), (4099, 5), (9, 2)):
+        inp = H.host_inputs(w, 777, n, k=k)
+        dparts = [H.to_dev_bf16(p, pad_front=shift) for p in inp.partials]
+        out = torch_mod.zeros(shift + n, dtype=torch_mod.float32, device="cuda")[shift:]
+        B.amsp_reduce_grad_shard(dparts, n, out)
+        got = out.cpu().numpy().astype(np.float64)
+        G = oracle.reduce(inp.partials)
+        sum_abs = sum(np.abs(synth.bf16_bits_to_f32(p).astype(np.float64)) for p in inp.partials)
+        # sequential fp32 sum: at most (k-1) roundings of 2^-24 relative to the running magnitude
+        assert np.all(np.abs(got - G) <= (k - 1) * 2.0 ** -24 * sum_abs)
+        if k == 1:
+            assert np.array_equal(got, G)
+
+
+def test_reduce_identical_partials_and_accumulate(B, torch_mod):
+    w = workloads.get(0)
+    n = 30_011
+    g = synth.fill_bf16(w.key(16), 0, n, w.sigma_grad)
+    d = H.to_dev_bf16(g)
+    out = torch_mod.zeros(n, dtype=torch_mod.float32, device="cuda")
+    for k in (2, 4, 8, 16):
+        B.amsp_reduce_grad_shard([d] * k, n, out)
+        assert np.array_equal(out.cpu().numpy().astype(np.float64), oracle.reduce([g] * k))   # k g exactly
+    # accumulate: two micro-batches
+    B.amsp_reduce_grad_shard([d, d], n, out, accumulate=False)
+    B.amsp_reduce_grad_shard([d, d], n, out, accumulate=True)
+    assert np.array_equal(out.cpu().numpy().astype(np.float64), oracle.reduce([g] * 4))
+    # bucketed launches give the same bits as one launch
+    ref = out.clone()
+    out.zero_()
+    B.amsp_reduce_grad_shard([d] * 4, n, out, bucket_elems=4097)
+    assert torch_mod.equal(out, ref)
+
+
+# ------------------------------------------------------------------ squared norm
+@pytest.mark.parametrize("k", [1, 2, 3, 8, 16])
+def test_sqnorm_against_oracle(B, torch_mod, k):
+    w = workloads.get(3)
+    ws = torch_mod.empty(B.amsp_workspace_bytes() // 8, dtype=torch_mod.float64, device="cuda")
+    d_s = torch_mod.full((1,), 123.0, dtype=torch_mod.float64, device="cuda")
+    for n, shift in ((1_000_003, 0), (2048 * 3 + 5, 3), (5, 0)):
+        inp = H.host_inputs(w, 31, n, k=k)
+        dparts = [H.to_dev_bf16(p, pad_front=shift) for p in inp.partials]
+        B.amsp_grad_sqnorm(dparts, None, n, d_s, ws)
+        S = oracle.sqnorm(oracle.reduce(inp.partials))
+        got = float(d_s.item())
+        assert abs(got - S) <= H.REL_TOL * S
+        # run-to-run determinism: no atomics, fixed order
+        for _ in range(3):
+            B.amsp_grad_sqnorm(dparts, None, n, d_s, ws)
+            assert float(d_s.item()) == got
+        # accumulate adds to what is there; bucketed launches accumulate in bucket order
+        B.amsp_grad_sqnorm(dparts, None, n, d_s, ws, accumulate=True)
+        assert float(d_s.item()) == pytest.approx(2 * got, rel=1e-14)
+        B.amsp_grad_sqnorm(dparts, None, n, d_s, ws, bucket_elems=max(1, n // 7 + 1))
+        assert float(d_s.item()) == pytest.approx(got, rel=1e-12)
+        # norm of the fp32 gradient buffer (k == 0 form) equals the norm of the partials
+        g32 = torch_mod.empty(n, dtype=torch_mod.float32, device="cuda")
+        B.amsp_reduce_grad_shard(dparts, n, g32)
+        B.amsp_grad_sqnorm(None, g32, n, d_s, ws)
+        assert float(d_s.item()) == pytest.approx(got, rel=1e-12)
+
+
+def test_sqnorm_constant_and_empty(B, torch_mod):
+    ws = torch_mod.empty(B.amsp_workspace_bytes() // 8, dtype=torch_mod.float64, device="cuda")
+    d_s = torch_mod.full((1,), 7.0, dtype=torch_mod.float64, device="cuda")
+    n, k, c = 50_000, 8, 0.375
+    d = H.to_dev_bf16(np.full(n, oracle.bf16_rne(c), dtype=np.uint16))
+    B.amsp_grad_sqnorm([d] * k, None, n, d_s, ws)
+    assert float(d_s.item()) == n * (k * c) ** 2
+    B.amsp_grad_sqnorm([d] * k, None, 0, d_s, ws, accumulate=True)
+    assert float(d_s.item()) == n * (k * c) ** 2            # empty range, accumulate: untouched
+    B.amsp_grad_sqnorm([d] * k, None, 0, d_s, ws)
+    assert float(d_s.item()) == 0.0                         # empty range, overwrite: zero
+
+
+# ------------------------------------------------------------------ fused AdamW step
+def _run_step(B, torch, w, inp, n, hp, shift=0, bucket_elems=0, fused=True, with_bf16=True):
+    """Norm pass then update on the device; returns host copies of p, m, v, bf16, sqnorm."""
+    dparts = [H.to_dev_bf16(p, pad_front=shift) for p in inp.partials]
+    dp, dm, dv = (H.to_dev_f32(x, pad_front=shift) for x in (inp.p, inp.m, inp.v))
+    out = torch.full((shift + n,), 0x5A5A, dtype=torch.int16, device="cuda")[shift:] if with_bf16 else None
+    ws = torch.empty(B.amsp_workspace_bytes() // 8, dtype=torch.float64, device="cuda")
+    d_s = torch.zeros(1, dtype=torch.float64, device="cuda")
+    B.amsp_grad_sqnorm(dparts, None, n, d_s, ws, bucket_elems=bucket_elems)
+    hpar = B.AdamWHparams(d_total_sqnorm=d_s, **hp)
+    if fused:
+        B.amsp_adamw_step_shard(dparts, None, n, dp, dm, dv, out, hpar, bucket_elems=bucket_elems)
+    else:
+        g32 = torch.empty(n, dtype=torch.float32, device="cuda")
+        B.amsp_reduce_grad_shard(dparts, n, g32)
+        B.amsp_adamw_step_shard(None, g32, n, dp, dm, dv, None, hpar)
+        if with_bf16:
+            B.amsp_cast_param_shard(dp, out, n)
+    _sync()
+    return (dp.cpu().numpy(), dm.cpu().numpy(), dv.cpu().numpy(),
+            H.dev_bits(out) if with_bf16 else None, float(d_s.item()))
+
+
+def _oracle_step(inp, hp):
+    return oracle.step(inp.partials, inp.p, inp.m, inp.v, threads=4, **hp)
+
+
+def _check_all(got, ref, inp, hp):
+    p, m, v, bits, S = got
+    assert abs(S - ref["sqnorm"]) <= H.REL_TOL * ref["sqnorm"]
+    stats = H.check_state(p, m, v, ref, inp.p, inp.m, hp)
+    if bits is not None:
+        stats["bf16_boundary_mismatches"] = H.check_bf16(bits, ref)
+        assert np.array_equal(bits, oracle.cast(p))        # the cast of the GPU's own fp32 is bit-exact
+        assert stats["bf16_boundary_mismatches"] <= max(3, 1e-4 * p.size)
+    return stats
+
+
+def test_workload0_full_step(B, torch_mod):
+    """Workload 0 whole: 2,094,336 elements, k = 2, clipping active (norm ~ 2.05 > 1)."""
+    w = workloads.get(0)
+    b, e = B.amsp_shard_range(w.total_elems, w.shard_factor, w.rank)
+    n = e - b
+    inp = H.host_inputs(w, b, n)
+    hp = H.hparams_of(w)
+    ref = _oracle_step(inp, hp)
+    assert ref["scale"] < 1.0
+    got = _run_step(B, torch_mod, w, inp, n, hp)
+    stats = _check_all(got, ref, inp, hp)
+    print("workload 0:", stats)
+    # unfused pieces (reduce -> AdamW on fp32 g -> cast) give the same bits as the fused pass
+    got2 = _run_step(B, torch_mod, w, inp, n, hp, fused=False)
+    for a, b_ in zip(got[:4], got2[:4]):
+        assert np.array_equal(a, b_)
+
+
+@pytest.mark.parametrize("cfg,k", [(1, 8), (3, 16), (4, 8), (2, 1), (0, 3), (0, 5), (3, 32)])
+def test_step_slices_of_each_workload(B, torch_mod, cfg, k):
+    """A slice of each workload at its k, ragged length, pointers shifted off 16 bytes."""
+    w = workloads.get(cfg)
+    b, _ = B.amsp_shard_range(w.total_elems, w.shard_factor, w.rank)
+    n = 300_007
+    inp = H.host_inputs(w, b + 1_000_001, n, k=k)
+    # the slice's own norm decides the scale; pick the threshold so that clipping is active
+    hp = H.hparams_of(w, max_norm=0.05 if cfg != 3 else 1.0)
+    ref = _oracle_step(inp, hp)
+    assert ref["scale"] < 1.0
+    for shift in (0, 3):
+        got = _run_step(B, torch_mod, w, inp, n, hp, shift=shift)
+        _check_all(got, ref, inp, hp)
+
+
+def test_step_without_clipping_scale_is_one(B, torch_mod):
+    w = workloads.get(0)
+    n = 65_537
+    inp = H.host_inputs(w, 0, n)
+    for max_norm in (1e9, 0.0):
+        hp = H.hparams_of(w, max_norm=max_norm)
+        ref = _oracle_step(inp, hp)
+        assert ref["scale"] == 1.0
+        _check_all(_run_step(B, torch_mod, w, inp, n, hp), ref, inp, hp)
+
+
+def test_step_bucketed_odd_buckets(B, torch_mod):
+    """Workload 4's structure in small: odd bucket length, ragged total, so every bucket after
+    the first starts at an odd element (2-byte-aligned bf16, 4-byte-aligned fp32)."""
+    w = workloads.get(4)
+    n = 1_000_000 - 3
+    inp = H.host_inputs(w, 20_330_589_760, n)
+    hp = H.hparams_of(w, max_norm=0.05)
+    ref = _oracle_step(inp, hp)
+    one = _run_step(B, torch_mod, w, inp, n, hp)
+    bucketed = _run_step(B, torch_mod, w, inp, n, hp, bucket_elems=25_001)
+    _check_all(bucketed, ref, inp, hp)
+    if abs(one[4] - bucketed[4]) == 0.0:                  # same norm bits -> same scale -> same update bits
+        for a, b_ in zip(one[:4], bucketed[:4]):
+            assert np.array_equal(a, b_)
+
+
+def test_step_mixed_phases_falls_back_elementwise(B, torch_mod):
+    """Streams with no common 16-byte phase take the element-wise path: same results."""
+    torch = torch_mod
+    w = workloads.get(0)
+    n = 20_001
+    inp = H.host_inputs(w, 5, n)
+    hp = H.hparams_of(w, max_norm=0.05)
+    ref = _oracle_step(inp, hp)
+    dparts = [H.to_dev_bf16(p, pad_front=j) for j, p in enumerate(inp.partials)]     # different phases
+    dp, dm, dv = H.to_dev_f32(inp.p, 1), H.to_dev_f32(inp.m, 2), H.to_dev_f32(inp.v, 0)
+    out = torch.zeros(n + 3, dtype=torch.int16, device="cuda")[3:]
+    ws = torch.empty(B.amsp_workspace_bytes() // 8, dtype=torch.float64, device="cuda")
+    d_s = torch.zeros(1, dtype=torch.float64, device="cuda")
+    B.amsp_grad_sqnorm(dparts, None, n, d_s, ws)
+    B.amsp_adamw_step_shard(dparts, None, n, dp, dm, dv, out, B.AdamWHparams(d_total_sqnorm=d_s, **hp))
+    got = (dp.cpu().numpy(), dm.cpu().numpy(), dv.cpu().numpy(), H.dev_bits(out), float(d_s.item()))
+    _check_all(got, ref, inp, hp)
+
+
+def test_step_closed_forms_on_device(B, torch_mod):
+    torch = torch_mod
+    w = workloads.get(0)
+    n = 40_003
+    inp = H.host_inputs(w, 0, n)
+    dparts = [H.to_dev_bf16(p) for p in inp.partials]
+    # lr = 0: parameters bit-identical, moments still advance
+    dp, dm, dv = H.to_dev_f32(inp.p), H.to_dev_f32(inp.m), H.to_dev_f32(inp.v)
+    hp = H.hparams_of(w, lr=0.0, max_norm=0.0)
+    B.amsp_adamw_step_shard(dparts, None, n, dp, dm, dv, None, B.AdamWHparams(**hp))
+    assert np.array_equal(dp.cpu().numpy(), inp.p)
+    assert not np.array_equal(dm.cpu().numpy(), inp.m)
+    # first step from m = v = 0 without decay: |update| = lr |g| / (|g| + eps)
+    z = np.zeros(n, dtype=np.float32)
+    dp, dm, dv = H.to_dev_f32(inp.p), H.to_dev_f32(z), H.to_dev_f32(z)
+    hp = H.hparams_of(w, weight_decay=0.0, step=1, max_norm=0.0)
+    B.amsp_adamw_step_shard(dparts, None, n, dp, dm, dv, None, B.AdamWHparams(**hp))
+    G = oracle.reduce(inp.partials)
+    lr, eps = float(np.float32(w.lr)), float(np.float32(w.eps))
+    want = inp.p.astype(np.float64) - lr * G / (np.abs(G) + eps)
+    err = np.abs(dp.cpu().numpy() - want) / np.maximum(np.abs(inp.p), lr)
+    assert err.max() <= H.REL_TOL
+    # grad_scale without a norm pointer scales the gradient (here: the mean over k partials)
+    dp, dm, dv = H.to_dev_f32(inp.p), H.to_dev_f32(inp.m), H.to_dev_f32(inp.v)
+    hp = H.hparams_of(w, max_norm=0.0)
+    B.amsp_adamw_step_shard(dparts, None, n, dp, dm, dv, None, B.AdamWHparams(grad_scale=0.5, **hp))
+    p1, m1, v1 = oracle.adamw(G, 0.5, inp.p, inp.m, inp.v, **{k_: v_ for k_, v_ in hp.items()
+                                                               if k_ not in ("max_norm", "clip_eps")})
+    ref = dict(p=p1, m=m1, v=v1, G=G, scale=0.5)
+    H.check_state(dp.cpu().numpy(), dm.cpu().numpy(), dv.cpu().numpy(), ref, inp.p, inp.m, hp)
+
+
+def test_error_paths_enqueue_nothing(B, torch_mod):
+    torch = torch_mod
+    n = 1000
+    p = torch.ones(n, dtype=torch.float32, device="cuda")
+    m = torch.zeros(n, dtype=torch.float32, device="cuda")
+    v = torch.zeros(n, dtype=torch.float32, device="cuda")
+    g = torch.zeros(n, dtype=torch.int16, device="cuda")
+    hp = dict(lr=1e-3, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.0, step=1)
+    for bad, code in ((dict(step=0), B.AMSP_EINVAL), (dict(lr=float("nan")), B.AMSP_EINVAL),
+                      (dict(beta1=1.0), B.AMSP_EINVAL), (dict(eps=-1.0), B.AMSP_EINVAL)):
+        with pytest.raises(B.AmspError) as ei:
+            B.amsp_adamw_step_shard([g], None, n, p, m, v, None, B.AdamWHparams(**dict(hp, **bad)))
+        assert ei.value.status == code
+    with pytest.raises(B.AmspError) as ei:
+        B.amsp_adamw_step_shard([g] * 33, None, n, p, m, v, None, B.AdamWHparams(**hp))
+    assert ei.value.status == B.AMSP_EINVAL
+    with pytest.raises(B.AmspError) as ei:
+        B.amsp_adamw_step_shard([g], None, n, p, None, v, None, B.AdamWHparams(**hp))
+    assert ei.value.status == B.AMSP_ENULL
+    _sync()
+    assert torch.all(p == 1.0) and torch.all(m == 0.0)
