@@ -1,0 +1,175 @@
+#!/usr/bin/env python3
+"""Benchmark of the per-GPU model-state step on one MI355X.
+
+A step is one pass of the whole path over one rank's shard, inputs resident in HBM:
+    amsp_grad_sqnorm (k bf16 partials -> squared norm)           2k   bytes/element
+    amsp_adamw_step_shard (reduce + clip + AdamW + bf16 cast)    2k+26 bytes/element
+Default workload: LLaMA-7B at shard factor 8, rank 3, k = 8 (842,301,952 elements).
+Prints ONE JSON line: throughput in elements/s, the HBM roofline of the fused kernel from
+HIP-event timing of that kernel alone, and the CPU oracle timed on a bounded slice.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=1, help="workload id 0..4 (default 1: LLaMA-7B, factor 8)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-elems", type=int, default=64 * 1024 * 1024)
+    ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "hbm_traffic.json"),
+                    help="per-launch HBM bytes of the fused kernel measured with rocprofv3 --pmc")
+    return ap.parse_args()
+
+
+def cpu_baseline(w, begin, sample):
+    """The oracle as it stands, timed on the host cores over a slice of the same workload."""
+    import oracle
+    from paper_2311_00257_amd import synth
+
+    cores = min(len(os.sched_getaffinity(0)), 16)
+    parts = [synth.fill_bf16(w.key(synth.TENSOR_PARTIAL0 + j), begin, sample, w.sigma_grad, threads=cores)
+             for j in range(w.k)]
+    p = synth.fill_f32(w.key(synth.TENSOR_MASTER), begin, sample, w.sigma_param, threads=cores)
+    m = synth.fill_f32(w.key(synth.TENSOR_EXP_AVG), begin, sample, w.sigma_m, threads=cores)
+    v = synth.fill_f32(w.key(synth.TENSOR_EXP_AVG_SQ), begin, sample, w.scale_v, absolute=True, threads=cores)
+    hp = dict(lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps, weight_decay=w.weight_decay, step=w.step,
+              max_norm=w.max_norm, clip_eps=w.clip_eps)
+    res = {}
+    for label, th in (("all", cores), ("one", 1)):
+        n_run = sample if th > 1 else max(1, sample // 8)
+        t0 = time.perf_counter()
+        oracle.step([q[:n_run] for q in parts], p[:n_run], m[:n_run], v[:n_run], threads=th, **hp)
+        res[label] = n_run / (time.perf_counter() - t0)
+    return {"value": res["all"], "unit": "elements/s", "cores": cores, "kind": "oracle",
+            "sample": "first %d elements of the %s shard, whole step (reduce, norm, clip, AdamW, cast) in fp64; "
+                      "one contiguous chunk per thread" % (sample, w.name),
+            "single_thread_value": res["one"]}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding across GPUs); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    from paper_2311_00257_amd import binding as B
+    from paper_2311_00257_amd import synth, synth_device, workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    B.load()
+    torch.cuda.set_device(0)
+    w = workloads.get(args.config)
+    begin, end = B.amsp_shard_range(w.total_elems, w.shard_factor, w.rank)
+    n = end - begin - w.drop_tail
+    k = w.k
+
+    # ---- inputs resident in HBM before the timed region
+    parts = []
+    for j in range(k):
+        t = torch.empty(n, dtype=torch.int16, device="cuda")
+        synth_device.fill_bf16(t, w.key(synth.TENSOR_PARTIAL0 + j), begin, w.sigma_grad)
+        parts.append(t)
+    master = torch.empty(n, dtype=torch.float32, device="cuda")
+    exp_avg = torch.empty(n, dtype=torch.float32, device="cuda")
+    exp_avg_sq = torch.empty(n, dtype=torch.float32, device="cuda")
+    synth_device.fill_f32(master, w.key(synth.TENSOR_MASTER), begin, w.sigma_param)
+    synth_device.fill_f32(exp_avg, w.key(synth.TENSOR_EXP_AVG), begin, w.sigma_m)
+    synth_device.fill_f32(exp_avg_sq, w.key(synth.TENSOR_EXP_AVG_SQ), begin, w.scale_v, absolute=True)
+    param_bf16 = torch.empty(n, dtype=torch.int16, device="cuda")
+    workspace = torch.empty(B.amsp_workspace_bytes() // 8, dtype=torch.float64, device="cuda")
+    d_sqnorm = torch.zeros(1, dtype=torch.float64, device="cuda")
+    torch.cuda.synchronize()
+
+    def step(t, ev=None):
+        hp = B.AdamWHparams(lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps, weight_decay=w.weight_decay,
+                            step=t, max_norm=w.max_norm, clip_eps=w.clip_eps, d_total_sqnorm=d_sqnorm)
+        if ev:
+            ev[0].record()
+        B.amsp_grad_sqnorm(parts, None, n, d_sqnorm, workspace, bucket_elems=w.bucket_elems)
+        if ev:
+            ev[1].record()
+        B.amsp_adamw_step_shard(parts, None, n, master, exp_avg, exp_avg_sq, param_bf16, hp,
+                                bucket_elems=w.bucket_elems)
+        if ev:
+            ev[2].record()
+
+    for i in range(args.warmup):
+        step(w.step + i)
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly --steps steps, HIP events on the launch stream around each kernel
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(w.step + args.warmup + i, events[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    ms_per_step = wall * 1e3 / args.steps
+    norm_ms = sum(e[0].elapsed_time(e[1]) for e in events) / args.steps
+    fused_ms = sum(e[1].elapsed_time(e[2]) for e in events) / args.steps
+    launches = 1 if not w.bucket_elems else -(-n // w.bucket_elems)
+    fused_bytes = w.bytes_per_elem_fused() * n
+    achieved = fused_bytes / (fused_ms * 1e-3) / 1e9
+
+    traffic = None
+    try:
+        with open(args.traffic_json) as f:
+            tj = json.load(f)
+        if tj.get("workload") == w.name:
+            traffic = tj.get("bytes_per_launch")
+    except (OSError, ValueError):
+        pass
+
+    out = {
+        "metric": "model-state elements updated/s per GPU (norm pass + fused reduce/AdamW/bf16-cast step)",
+        "value": n / (ms_per_step * 1e-3),
+        "unit": "elements/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": w.name, "elements": n, "k": k, "shard_factor": w.shard_factor, "rank": w.rank,
+                   "bucket_elems": w.bucket_elems, "launches_per_pass": launches},
+        "roofline": {"bound": "hbm", "kernel": "adamw_kernel<k=%d,bf16 out> (amsp_adamw_step_shard)" % k,
+                     "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
+                     "bytes_per_element": w.bytes_per_elem_fused(), "kernel_ms": fused_ms / launches,
+                     "launches": launches},
+        "norm_pass": {"ms": norm_ms, "GB/s": w.bytes_per_elem_norm() * n / (norm_ms * 1e-3) / 1e9,
+                      "bytes_per_element": w.bytes_per_elem_norm()},
+        "whole_step_GBps": (w.bytes_per_elem_fused() + w.bytes_per_elem_norm()) * n / (ms_per_step * 1e-3) / 1e9,
+    }
+    if not args.no_cpu_baseline:
+        del parts, master, exp_avg, exp_avg_sq, param_bf16
+        out["cpu_baseline"] = cpu_baseline(w, begin, min(args.cpu_sample_elems, n))
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -60,6 +60,11 @@ def load() -> ctypes.CDLL:
         if not os.path.exists(_build.LIB_AMSP):
             raise RuntimeError("libamsp.so is not built: run `python -m paper_2311_00257_amd.build` "
                                "(there is no CPU fallback)")
+        # torch supplies the device memory these kernels touch, so the library must bind to the
+        # HIP runtime torch has loaded: importing torch first makes the dynamic linker reuse it
+        # (two HIP runtimes in one process do not see each other's device state).
+        import torch  # noqa: F401
+
         lib = ctypes.CDLL(_build.LIB_AMSP)
         u64, u32, vp, ci = ctypes.c_uint64, ctypes.c_uint32, ctypes.c_void_p, ctypes.c_int
         lib.amsp_status_string.argtypes = [ci]

@@ -2,20 +2,30 @@
 // reduction, squared gradient norm, fused AdamW on fp32 master/m/v, bf16 parameter cast.
 //
 // Everything here is an HBM stream with a handful of fp32 operations per element, so the
-// design is about memory traffic only: every lane moves 8 consecutive elements per stream
-// per iteration (one 128-bit access per bf16 stream, two per fp32 stream), a wave covers
-// 1 KiB (bf16) / 2 KiB (fp32) of contiguous memory per access, blocks walk the range with a
-// grid stride, and nothing is staged through LDS except the block-level sum of the norm.
-// No matrix cores: there is no contraction on this path.
+// design is about memory traffic only.  What measurement on MI355X settled:
+//   - Every access of a wave is one fully contiguous piece: in the kernels that write, a lane
+//     owns 4 consecutive elements per stream (8-byte bf16 and 16-byte fp32 accesses, so a wave
+//     instruction covers 512 B or 1 KiB without gaps).  Letting a lane own 8 elements makes
+//     its fp32 accesses two 16-byte pieces 32 bytes apart and costs 10-20 % of bandwidth.
+//   - Kernels that read AND write run one vector per lane on a grid that covers the whole
+//     range ("full grid"): the hardware dispatcher then hands out the range in address order
+//     and balances the CUs.  The same kernels as persistent grid-stride loops reach ~4.5 TB/s
+//     instead of ~5.8 TB/s on the k = 8 fused step.
+//   - The read-only norm pass keeps a fixed grid with a grid-stride loop (its per-block sums
+//     must land in a fixed-size workspace in a fixed order) and reads 16 bytes per lane.
+//   - Non-temporal hints on all loads and stores: nothing is reused.
+// Nothing is staged through LDS except the block-level sum of the norm.  No matrix cores:
+// there is no contraction on this path.
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
+#include <stdio.h>
 #include <stdlib.h>
 
 #include "amsp.h"
 
 #ifndef AMSP_NT_LOAD
-#define AMSP_NT_LOAD 1   // non-temporal hint on loads of streams that are read once
+#define AMSP_NT_LOAD 1   // non-temporal hint on loads
 #endif
 #ifndef AMSP_NT_STORE
 #define AMSP_NT_STORE 1  // non-temporal hint on stores
@@ -24,10 +34,12 @@
 namespace {
 
 constexpr int kThreads = 256;          // 4 waves of 64
-constexpr int kVec = 8;                // elements per lane per iteration
-constexpr int kMaxBlocks = 4096;       // upper bound on any grid here; sizes the norm workspace
-constexpr int kEdgeMax = 2 * (kVec - 1);
+constexpr int kVecRW = 4;              // elements per lane per stream in the kernels that write
+constexpr int kVecNorm = 8;            // elements per lane per stream in the norm pass
+constexpr int kNormBlocks = 2048;      // fixed grid of the norm pass; sizes its workspace
+constexpr uint64_t kMaxGrid = 1u << 30;
 
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
@@ -53,17 +65,24 @@ __device__ __forceinline__ void st_stream(T *p, T v) {
 #endif
 }
 
-__device__ __forceinline__ void ld8_f32(const float *base, uint64_t e, float (&x)[kVec]) {
+// VEC consecutive fp32 values as VEC/4 16-byte accesses.
+template <int VEC>
+__device__ __forceinline__ void ld_f32(const float *base, uint64_t e, float (&x)[VEC]) {
     const f32x4 *q = reinterpret_cast<const f32x4 *>(base + e);
-    f32x4 a = ld_stream(q), b = ld_stream(q + 1);
-    x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w;
-    x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+#pragma unroll
+    for (int h = 0; h < VEC / 4; ++h) {
+        f32x4 a = ld_stream(q + h);
+        x[4 * h] = a.x; x[4 * h + 1] = a.y; x[4 * h + 2] = a.z; x[4 * h + 3] = a.w;
+    }
 }
-__device__ __forceinline__ void st8_f32(float *base, uint64_t e, const float (&x)[kVec]) {
+template <int VEC>
+__device__ __forceinline__ void st_f32(float *base, uint64_t e, const float (&x)[VEC]) {
     f32x4 *q = reinterpret_cast<f32x4 *>(base + e);
-    f32x4 a = {x[0], x[1], x[2], x[3]}, b = {x[4], x[5], x[6], x[7]};
-    st_stream(q, a);
-    st_stream(q + 1, b);
+#pragma unroll
+    for (int h = 0; h < VEC / 4; ++h) {
+        f32x4 a = {x[4 * h], x[4 * h + 1], x[4 * h + 2], x[4 * h + 3]};
+        st_stream(q + h, a);
+    }
 }
 
 // bf16 -> fp32 is a 16-bit shift of the pattern (exact).
@@ -78,44 +97,55 @@ __device__ __forceinline__ uint32_t f32_to_bf16(float x) {
     uint32_t qnan = ((u >> 16) & 0x8000u) | 0x7FC0u;
     return (u & 0x7FFFFFFFu) > 0x7F800000u ? qnan : rounded;
 }
-__device__ __forceinline__ void st8_bf16(uint16_t *base, uint64_t e, const float (&x)[kVec]) {
-    u32x4 w;
-    w.x = f32_to_bf16(x[0]) | (f32_to_bf16(x[1]) << 16);
-    w.y = f32_to_bf16(x[2]) | (f32_to_bf16(x[3]) << 16);
-    w.z = f32_to_bf16(x[4]) | (f32_to_bf16(x[5]) << 16);
-    w.w = f32_to_bf16(x[6]) | (f32_to_bf16(x[7]) << 16);
-    st_stream(reinterpret_cast<u32x4 *>(base + e), w);
+
+// VEC consecutive bf16 values as one 8- or 16-byte access: VEC/2 packed words.
+template <int VEC> struct Bf16Words;
+template <> struct Bf16Words<4> { typedef u32x2 type; };
+template <> struct Bf16Words<8> { typedef u32x4 type; };
+
+template <int VEC>
+__device__ __forceinline__ void st_bf16(uint16_t *base, uint64_t e, const float (&x)[VEC]) {
+    typename Bf16Words<VEC>::type w;
+#pragma unroll
+    for (int c = 0; c < VEC / 2; ++c) w[c] = f32_to_bf16(x[2 * c]) | (f32_to_bf16(x[2 * c + 1]) << 16);
+    st_stream(reinterpret_cast<typename Bf16Words<VEC>::type *>(base + e), w);
 }
 
 // ---------------------------------------------------------------- the reduced gradient
 // K > 0: k == K known at compile time (all loads issued up front); K == -1: run-time k;
 // K == 0: the gradient is already reduced, read it as fp32.
 // The sum runs j = 0..k-1 in fp32 in every kernel, so all of them see the same bits.
-template <int K>
-__device__ __forceinline__ void grad8(const PartialPtrs &pp, int k, const float *gf32, uint64_t e,
-                                      float (&g)[kVec]) {
+template <int VEC, typename W>
+__device__ __forceinline__ void widen_first(const W &w, float (&g)[VEC]) {
+#pragma unroll
+    for (int c = 0; c < VEC / 2; ++c) { g[2 * c] = bf16_lo(w[c]); g[2 * c + 1] = bf16_hi(w[c]); }
+}
+template <int VEC, typename W>
+__device__ __forceinline__ void widen_add(const W &w, float (&g)[VEC]) {
+#pragma unroll
+    for (int c = 0; c < VEC / 2; ++c) { g[2 * c] += bf16_lo(w[c]); g[2 * c + 1] += bf16_hi(w[c]); }
+}
+
+template <int K, int VEC>
+__device__ __forceinline__ void grad_vec(const PartialPtrs &pp, int k, const float *gf32, uint64_t e,
+                                         float (&g)[VEC]) {
+    typedef typename Bf16Words<VEC>::type W;
     if constexpr (K == 0) {
-        ld8_f32(gf32, e, g);
+        ld_f32<VEC>(gf32, e, g);
     } else if constexpr (K > 0) {
-        u32x4 w[K];
+        W w[K];
 #pragma unroll
-        for (int j = 0; j < K; ++j) w[j] = ld_stream(reinterpret_cast<const u32x4 *>(pp.p[j] + e));
-        g[0] = bf16_lo(w[0].x); g[1] = bf16_hi(w[0].x); g[2] = bf16_lo(w[0].y); g[3] = bf16_hi(w[0].y);
-        g[4] = bf16_lo(w[0].z); g[5] = bf16_hi(w[0].z); g[6] = bf16_lo(w[0].w); g[7] = bf16_hi(w[0].w);
+        for (int j = 0; j < K; ++j) w[j] = ld_stream(reinterpret_cast<const W *>(pp.p[j] + e));
+        widen_first<VEC>(w[0], g);
 #pragma unroll
-        for (int j = 1; j < K; ++j) {
-            g[0] += bf16_lo(w[j].x); g[1] += bf16_hi(w[j].x); g[2] += bf16_lo(w[j].y); g[3] += bf16_hi(w[j].y);
-            g[4] += bf16_lo(w[j].z); g[5] += bf16_hi(w[j].z); g[6] += bf16_lo(w[j].w); g[7] += bf16_hi(w[j].w);
-        }
+        for (int j = 1; j < K; ++j) widen_add<VEC>(w[j], g);
     } else {
-        u32x4 w = ld_stream(reinterpret_cast<const u32x4 *>(pp.p[0] + e));
-        g[0] = bf16_lo(w.x); g[1] = bf16_hi(w.x); g[2] = bf16_lo(w.y); g[3] = bf16_hi(w.y);
-        g[4] = bf16_lo(w.z); g[5] = bf16_hi(w.z); g[6] = bf16_lo(w.w); g[7] = bf16_hi(w.w);
+        W w = ld_stream(reinterpret_cast<const W *>(pp.p[0] + e));
+        widen_first<VEC>(w, g);
 #pragma unroll 4
         for (int j = 1; j < k; ++j) {
-            w = ld_stream(reinterpret_cast<const u32x4 *>(pp.p[j] + e));
-            g[0] += bf16_lo(w.x); g[1] += bf16_hi(w.x); g[2] += bf16_lo(w.y); g[3] += bf16_hi(w.y);
-            g[4] += bf16_lo(w.z); g[5] += bf16_hi(w.z); g[6] += bf16_lo(w.w); g[7] += bf16_hi(w.w);
+            w = ld_stream(reinterpret_cast<const W *>(pp.p[j] + e));
+            widen_add<VEC>(w, g);
         }
     }
 }
@@ -133,11 +163,11 @@ __device__ __forceinline__ float grad1(const PartialPtrs &pp, int k, const float
     }
 }
 
-// A launch covers n elements: `head` leading ones (0..7) up to the common 16-byte phase of
-// all streams, nvec groups of 8 taken with 128-bit accesses, and a tail of < 8.  Head and
-// tail (at most 14 elements) are the "edge", done element-wise by block 0.  When the
-// streams have no common phase the host sets nvec = 0 and vectorised = 0 and every element
-// goes through the element-wise loop.
+// A launch covers n elements: `head` leading ones (< VEC) up to the element at which every
+// stream reaches the alignment its vector access needs, nvec groups of VEC taken with vector
+// accesses, and a tail of < VEC.  Head and tail are the "edge", done element-wise by the first
+// lanes of block 0.  When the streams have no common phase the host sets vectorised = 0 and
+// every element goes through the element-wise loop.
 struct Span {
     uint64_t n;
     uint64_t nvec;
@@ -145,31 +175,33 @@ struct Span {
     uint32_t vectorised;
 };
 
+template <int VEC>
 __device__ __forceinline__ bool edge_index(const Span &s, uint32_t t, uint64_t &i) {
-    // t-th edge element -> element index
     if (t < s.head) { i = t; return true; }
-    uint64_t j = (uint64_t)s.head + s.nvec * kVec + (t - s.head);
+    uint64_t j = (uint64_t)s.head + s.nvec * VEC + (t - s.head);
     if (j < s.n) { i = j; return true; }
     return false;
 }
 
+__device__ __forceinline__ uint64_t global_thread() { return (uint64_t)blockIdx.x * kThreads + threadIdx.x; }
+__device__ __forceinline__ uint64_t grid_threads() { return (uint64_t)gridDim.x * kThreads; }
+
 // ---------------------------------------------------------------- step 4: cast
 __global__ void __launch_bounds__(kThreads) cast_kernel(const float *__restrict__ master,
                                                         uint16_t *__restrict__ out, Span s) {
-    const uint64_t stride = (uint64_t)gridDim.x * kThreads;
+    constexpr int VEC = kVecRW;
     if (s.vectorised) {
-        for (uint64_t v = (uint64_t)blockIdx.x * kThreads + threadIdx.x; v < s.nvec; v += stride) {
-            const uint64_t e = s.head + v * kVec;
-            float x[kVec];
-            ld8_f32(master, e, x);
-            st8_bf16(out, e, x);
+        for (uint64_t v = global_thread(); v < s.nvec; v += grid_threads()) {
+            const uint64_t e = s.head + v * VEC;
+            float x[VEC];
+            ld_f32<VEC>(master, e, x);
+            st_bf16<VEC>(out, e, x);
         }
         uint64_t i;
-        if (blockIdx.x == 0 && threadIdx.x < kEdgeMax && edge_index(s, threadIdx.x, i))
+        if (blockIdx.x == 0 && threadIdx.x < 2 * (VEC - 1) && edge_index<VEC>(s, threadIdx.x, i))
             out[i] = (uint16_t)f32_to_bf16(master[i]);
     } else {
-        for (uint64_t i = (uint64_t)blockIdx.x * kThreads + threadIdx.x; i < s.n; i += stride)
-            out[i] = (uint16_t)f32_to_bf16(master[i]);
+        for (uint64_t i = global_thread(); i < s.n; i += grid_threads()) out[i] = (uint16_t)f32_to_bf16(master[i]);
     }
 }
 
@@ -177,27 +209,27 @@ __global__ void __launch_bounds__(kThreads) cast_kernel(const float *__restrict_
 template <int K>
 __global__ void __launch_bounds__(kThreads) reduce_kernel(PartialPtrs pp, int k, float *__restrict__ out,
                                                           int accumulate, Span s) {
-    const uint64_t stride = (uint64_t)gridDim.x * kThreads;
+    constexpr int VEC = kVecRW;
     if (s.vectorised) {
-        for (uint64_t v = (uint64_t)blockIdx.x * kThreads + threadIdx.x; v < s.nvec; v += stride) {
-            const uint64_t e = s.head + v * kVec;
-            float g[kVec];
-            grad8<K>(pp, k, nullptr, e, g);
+        for (uint64_t v = global_thread(); v < s.nvec; v += grid_threads()) {
+            const uint64_t e = s.head + v * VEC;
+            float g[VEC];
+            grad_vec<K, VEC>(pp, k, nullptr, e, g);
             if (accumulate) {
-                float o[kVec];
-                ld8_f32(out, e, o);
+                float o[VEC];
+                ld_f32<VEC>(out, e, o);
 #pragma unroll
-                for (int c = 0; c < kVec; ++c) g[c] = o[c] + g[c];
+                for (int c = 0; c < VEC; ++c) g[c] = o[c] + g[c];
             }
-            st8_f32(out, e, g);
+            st_f32<VEC>(out, e, g);
         }
         uint64_t i;
-        if (blockIdx.x == 0 && threadIdx.x < kEdgeMax && edge_index(s, threadIdx.x, i)) {
+        if (blockIdx.x == 0 && threadIdx.x < 2 * (VEC - 1) && edge_index<VEC>(s, threadIdx.x, i)) {
             float g = grad1<K>(pp, k, nullptr, i);
             out[i] = accumulate ? out[i] + g : g;
         }
     } else {
-        for (uint64_t i = (uint64_t)blockIdx.x * kThreads + threadIdx.x; i < s.n; i += stride) {
+        for (uint64_t i = global_thread(); i < s.n; i += grid_threads()) {
             float g = grad1<K>(pp, k, nullptr, i);
             out[i] = accumulate ? out[i] + g : g;
         }
@@ -215,25 +247,36 @@ __device__ __forceinline__ double wave_sum(double x) {
     return x;
 }
 
-template <int K>
+template <int K, int VEC, int UNROLL>
 __global__ void __launch_bounds__(kThreads) sqnorm_kernel(PartialPtrs pp, int k, const float *__restrict__ gf32,
                                                           double *__restrict__ block_sums, Span s) {
-    const uint64_t stride = (uint64_t)gridDim.x * kThreads;
     double acc = 0.0;
     if (s.vectorised) {
-        for (uint64_t v = (uint64_t)blockIdx.x * kThreads + threadIdx.x; v < s.nvec; v += stride) {
-            float g[kVec];
-            grad8<K>(pp, k, gf32, s.head + v * kVec, g);
+        const uint64_t stride = grid_threads();
+        for (uint64_t v0 = global_thread(); v0 < s.nvec; v0 += stride * UNROLL) {
+            float g[UNROLL][VEC];
 #pragma unroll
-            for (int c = 0; c < kVec; ++c) acc = fma((double)g[c], (double)g[c], acc);
+            for (int u = 0; u < UNROLL; ++u) {
+                const uint64_t v = v0 + u * stride;
+                if (v < s.nvec) {
+                    grad_vec<K, VEC>(pp, k, gf32, s.head + v * VEC, g[u]);
+                } else {
+#pragma unroll
+                    for (int c = 0; c < VEC; ++c) g[u][c] = 0.0f;
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u)
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) acc = fma((double)g[u][c], (double)g[u][c], acc);
         }
         uint64_t i;
-        if (blockIdx.x == 0 && threadIdx.x < kEdgeMax && edge_index(s, threadIdx.x, i)) {
+        if (blockIdx.x == 0 && threadIdx.x < 2 * (VEC - 1) && edge_index<VEC>(s, threadIdx.x, i)) {
             double g = (double)grad1<K>(pp, k, gf32, i);
             acc = fma(g, g, acc);
         }
     } else {
-        for (uint64_t i = (uint64_t)blockIdx.x * kThreads + threadIdx.x; i < s.n; i += stride) {
+        for (uint64_t i = global_thread(); i < s.n; i += grid_threads()) {
             double g = (double)grad1<K>(pp, k, gf32, i);
             acc = fma(g, g, acc);
         }
@@ -297,31 +340,31 @@ __global__ void __launch_bounds__(kThreads) adamw_kernel(PartialPtrs pp, int k, 
                                                          float *__restrict__ master, float *__restrict__ exp_avg,
                                                          float *__restrict__ exp_avg_sq, uint16_t *__restrict__ out,
                                                          AdamConsts c, Span s) {
-    const uint64_t stride = (uint64_t)gridDim.x * kThreads;
+    constexpr int VEC = kVecRW;
     const float scale = clip_scale(c);
     if (s.vectorised) {
-        for (uint64_t vi = (uint64_t)blockIdx.x * kThreads + threadIdx.x; vi < s.nvec; vi += stride) {
-            const uint64_t e = s.head + vi * kVec;
-            float g[kVec], p[kVec], m[kVec], v[kVec];
-            grad8<K>(pp, k, gf32, e, g);
-            ld8_f32(master, e, p);
-            ld8_f32(exp_avg, e, m);
-            ld8_f32(exp_avg_sq, e, v);
+        for (uint64_t vi = global_thread(); vi < s.nvec; vi += grid_threads()) {
+            const uint64_t e = s.head + vi * VEC;
+            float g[VEC], p[VEC], m[VEC], v[VEC];
+            grad_vec<K, VEC>(pp, k, gf32, e, g);
+            ld_f32<VEC>(master, e, p);
+            ld_f32<VEC>(exp_avg, e, m);
+            ld_f32<VEC>(exp_avg_sq, e, v);
 #pragma unroll
-            for (int q = 0; q < kVec; ++q) adamw1(c, scale, g[q], p[q], m[q], v[q]);
-            st8_f32(master, e, p);
-            st8_f32(exp_avg, e, m);
-            st8_f32(exp_avg_sq, e, v);
-            if constexpr (WRITE_BF16) st8_bf16(out, e, p);
+            for (int q = 0; q < VEC; ++q) adamw1(c, scale, g[q], p[q], m[q], v[q]);
+            st_f32<VEC>(master, e, p);
+            st_f32<VEC>(exp_avg, e, m);
+            st_f32<VEC>(exp_avg_sq, e, v);
+            if constexpr (WRITE_BF16) st_bf16<VEC>(out, e, p);
         }
     }
     const bool edge = s.vectorised != 0;
     if (edge && blockIdx.x != 0) return;
-    const uint64_t first = edge ? threadIdx.x : (uint64_t)blockIdx.x * kThreads + threadIdx.x;
-    const uint64_t count = edge ? kEdgeMax : s.n;
-    for (uint64_t t = first; t < count; t += edge ? (uint64_t)kThreads : stride) {
+    const uint64_t first = edge ? threadIdx.x : global_thread();
+    const uint64_t count = edge ? 2 * (VEC - 1) : s.n;
+    for (uint64_t t = first; t < count; t += edge ? (uint64_t)kThreads : grid_threads()) {
         uint64_t i = t;
-        if (edge && !edge_index(s, (uint32_t)t, i)) continue;
+        if (edge && !edge_index<VEC>(s, (uint32_t)t, i)) continue;
         float p = master[i], m = exp_avg[i], v = exp_avg_sq[i];
         adamw1(c, scale, grad1<K>(pp, k, gf32, i), p, m, v);
         master[i] = p;
@@ -337,54 +380,45 @@ struct Stream16 {
     uint32_t elem;   // bytes per element: 2 or 4
 };
 
-// Smallest head in 0..7 at which every stream is 16-byte aligned, or -1.
-int common_head(const Stream16 *st, int ns) {
-    for (int h = 0; h < kVec; ++h) {
+// Smallest head in 0..vec-1 at which every stream is aligned for its vector access
+// (vec * elem bytes, at most 16), or -1.
+int common_head(const Stream16 *st, int ns, int vec) {
+    for (int h = 0; h < vec; ++h) {
         bool ok = true;
-        for (int i = 0; i < ns && ok; ++i) ok = ((reinterpret_cast<uintptr_t>(st[i].ptr) + (uintptr_t)h * st[i].elem) & 15u) == 0;
+        for (int i = 0; i < ns && ok; ++i) {
+            uintptr_t need = (uintptr_t)vec * st[i].elem;
+            if (need > 16) need = 16;
+            ok = ((reinterpret_cast<uintptr_t>(st[i].ptr) + (uintptr_t)h * st[i].elem) & (need - 1)) == 0;
+        }
         if (ok) return h;
     }
     return -1;
 }
 
-Span make_span(uint64_t n, const Stream16 *st, int ns) {
+Span make_span(uint64_t n, const Stream16 *st, int ns, int vec) {
     Span s{n, 0, 0, 0};
-    int h = common_head(st, ns);
-    if (h >= 0 && n >= (uint64_t)h + kVec) {
+    int h = common_head(st, ns, vec);
+    if (h >= 0 && n >= (uint64_t)h + vec) {
         s.head = (uint32_t)h;
-        s.nvec = (n - (uint64_t)h) / kVec;
+        s.nvec = (n - (uint64_t)h) / vec;
         s.vectorised = 1;
     }
     return s;
 }
 
-int blocks_per_cu() {
-    static int v = [] {
-        const char *e = getenv("AMSP_BLOCKS_PER_CU");
-        int x = e ? atoi(e) : 0;
-        return (x >= 1 && x <= 16) ? x : 8;
-    }();
-    return v;
-}
-
-int cu_count() {
-    static int cached[64] = {0};
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
-    if (cached[dev] == 0) {
-        int n = 0;
-        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
-        cached[dev] = n;
-    }
-    return cached[dev];
-}
-
-int grid_for(const Span &s) {
+// One lane per vector (or per element on the element-wise path), the whole range in one grid.
+int full_grid(const Span &s) {
     uint64_t work = s.vectorised ? s.nvec : s.n;
     uint64_t blocks = (work + kThreads - 1) / kThreads;
-    uint64_t cap = (uint64_t)cu_count() * blocks_per_cu();
-    if (cap > kMaxBlocks) cap = kMaxBlocks;
-    if (blocks > cap) blocks = cap;
+    if (blocks > kMaxGrid) blocks = kMaxGrid;   // the kernels loop, so a capped grid is still correct
+    return blocks == 0 ? 1 : (int)blocks;
+}
+
+// The norm pass: at most kNormBlocks blocks, each lane taking `unroll` vectors per trip.
+int norm_grid(const Span &s, int unroll) {
+    uint64_t work = s.vectorised ? (s.nvec + unroll - 1) / unroll : s.n;
+    uint64_t blocks = (work + kThreads - 1) / kThreads;
+    if (blocks > kNormBlocks) blocks = kNormBlocks;
     return blocks == 0 ? 1 : (int)blocks;
 }
 
@@ -402,7 +436,16 @@ int check_partials(const uint16_t *const *partials, uint32_t k, PartialPtrs &pp)
     return AMSP_OK;
 }
 
-inline int launched() { return hipGetLastError() == hipSuccess ? AMSP_OK : AMSP_EDEVICE; }
+// The HIP error state is per thread and shared with every other user of the runtime in the
+// process, so anything left there by someone else is dropped before a launch and only the
+// launch's own status is reported.
+inline void clear_stale_error() { (void)hipGetLastError(); }
+inline int launched() {
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess) return AMSP_OK;
+    fprintf(stderr, "amsp: kernel launch failed: %s\n", hipGetErrorString(e));
+    return AMSP_EDEVICE;
+}
 
 // Calls f(offset, length) for each bucket of [0,n).
 template <typename F>
@@ -454,7 +497,7 @@ const char *amsp_status_string(int status) {
     }
 }
 
-size_t amsp_workspace_bytes(void) { return (size_t)kMaxBlocks * sizeof(double); }
+size_t amsp_workspace_bytes(void) { return (size_t)kNormBlocks * sizeof(double); }
 
 int amsp_shard_range(uint64_t total_elems, uint32_t shard_factor, uint32_t rank, uint64_t *begin, uint64_t *end) {
     if (begin == nullptr || end == nullptr) return AMSP_ENULL;
@@ -471,8 +514,9 @@ int amsp_cast_param_shard(const float *master, uint16_t *param_bf16_out, uint64_
     if (master == nullptr || param_bf16_out == nullptr) return AMSP_ENULL;
     if (misaligned(master, 4) || misaligned(param_bf16_out, 2)) return AMSP_EALIGN;
     Stream16 st[2] = {{master, 4}, {param_bf16_out, 2}};
-    Span s = make_span(n, st, 2);
-    hipLaunchKernelGGL(cast_kernel, dim3(grid_for(s)), dim3(kThreads), 0, (hipStream_t)stream, master, param_bf16_out, s);
+    Span s = make_span(n, st, 2, kVecRW);
+    clear_stale_error();
+    hipLaunchKernelGGL(cast_kernel, dim3(full_grid(s)), dim3(kThreads), 0, (hipStream_t)stream, master, param_bf16_out, s);
     return launched();
 }
 
@@ -489,8 +533,9 @@ int amsp_reduce_grad_shard(const uint16_t *const *partials, uint32_t k, uint64_t
         Stream16 st[AMSP_MAX_K + 1];
         int ns = add_partial_streams(st, 0, q, k);
         st[ns++] = Stream16{grad_out + off, 4};
-        Span s = make_span(len, st, ns);
-        AMSP_DISPATCH_K(k, hipLaunchKernelGGL(reduce_kernel<KK>, dim3(grid_for(s)), dim3(kThreads), 0,
+        Span s = make_span(len, st, ns, kVecRW);
+        clear_stale_error();
+        AMSP_DISPATCH_K(k, hipLaunchKernelGGL(reduce_kernel<KK>, dim3(full_grid(s)), dim3(kThreads), 0,
                                               (hipStream_t)stream, q, (int)k, grad_out + off, accumulate, s));
         return launched();
     });
@@ -512,6 +557,7 @@ int amsp_grad_sqnorm(const uint16_t *const *partials, uint32_t k, const float *g
     if (workspace_bytes < amsp_workspace_bytes()) return AMSP_EWORKSPACE;
     double *block_sums = static_cast<double *>(workspace);
     hipStream_t hs = (hipStream_t)stream;
+    clear_stale_error();
     if (n == 0) {
         if (!accumulate) {
             hipLaunchKernelGGL(sqnorm_finish_kernel, dim3(1), dim3(kThreads), 0, hs, block_sums, 0, d_sqnorm, 0);
@@ -529,14 +575,25 @@ int amsp_grad_sqnorm(const uint16_t *const *partials, uint32_t k, const float *g
             gf = grad_f32 + off;
             st[ns++] = Stream16{gf, 4};
         }
-        Span s = make_span(len, st, ns);
-        const int grid = grid_for(s);
-        if (k == 0) {
-            hipLaunchKernelGGL(sqnorm_kernel<0>, dim3(grid), dim3(kThreads), 0, hs, q, 0, gf, block_sums, s);
-        } else {
-            AMSP_DISPATCH_K(k, hipLaunchKernelGGL(sqnorm_kernel<KK>, dim3(grid), dim3(kThreads), 0, hs, q, (int)k,
-                                                  gf, block_sums, s));
+        // 16-byte accesses in every case: 8 bf16 elements per lane, or 4 of the fp32 gradient
+        const int vec = k == 0 ? 4 : kVecNorm;
+        Span s = make_span(len, st, ns, vec);
+        // vectors in flight per lane (U): enough 16-byte loads to cover HBM latency, few enough
+        // to keep the register file at full occupancy
+        int grid;
+#define AMSP_LAUNCH_SQNORM(KV, V, U)                                                                  \
+        grid = norm_grid(s, U);                                                                       \
+        hipLaunchKernelGGL((sqnorm_kernel<KV, V, U>), dim3(grid), dim3(kThreads), 0, hs, q, (int)k, gf, block_sums, s)
+        switch (k) {
+            case 0: AMSP_LAUNCH_SQNORM(0, 4, 4); break;
+            case 1: AMSP_LAUNCH_SQNORM(1, kVecNorm, 4); break;
+            case 2: AMSP_LAUNCH_SQNORM(2, kVecNorm, 4); break;
+            case 4: AMSP_LAUNCH_SQNORM(4, kVecNorm, 2); break;
+            case 8: AMSP_LAUNCH_SQNORM(8, kVecNorm, 2); break;
+            case 16: AMSP_LAUNCH_SQNORM(16, kVecNorm, 1); break;
+            default: AMSP_LAUNCH_SQNORM(-1, kVecNorm, 1); break;
         }
+#undef AMSP_LAUNCH_SQNORM
         if (launched() != AMSP_OK) return (int)AMSP_EDEVICE;
         const int acc = (accumulate || !first) ? 1 : 0;
         first = false;
@@ -592,8 +649,9 @@ int amsp_adamw_step_shard(const uint16_t *const *partials, uint32_t k, const flo
         st[ns++] = Stream16{exp_avg_sq + off, 4};
         uint16_t *out = param_bf16_out ? param_bf16_out + off : nullptr;
         if (out) st[ns++] = Stream16{out, 2};
-        Span s = make_span(len, st, ns);
-        const dim3 grid(grid_for(s)), block(kThreads);
+        Span s = make_span(len, st, ns, kVecRW);
+        const dim3 grid(full_grid(s)), block(kThreads);
+        clear_stale_error();
 #define AMSP_LAUNCH_ADAMW(KV)                                                                              \
         if (out) hipLaunchKernelGGL((adamw_kernel<KV, true>), grid, block, 0, hs, q, (int)k, gf, master + off, \
                                     exp_avg + off, exp_avg_sq + off, out, c, s);                            \

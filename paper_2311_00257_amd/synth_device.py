@@ -17,6 +17,11 @@ def load() -> ctypes.CDLL:
     if _lib is None:
         if not os.path.exists(_build.LIB_SYNTH):
             raise RuntimeError("libamsp_synth.so is not built: run `python -m paper_2311_00257_amd.build`")
+        # torch supplies the device memory these kernels touch, so the library must bind to the
+        # HIP runtime torch has loaded: importing torch first makes the dynamic linker reuse it
+        # (two HIP runtimes in one process do not see each other's device state).
+        import torch  # noqa: F401
+
         lib = ctypes.CDLL(_build.LIB_SYNTH)
         u64, vp = ctypes.c_uint64, ctypes.c_void_p
         lib.amsp_synth_fill_f32.argtypes = [vp, u64, u64, u64, vp, ctypes.c_float, ctypes.c_int, vp]
