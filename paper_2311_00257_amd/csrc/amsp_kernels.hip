@@ -11,8 +11,10 @@
 //     range ("full grid"): the hardware dispatcher then hands out the range in address order
 //     and balances the CUs.  The same kernels as persistent grid-stride loops reach ~4.5 TB/s
 //     instead of ~5.8 TB/s on the k = 8 fused step.
-//   - The read-only norm pass keeps a fixed grid with a grid-stride loop (its per-block sums
-//     must land in a fixed-size workspace in a fixed order) and reads 16 bytes per lane.
+//   - The read-only norm pass is the opposite case: a persistent grid of exactly the resident
+//     size (two 1024-thread blocks per CU) with a grid-stride loop and 16-byte loads reads at
+//     6.6-6.9 TB/s, more than any full-grid or 256-thread variant, and its per-block sums fit a
+//     small fixed workspace, summed in a fixed order.
 //   - Non-temporal hints on all loads and stores: nothing is reused.
 // Nothing is staged through LDS except the block-level sum of the norm.  No matrix cores:
 // there is no contraction on this path.
@@ -36,7 +38,8 @@ namespace {
 constexpr int kThreads = 256;          // 4 waves of 64
 constexpr int kVecRW = 4;              // elements per lane per stream in the kernels that write
 constexpr int kVecNorm = 8;            // elements per lane per stream in the norm pass
-constexpr int kNormBlocks = 2048;      // fixed grid of the norm pass; sizes its workspace
+constexpr int kNormThreads = 1024;     // the norm pass runs 16-wave blocks, two per CU
+constexpr int kNormBlocks = 2048;      // upper bound of the norm pass's grid; sizes its workspace
 constexpr uint64_t kMaxGrid = 1u << 30;
 
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
@@ -247,28 +250,18 @@ __device__ __forceinline__ double wave_sum(double x) {
     return x;
 }
 
-template <int K, int VEC, int UNROLL>
-__global__ void __launch_bounds__(kThreads) sqnorm_kernel(PartialPtrs pp, int k, const float *__restrict__ gf32,
-                                                          double *__restrict__ block_sums, Span s) {
+template <int K, int VEC>
+__global__ void __launch_bounds__(kNormThreads) sqnorm_kernel(PartialPtrs pp, int k, const float *__restrict__ gf32,
+                                                              double *__restrict__ block_sums, Span s) {
+    const uint64_t first = (uint64_t)blockIdx.x * kNormThreads + threadIdx.x;
+    const uint64_t stride = (uint64_t)gridDim.x * kNormThreads;
     double acc = 0.0;
     if (s.vectorised) {
-        const uint64_t stride = grid_threads();
-        for (uint64_t v0 = global_thread(); v0 < s.nvec; v0 += stride * UNROLL) {
-            float g[UNROLL][VEC];
+        for (uint64_t v = first; v < s.nvec; v += stride) {
+            float g[VEC];
+            grad_vec<K, VEC>(pp, k, gf32, s.head + v * VEC, g);
 #pragma unroll
-            for (int u = 0; u < UNROLL; ++u) {
-                const uint64_t v = v0 + u * stride;
-                if (v < s.nvec) {
-                    grad_vec<K, VEC>(pp, k, gf32, s.head + v * VEC, g[u]);
-                } else {
-#pragma unroll
-                    for (int c = 0; c < VEC; ++c) g[u][c] = 0.0f;
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < UNROLL; ++u)
-#pragma unroll
-                for (int c = 0; c < VEC; ++c) acc = fma((double)g[u][c], (double)g[u][c], acc);
+            for (int c = 0; c < VEC; ++c) acc = fma((double)g[c], (double)g[c], acc);
         }
         uint64_t i;
         if (blockIdx.x == 0 && threadIdx.x < 2 * (VEC - 1) && edge_index<VEC>(s, threadIdx.x, i)) {
@@ -276,19 +269,19 @@ __global__ void __launch_bounds__(kThreads) sqnorm_kernel(PartialPtrs pp, int k,
             acc = fma(g, g, acc);
         }
     } else {
-        for (uint64_t i = global_thread(); i < s.n; i += grid_threads()) {
+        for (uint64_t i = first; i < s.n; i += stride) {
             double g = (double)grad1<K>(pp, k, gf32, i);
             acc = fma(g, g, acc);
         }
     }
-    __shared__ double wave_part[kThreads / 64];
+    __shared__ double wave_part[kNormThreads / 64];
     acc = wave_sum(acc);
     if ((threadIdx.x & 63) == 0) wave_part[threadIdx.x >> 6] = acc;
     __syncthreads();
     if (threadIdx.x == 0) {
         double t = wave_part[0];
 #pragma unroll
-        for (int w = 1; w < kThreads / 64; ++w) t += wave_part[w];
+        for (int w = 1; w < kNormThreads / 64; ++w) t += wave_part[w];
         block_sums[blockIdx.x] = t;
     }
 }
@@ -414,11 +407,25 @@ int full_grid(const Span &s) {
     return blocks == 0 ? 1 : (int)blocks;
 }
 
-// The norm pass: at most kNormBlocks blocks, each lane taking `unroll` vectors per trip.
-int norm_grid(const Span &s, int unroll) {
-    uint64_t work = s.vectorised ? (s.nvec + unroll - 1) / unroll : s.n;
-    uint64_t blocks = (work + kThreads - 1) / kThreads;
-    if (blocks > kNormBlocks) blocks = kNormBlocks;
+int cu_count() {
+    static int cached[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        cached[dev] = n;
+    }
+    return cached[dev];
+}
+
+// The norm pass: two 1024-thread blocks per CU (what a CU holds), at most kNormBlocks.
+int norm_grid(const Span &s) {
+    uint64_t work = s.vectorised ? s.nvec : s.n;
+    uint64_t blocks = (work + kNormThreads - 1) / kNormThreads;
+    uint64_t cap = 2 * (uint64_t)cu_count();
+    if (cap > kNormBlocks) cap = kNormBlocks;
+    if (blocks > cap) blocks = cap;
     return blocks == 0 ? 1 : (int)blocks;
 }
 
@@ -578,20 +585,13 @@ int amsp_grad_sqnorm(const uint16_t *const *partials, uint32_t k, const float *g
         // 16-byte accesses in every case: 8 bf16 elements per lane, or 4 of the fp32 gradient
         const int vec = k == 0 ? 4 : kVecNorm;
         Span s = make_span(len, st, ns, vec);
-        // vectors in flight per lane (U): enough 16-byte loads to cover HBM latency, few enough
-        // to keep the register file at full occupancy
-        int grid;
-#define AMSP_LAUNCH_SQNORM(KV, V, U)                                                                  \
-        grid = norm_grid(s, U);                                                                       \
-        hipLaunchKernelGGL((sqnorm_kernel<KV, V, U>), dim3(grid), dim3(kThreads), 0, hs, q, (int)k, gf, block_sums, s)
-        switch (k) {
-            case 0: AMSP_LAUNCH_SQNORM(0, 4, 4); break;
-            case 1: AMSP_LAUNCH_SQNORM(1, kVecNorm, 4); break;
-            case 2: AMSP_LAUNCH_SQNORM(2, kVecNorm, 4); break;
-            case 4: AMSP_LAUNCH_SQNORM(4, kVecNorm, 2); break;
-            case 8: AMSP_LAUNCH_SQNORM(8, kVecNorm, 2); break;
-            case 16: AMSP_LAUNCH_SQNORM(16, kVecNorm, 1); break;
-            default: AMSP_LAUNCH_SQNORM(-1, kVecNorm, 1); break;
+        const int grid = norm_grid(s);
+#define AMSP_LAUNCH_SQNORM(KV, V)                                                                     \
+        hipLaunchKernelGGL((sqnorm_kernel<KV, V>), dim3(grid), dim3(kNormThreads), 0, hs, q, (int)k, gf, block_sums, s)
+        if (k == 0) {
+            AMSP_LAUNCH_SQNORM(0, 4);
+        } else {
+            AMSP_DISPATCH_K(k, AMSP_LAUNCH_SQNORM(KK, kVecNorm));
         }
 #undef AMSP_LAUNCH_SQNORM
         if (launched() != AMSP_OK) return (int)AMSP_EDEVICE;
