@@ -31,8 +31,11 @@ def parse_args():
     ap.add_argument("--config", type=int, default=1, help="workload id 0..4 (default 1: LLaMA-7B, factor 8)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-elems", type=int, default=64 * 1024 * 1024)
-    ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "hbm_traffic.json"),
-                    help="per-launch HBM bytes of the fused kernel measured with rocprofv3 --pmc")
+    ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "fused_adamw_hbm_traffic.txt"),
+                    help="rocprofv3 --pmc summary holding the fused kernel's measured HBM bytes per launch")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (a kernel of known traffic, for scaling "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     return ap.parse_args()
 
 
@@ -113,6 +116,13 @@ def main():
         if ev:
             ev[2].record()
 
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     for i in range(args.warmup):
         step(w.step + i)
     torch.cuda.synchronize()
@@ -134,11 +144,10 @@ def main():
 
     traffic = None
     try:
-        with open(args.traffic_json) as f:
-            tj = json.load(f)
-        if tj.get("workload") == w.name:
-            traffic = tj.get("bytes_per_launch")
-    except (OSError, ValueError):
+        fields = dict(line.split(":", 1) for line in open(args.traffic_file) if ":" in line and line[0] != "#")
+        if fields.get("workload", "").strip() == w.name:
+            traffic = float(fields["hbm_bytes_per_launch"])
+    except (OSError, ValueError, KeyError):
         pass
 
     out = {
