@@ -1,0 +1,124 @@
+"""GPU parity at the workloads' full sizes, in the launch configuration bench.py times.
+
+The device runs the whole step (norm pass, then the fused update) on the full shard.  The
+oracle streams the same seeded inputs chunk by chunk on the host to get the full squared
+norm (so the clip scale is the oracle's own), then recomputes a seeded sample of chunks,
+plus the first and last elements and a bucket boundary, element by element."""
+import numpy as np
+import pytest
+
+import helpers as H
+import oracle
+from paper_2311_00257_amd import synth, workloads
+
+pytestmark = pytest.mark.gpu
+
+CHUNK = 1 << 24
+THREADS = 16
+
+
+def _oracle_sqnorm_streamed(w, begin, n):
+    """Full-shard sum of squares by the oracle, CHUNK elements at a time, added in chunk order."""
+    bufs = [np.empty(CHUNK, dtype=np.uint16) for _ in range(w.k)]
+    total = 0.0
+    for off in range(0, n, CHUNK):
+        m = min(CHUNK, n - off)
+        parts = [synth.fill_bf16(w.key(synth.TENSOR_PARTIAL0 + j), begin + off, m, w.sigma_grad, out=bufs[j],
+                                 threads=THREADS) for j in range(w.k)]
+        total += oracle.sqnorm(oracle.reduce(parts, threads=THREADS), threads=THREADS)
+    return total
+
+
+def _sample_windows(w, n, count, width, seed):
+    rng = np.random.default_rng(seed)
+    starts = {0, n - width}
+    if w.bucket_elems:
+        nb = -(-n // w.bucket_elems)
+        for b in (1, nb // 2, nb - 1):                      # windows straddling bucket boundaries
+            starts.add(b * w.bucket_elems - width // 2)
+    while len(starts) < count:
+        starts.add(int(rng.integers(0, n - width)))
+    return sorted(starts)
+
+
+def _run_fullsize(cfg, windows=24, width=1 << 16):
+    import torch
+
+    from paper_2311_00257_amd import binding as B
+    from paper_2311_00257_amd import synth_device
+
+    w = workloads.get(cfg)
+    begin, end = B.amsp_shard_range(w.total_elems, w.shard_factor, w.rank)
+    assert (begin, end) == oracle.shard_range(w.total_elems, w.shard_factor, w.rank)
+    n = end - begin - w.drop_tail
+    need = n * (2 * w.k + 14) + (1 << 30)
+    torch.cuda.empty_cache()
+    free, _ = torch.cuda.mem_get_info()
+    if free < need:
+        pytest.skip("needs %.0f GB of device memory, %.0f free" % (need / 1e9, free / 1e9))
+
+    print("workload %d (%s): n=%d k=%d on device" % (cfg, w.name, n, w.k), flush=True)
+    parts = []
+    for j in range(w.k):
+        t = torch.empty(n, dtype=torch.int16, device="cuda")
+        synth_device.fill_bf16(t, w.key(synth.TENSOR_PARTIAL0 + j), begin, w.sigma_grad)
+        parts.append(t)
+    dp = torch.empty(n, dtype=torch.float32, device="cuda")
+    dm = torch.empty(n, dtype=torch.float32, device="cuda")
+    dv = torch.empty(n, dtype=torch.float32, device="cuda")
+    synth_device.fill_f32(dp, w.key(synth.TENSOR_MASTER), begin, w.sigma_param)
+    synth_device.fill_f32(dm, w.key(synth.TENSOR_EXP_AVG), begin, w.sigma_m)
+    synth_device.fill_f32(dv, w.key(synth.TENSOR_EXP_AVG_SQ), begin, w.scale_v, absolute=True)
+    out = torch.empty(n, dtype=torch.int16, device="cuda")
+    ws = torch.empty(B.amsp_workspace_bytes() // 8, dtype=torch.float64, device="cuda")
+    d_s = torch.zeros(1, dtype=torch.float64, device="cuda")
+    hp = H.hparams_of(w)
+    B.amsp_grad_sqnorm(parts, None, n, d_s, ws, bucket_elems=w.bucket_elems)
+    B.amsp_adamw_step_shard(parts, None, n, dp, dm, dv, out, B.AdamWHparams(d_total_sqnorm=d_s, **hp),
+                            bucket_elems=w.bucket_elems)
+    torch.cuda.synchronize()
+    S_gpu = float(d_s.item())
+
+    print("  oracle: streaming the full squared norm on the host", flush=True)
+    S = _oracle_sqnorm_streamed(w, begin, n)
+    assert abs(S_gpu - S) <= H.REL_TOL * S, (S_gpu, S)
+    # the statistical closed form of the synthetic gradients: E[S] = n k sigma^2, less ~0.55 % because
+    # the generator truncates each draw to bf16 (mean relative magnitude loss ~2^-8.5)
+    assert S == pytest.approx(n * w.k * w.sigma_grad ** 2, rel=1e-2)
+    scale = oracle.clip_scale(S, hp["max_norm"], hp["clip_eps"])
+    assert scale < 1.0                                       # clipping is active in every full workload
+
+    worst = dict(max_p=0.0, max_m=0.0, max_v=0.0, mismatches=0, elements=0)
+    for start in _sample_windows(w, n, windows, width, seed=cfg):
+        inp = H.host_inputs(w, begin + start, width, threads=THREADS)
+        G = oracle.reduce(inp.partials, threads=THREADS)
+        p1, m1, v1 = oracle.adamw(G, scale, inp.p, inp.m, inp.v, lr=hp["lr"], beta1=hp["beta1"], beta2=hp["beta2"],
+                                  eps=hp["eps"], weight_decay=hp["weight_decay"], step=hp["step"], threads=THREADS)
+        ref = dict(G=G, scale=scale, p=p1, m=m1, v=v1, p_bf16=oracle.cast(oracle.round_f32(p1)))
+        sl = slice(start, start + width)
+        gp, gm, gv = dp[sl].cpu().numpy(), dm[sl].cpu().numpy(), dv[sl].cpu().numpy()
+        st = H.check_state(gp, gm, gv, ref, inp.p, inp.m, hp)
+        bits = H.dev_bits(out[sl])
+        worst["mismatches"] += H.check_bf16(bits, ref)
+        assert np.array_equal(bits, oracle.cast(gp))         # the cast of the GPU's own fp32 is bit-exact
+        for key in ("max_p", "max_m", "max_v"):
+            worst[key] = max(worst[key], st[key])
+        worst["elements"] += width
+    assert worst["mismatches"] <= max(3, 1e-4 * worst["elements"])
+    print("  sqnorm gpu %.12g oracle %.12g scale %.6g; sampled %s" % (S_gpu, S, scale, worst), flush=True)
+
+
+def test_workload1_llama7b_factor8_full():
+    _run_fullsize(1)
+
+
+def test_workload3_llama13b_factor16_full():
+    _run_fullsize(3)
+
+
+def test_workload4_llama30b_bucketed_full():
+    _run_fullsize(4)
+
+
+def test_workload2_llama7b_full_replica_full():
+    _run_fullsize(2)
