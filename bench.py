@@ -30,7 +30,8 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=1, help="workload id 0..4 (default 1: LLaMA-7B, factor 8)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-elems", type=int, default=64 * 1024 * 1024)
+    ap.add_argument("--no-alt", action="store_true", help="skip the materialised-gradient composition")
+    ap.add_argument("--cpu-sample-elems", type=int, default=256 * 1024 * 1024)
     ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "fused_adamw_hbm_traffic.txt"),
                     help="rocprofv3 --pmc summary holding the fused kernel's measured HBM bytes per launch")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -62,6 +63,44 @@ def cpu_baseline(w, begin, sample):
             "sample": "first %d elements of the %s shard, whole step (reduce, norm, clip, AdamW, cast) in fp64; "
                       "one contiguous chunk per thread" % (sample, w.name),
             "single_thread_value": res["one"]}
+
+
+def alt_step(args, torch, B, w, n, parts, master, exp_avg, exp_avg_sq, param_bf16, d_sqnorm):
+    """The other composition of the same steps, timed after the primary one: amsp_reduce_grad_shard with
+    the norm fused in writes the fp32 gradient (2k + 4 bytes/element), then amsp_adamw_step_shard on that
+    gradient with the bf16 cast (30 bytes/element): 2k + 34 in all instead of 4k + 26."""
+    g32 = torch.empty(n, dtype=torch.float32, device="cuda")
+    ws = torch.empty(B.amsp_reduce_workspace_bytes(n, w.bucket_elems) // 8, dtype=torch.float64, device="cuda")
+
+    def step(t, ev=None):
+        hp = B.AdamWHparams(lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps, weight_decay=w.weight_decay,
+                            step=t, max_norm=w.max_norm, clip_eps=w.clip_eps, d_total_sqnorm=d_sqnorm)
+        if ev:
+            ev[0].record()
+        B.amsp_reduce_grad_shard(parts, n, g32, bucket_elems=w.bucket_elems, d_sqnorm=d_sqnorm, workspace=ws)
+        if ev:
+            ev[1].record()
+        B.amsp_adamw_step_shard(None, g32, n, master, exp_avg, exp_avg_sq, param_bf16, hp,
+                                bucket_elems=w.bucket_elems)
+        if ev:
+            ev[2].record()
+
+    for i in range(args.warmup):
+        step(w.step + i)
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(w.step + args.warmup + i, events[i])
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    red_ms = sum(e[0].elapsed_time(e[1]) for e in events) / args.steps
+    upd_ms = sum(e[1].elapsed_time(e[2]) for e in events) / args.steps
+    return {"composition": "reduce+norm -> fp32 gradient -> AdamW+cast", "bytes_per_element": 2 * w.k + 34,
+            "ms_per_step": ms, "value": n / (ms * 1e-3), "unit": "elements/s",
+            "reduce_norm": {"ms": red_ms, "GB/s": (2 * w.k + 4) * n / (red_ms * 1e-3) / 1e9,
+                            "bytes_per_element": 2 * w.k + 4},
+            "adamw_f32_grad": {"ms": upd_ms, "GB/s": 30 * n / (upd_ms * 1e-3) / 1e9, "bytes_per_element": 30}}
 
 
 def main():
@@ -174,6 +213,8 @@ def main():
                       "bytes_per_element": w.bytes_per_elem_norm()},
         "whole_step_GBps": (w.bytes_per_elem_fused() + w.bytes_per_elem_norm()) * n / (ms_per_step * 1e-3) / 1e9,
     }
+    if not args.no_alt:
+        out["alt_step"] = alt_step(args, torch, B, w, n, parts, master, exp_avg, exp_avg_sq, param_bf16, d_sqnorm)
     if not args.no_cpu_baseline:
         del parts, master, exp_avg, exp_avg_sq, param_bf16
         out["cpu_baseline"] = cpu_baseline(w, begin, min(args.cpu_sample_elems, n))

@@ -26,8 +26,10 @@
  *     applies its shard or bucket offset); element i of every buffer is the same model-state
  *     element.  Buffers must not overlap, except that master/m/v are updated in place.
  *   - Pointers need only natural alignment (2 B bf16, 4 B fp32, 8 B double).  When all
- *     streams of a call reach 16-byte alignment at the same element index the kernels use
- *     128-bit accesses; otherwise a slower element-wise path gives the same results.
+ *     streams of a call reach the alignment of their vector access (8 or 16 bytes) at the
+ *     same element index, as they do when every buffer is offset by the same number of
+ *     elements from a 16-byte boundary, the kernels use vector accesses; otherwise a slower
+ *     element-wise path gives the same results.
  *   - bf16 values are passed as uint16_t bit patterns.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is
  *     enqueued and the call returns without waiting; amsp_shard_range alone is synchronous.
@@ -55,7 +57,7 @@ enum {
     AMSP_EINVAL = -1,     /* bad k / shard factor / rank / hyper-parameter */
     AMSP_ENULL = -2,      /* a required pointer is NULL */
     AMSP_EALIGN = -3,     /* a pointer is not aligned to its element size */
-    AMSP_EWORKSPACE = -4, /* workspace smaller than amsp_workspace_bytes() */
+    AMSP_EWORKSPACE = -4, /* workspace smaller than the entry point's requirement */
     AMSP_EDEVICE = -5     /* a HIP call failed */
 };
 
@@ -79,15 +81,25 @@ int amsp_shard_range(uint64_t total_elems, uint32_t shard_factor, uint32_t rank,
                      uint64_t *begin, uint64_t *end);
 
 /*
- * Step 1 alone: grad_out[i] (=|+=) sum_{j<k} partials[j][i], in fp32, j ascending.
+ * Step 1 alone: grad_out[i] (=|+=) sum_{j<k} partials[j][i], in fp32, j ascending; optionally with
+ * step 2 fused in for callers that keep the fp32 gradient (then the update reads 4 bytes per
+ * element instead of re-reading 2k).
  *   partials    host array of k device pointers, each bf16[n]
  *   k           1..AMSP_MAX_K
  *   grad_out    device fp32[n]
  *   accumulate  0: overwrite; 1: add the sum to what grad_out holds (gradient accumulation
  *               over micro-batches, Section IV-C.3)
+ *   d_sqnorm    device double or NULL.  Not NULL: *d_sqnorm (=|+=) sum_i grad_out[i]^2 of the
+ *               values just written (after `accumulate`), in fp64 in a fixed order, added in
+ *               bucket order; sqnorm_accumulate 0 overwrites, 1 adds to the value already there
+ *   workspace   device, >= amsp_reduce_workspace_bytes(n, bucket_elems), 8-byte aligned, used only
+ *               when d_sqnorm != NULL (else may be NULL); no initialisation needed, clobbered
  */
+size_t amsp_reduce_workspace_bytes(uint64_t n, uint64_t bucket_elems);
 int amsp_reduce_grad_shard(const uint16_t *const *partials, uint32_t k, uint64_t n,
-                           uint64_t bucket_elems, float *grad_out, int accumulate, void *stream);
+                           uint64_t bucket_elems, float *grad_out, int accumulate,
+                           double *d_sqnorm, int sqnorm_accumulate,
+                           void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Step 2: *d_sqnorm (=|+=) sum_i g[i]^2 with g the reduced gradient, accumulated in fp64 in a

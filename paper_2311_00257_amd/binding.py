@@ -18,7 +18,8 @@ from . import build as _build
 AMSP_OK, AMSP_EINVAL, AMSP_ENULL, AMSP_EALIGN, AMSP_EWORKSPACE, AMSP_EDEVICE = 0, -1, -2, -3, -4, -5
 AMSP_MAX_K = 32
 
-EXPORTS = ("amsp_status_string", "amsp_workspace_bytes", "amsp_shard_range", "amsp_reduce_grad_shard",
+EXPORTS = ("amsp_status_string", "amsp_workspace_bytes", "amsp_reduce_workspace_bytes", "amsp_shard_range",
+           "amsp_reduce_grad_shard",
            "amsp_grad_sqnorm", "amsp_adamw_step_shard", "amsp_cast_param_shard")
 
 
@@ -72,11 +73,13 @@ def load() -> ctypes.CDLL:
         lib.amsp_workspace_bytes.argtypes = []
         lib.amsp_workspace_bytes.restype = ctypes.c_size_t
         lib.amsp_shard_range.argtypes = [u64, u32, u32, ctypes.POINTER(u64), ctypes.POINTER(u64)]
-        lib.amsp_reduce_grad_shard.argtypes = [vp, u32, u64, u64, vp, ci, vp]
+        lib.amsp_reduce_workspace_bytes.argtypes = [u64, u64]
+        lib.amsp_reduce_workspace_bytes.restype = ctypes.c_size_t
+        lib.amsp_reduce_grad_shard.argtypes = [vp, u32, u64, u64, vp, ci, vp, ci, vp, ctypes.c_size_t, vp]
         lib.amsp_grad_sqnorm.argtypes = [vp, u32, vp, u64, u64, vp, ci, vp, ctypes.c_size_t, vp]
         lib.amsp_adamw_step_shard.argtypes = [vp, u32, vp, u64, u64, vp, vp, vp, vp, ctypes.POINTER(_Hparams), vp]
         lib.amsp_cast_param_shard.argtypes = [vp, vp, u64, vp]
-        for name in EXPORTS[2:]:
+        for name in EXPORTS[3:]:
             getattr(lib, name).restype = ci
         _lib = lib
     return _lib
@@ -128,20 +131,31 @@ def amsp_shard_range(total_elems: int, shard_factor: int, rank: int):
     return b.value, e.value
 
 
+def amsp_reduce_workspace_bytes(n: int, bucket_elems: int = 0) -> int:
+    return int(load().amsp_reduce_workspace_bytes(n, bucket_elems))
+
+
+def _nbytes(t, given: Optional[int]) -> int:
+    if given is not None:
+        return given
+    return 0 if t is None or isinstance(t, int) else t.numel() * t.element_size()
+
+
 def amsp_reduce_grad_shard(partials, n: int, grad_out, bucket_elems: int = 0, accumulate: bool = False,
-                           stream=None) -> None:
+                           d_sqnorm=None, sqnorm_accumulate: bool = False, workspace=None,
+                           workspace_bytes: Optional[int] = None, stream=None) -> None:
     arr, k = _partials(partials)
-    _check(load().amsp_reduce_grad_shard(arr, k, n, bucket_elems, _ptr(grad_out), int(accumulate), _stream(stream)),
-           "amsp_reduce_grad_shard")
+    _check(load().amsp_reduce_grad_shard(arr, k, n, bucket_elems, _ptr(grad_out), int(accumulate), _ptr(d_sqnorm),
+                                         int(sqnorm_accumulate), _ptr(workspace), _nbytes(workspace, workspace_bytes),
+                                         _stream(stream)), "amsp_reduce_grad_shard")
 
 
 def amsp_grad_sqnorm(partials, grad_f32, n: int, d_sqnorm, workspace, bucket_elems: int = 0,
                      accumulate: bool = False, stream=None, workspace_bytes: Optional[int] = None) -> None:
     arr, k = _partials(partials)
-    if workspace_bytes is None:
-        workspace_bytes = 0 if workspace is None or isinstance(workspace, int) else workspace.numel() * workspace.element_size()
     _check(load().amsp_grad_sqnorm(arr, k, _ptr(grad_f32), n, bucket_elems, _ptr(d_sqnorm), int(accumulate),
-                                   _ptr(workspace), workspace_bytes, _stream(stream)), "amsp_grad_sqnorm")
+                                   _ptr(workspace), _nbytes(workspace, workspace_bytes), _stream(stream)),
+           "amsp_grad_sqnorm")
 
 
 def amsp_adamw_step_shard(partials, grad_f32, n: int, master, exp_avg, exp_avg_sq, param_bf16_out,

@@ -208,34 +208,86 @@ __global__ void __launch_bounds__(kThreads) cast_kernel(const float *__restrict_
     }
 }
 
-// ---------------------------------------------------------------- step 1: reduce
-template <int K>
-__global__ void __launch_bounds__(kThreads) reduce_kernel(PartialPtrs pp, int k, float *__restrict__ out,
-                                                          int accumulate, Span s) {
-    constexpr int VEC = kVecRW;
-    if (s.vectorised) {
-        for (uint64_t v = global_thread(); v < s.nvec; v += grid_threads()) {
-            const uint64_t e = s.head + v * VEC;
-            float g[VEC];
-            grad_vec<K, VEC>(pp, k, nullptr, e, g);
-            if (accumulate) {
-                float o[VEC];
-                ld_f32<VEC>(out, e, o);
+// ---------------------------------------------------------------- block-level fp64 sums
+// Lanes are summed by a shuffle tree, waves through LDS, in a fixed order; thread 0 gets the sum.
+__device__ __forceinline__ double wave_sum(double x) {
 #pragma unroll
-                for (int c = 0; c < VEC; ++c) g[c] = o[c] + g[c];
+    for (int off = 32; off > 0; off >>= 1) x += __shfl_down(x, off, 64);
+    return x;
+}
+
+template <int THREADS>
+__device__ __forceinline__ double block_sum(double acc) {
+    __shared__ double wave_part[THREADS / 64];
+    acc = wave_sum(acc);
+    if ((threadIdx.x & 63) == 0) wave_part[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    double t = 0.0;
+    if (threadIdx.x == 0) {
+        t = wave_part[0];
+#pragma unroll
+        for (int w = 1; w < THREADS / 64; ++w) t += wave_part[w];
+    }
+    return t;
+}
+
+// ---------------------------------------------------------------- step 1: reduce
+// NORM: also sum the squares of the values written, one double per block into block_sums
+// (step 2 fused into step 1 for callers that keep the fp32 gradient).  A block then covers
+// ROWS * 256 consecutive vectors, which keeps the number of block sums at n / 4096.
+template <int K, bool NORM, int ROWS>
+__global__ void __launch_bounds__(kThreads) reduce_kernel(PartialPtrs pp, int k, float *__restrict__ out,
+                                                          int accumulate, double *__restrict__ block_sums, Span s) {
+    constexpr int VEC = kVecRW;
+    double acc = 0.0;
+    if (s.vectorised) {
+        const uint64_t block_vecs = (uint64_t)ROWS * kThreads;
+        for (uint64_t v0 = blockIdx.x * block_vecs + threadIdx.x; v0 < s.nvec; v0 += gridDim.x * block_vecs) {
+            float g[ROWS][VEC];
+#pragma unroll
+            for (int r = 0; r < ROWS; ++r) {
+                const uint64_t v = v0 + (uint64_t)r * kThreads;
+                if (v < s.nvec) {
+                    const uint64_t e = s.head + v * VEC;
+                    grad_vec<K, VEC>(pp, k, nullptr, e, g[r]);
+                    if (accumulate) {
+                        float o[VEC];
+                        ld_f32<VEC>(out, e, o);
+#pragma unroll
+                        for (int c = 0; c < VEC; ++c) g[r][c] = o[c] + g[r][c];
+                    }
+                }
             }
-            st_f32<VEC>(out, e, g);
+#pragma unroll
+            for (int r = 0; r < ROWS; ++r) {
+                const uint64_t v = v0 + (uint64_t)r * kThreads;
+                if (v < s.nvec) {
+                    st_f32<VEC>(out, s.head + v * VEC, g[r]);
+                    if constexpr (NORM) {
+#pragma unroll
+                        for (int c = 0; c < VEC; ++c) acc = fma((double)g[r][c], (double)g[r][c], acc);
+                    }
+                }
+            }
         }
         uint64_t i;
         if (blockIdx.x == 0 && threadIdx.x < 2 * (VEC - 1) && edge_index<VEC>(s, threadIdx.x, i)) {
             float g = grad1<K>(pp, k, nullptr, i);
-            out[i] = accumulate ? out[i] + g : g;
+            if (accumulate) g = out[i] + g;
+            out[i] = g;
+            if constexpr (NORM) acc = fma((double)g, (double)g, acc);
         }
     } else {
         for (uint64_t i = global_thread(); i < s.n; i += grid_threads()) {
             float g = grad1<K>(pp, k, nullptr, i);
-            out[i] = accumulate ? out[i] + g : g;
+            if (accumulate) g = out[i] + g;
+            out[i] = g;
+            if constexpr (NORM) acc = fma((double)g, (double)g, acc);
         }
+    }
+    if constexpr (NORM) {
+        const double t = block_sum<kThreads>(acc);
+        if (threadIdx.x == 0) block_sums[blockIdx.x] = t;
     }
 }
 
@@ -244,12 +296,6 @@ __global__ void __launch_bounds__(kThreads) reduce_kernel(PartialPtrs pp, int k,
 // shuffle tree, waves through LDS, and each block stores one double.  A second one-block
 // kernel adds the block sums in index order.  No atomics, so the result depends only on
 // (n, alignment, grid size), never on timing.
-__device__ __forceinline__ double wave_sum(double x) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) x += __shfl_down(x, off, 64);
-    return x;
-}
-
 template <int K, int VEC>
 __global__ void __launch_bounds__(kNormThreads) sqnorm_kernel(PartialPtrs pp, int k, const float *__restrict__ gf32,
                                                               double *__restrict__ block_sums, Span s) {
@@ -274,18 +320,11 @@ __global__ void __launch_bounds__(kNormThreads) sqnorm_kernel(PartialPtrs pp, in
             acc = fma(g, g, acc);
         }
     }
-    __shared__ double wave_part[kNormThreads / 64];
-    acc = wave_sum(acc);
-    if ((threadIdx.x & 63) == 0) wave_part[threadIdx.x >> 6] = acc;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        double t = wave_part[0];
-#pragma unroll
-        for (int w = 1; w < kNormThreads / 64; ++w) t += wave_part[w];
-        block_sums[blockIdx.x] = t;
-    }
+    const double t = block_sum<kNormThreads>(acc);
+    if (threadIdx.x == 0) block_sums[blockIdx.x] = t;
 }
 
+// Adds nblocks block sums in a fixed order (lane-strided, then a tree) and stores or adds the total.
 __global__ void __launch_bounds__(kThreads) sqnorm_finish_kernel(const double *__restrict__ block_sums, int nblocks,
                                                                  double *__restrict__ out, int accumulate) {
     __shared__ double part[kThreads];
@@ -298,6 +337,17 @@ __global__ void __launch_bounds__(kThreads) sqnorm_finish_kernel(const double *_
         __syncthreads();
     }
     if (threadIdx.x == 0) *out = accumulate ? *out + part[0] : part[0];
+}
+
+// First stage for long lists of block sums: block f adds the slice [f*slice, (f+1)*slice).
+__global__ void __launch_bounds__(kThreads) sum_slices_kernel(const double *__restrict__ block_sums, uint64_t count,
+                                                              uint64_t slice, double *__restrict__ slice_sums) {
+    const uint64_t lo = blockIdx.x * slice;
+    const uint64_t hi = lo + slice < count ? lo + slice : count;
+    double t = 0.0;
+    for (uint64_t b = lo + threadIdx.x; b < hi; b += kThreads) t += block_sums[b];
+    t = block_sum<kThreads>(t);
+    if (threadIdx.x == 0) slice_sums[blockIdx.x] = t;
 }
 
 // ---------------------------------------------------------------- step 3 (+1, +4): AdamW
@@ -419,6 +469,32 @@ int cu_count() {
     return cached[dev];
 }
 
+// Reduce with the norm fused in: one block per kReduceNormRows * 256 vectors on the vector path,
+// a capped grid-stride grid on the element-wise path; every block leaves one double.
+constexpr int kReduceNormRows = 4;
+constexpr int kSliceBlocks = 256;
+
+uint64_t reduce_norm_grid(const Span &s) {
+    uint64_t blocks;
+    if (s.vectorised) {
+        const uint64_t per = (uint64_t)kReduceNormRows * kThreads;
+        blocks = (s.nvec + per - 1) / per;
+    } else {
+        blocks = (s.n + kThreads - 1) / kThreads;
+        if (blocks > (uint64_t)kNormBlocks) blocks = kNormBlocks;
+    }
+    if (blocks > kMaxGrid) blocks = kMaxGrid;
+    return blocks == 0 ? 1 : blocks;
+}
+
+// Upper bound of reduce_norm_grid over every alignment of a launch of `len` elements.
+uint64_t reduce_norm_blocks_max(uint64_t len) {
+    const uint64_t per = (uint64_t)kReduceNormRows * kThreads * kVecRW;
+    uint64_t blocks = len / per + 2;
+    if (blocks < (uint64_t)kNormBlocks) blocks = kNormBlocks;
+    return blocks;
+}
+
 // The norm pass: two 1024-thread blocks per CU (what a CU holds), at most kNormBlocks.
 int norm_grid(const Span &s) {
     uint64_t work = s.vectorised ? s.nvec : s.n;
@@ -527,14 +603,36 @@ int amsp_cast_param_shard(const float *master, uint16_t *param_bf16_out, uint64_
     return launched();
 }
 
+size_t amsp_reduce_workspace_bytes(uint64_t n, uint64_t bucket_elems) {
+    const uint64_t launch = (bucket_elems != 0 && bucket_elems < n) ? bucket_elems : n;
+    return (size_t)(reduce_norm_blocks_max(launch) + kSliceBlocks) * sizeof(double);
+}
+
 int amsp_reduce_grad_shard(const uint16_t *const *partials, uint32_t k, uint64_t n, uint64_t bucket_elems,
-                           float *grad_out, int accumulate, void *stream) {
+                           float *grad_out, int accumulate, double *d_sqnorm, int sqnorm_accumulate,
+                           void *workspace, size_t workspace_bytes, void *stream) {
     PartialPtrs pp;
     int rc = check_partials(partials, k, pp);
     if (rc != AMSP_OK) return rc;
-    if (n == 0) return AMSP_OK;
+    const bool norm = d_sqnorm != nullptr;
+    if (norm) {
+        if (workspace == nullptr) return AMSP_ENULL;
+        if (misaligned(d_sqnorm, 8) || misaligned(workspace, 8)) return AMSP_EALIGN;
+        if (workspace_bytes < amsp_reduce_workspace_bytes(n, bucket_elems)) return AMSP_EWORKSPACE;
+    }
+    hipStream_t hs = (hipStream_t)stream;
+    double *block_sums = static_cast<double *>(workspace);
+    if (n == 0) {
+        if (norm && !sqnorm_accumulate) {
+            clear_stale_error();
+            hipLaunchKernelGGL(sqnorm_finish_kernel, dim3(1), dim3(kThreads), 0, hs, block_sums, 0, d_sqnorm, 0);
+            return launched();
+        }
+        return AMSP_OK;
+    }
     if (grad_out == nullptr) return AMSP_ENULL;
     if (misaligned(grad_out, 4)) return AMSP_EALIGN;
+    bool first = true;
     return for_buckets(n, bucket_elems, [&](uint64_t off, uint64_t len) {
         PartialPtrs q = offset_partials(pp, k, off);
         Stream16 st[AMSP_MAX_K + 1];
@@ -542,8 +640,31 @@ int amsp_reduce_grad_shard(const uint16_t *const *partials, uint32_t k, uint64_t
         st[ns++] = Stream16{grad_out + off, 4};
         Span s = make_span(len, st, ns, kVecRW);
         clear_stale_error();
-        AMSP_DISPATCH_K(k, hipLaunchKernelGGL(reduce_kernel<KK>, dim3(full_grid(s)), dim3(kThreads), 0,
-                                              (hipStream_t)stream, q, (int)k, grad_out + off, accumulate, s));
+        if (!norm) {
+            AMSP_DISPATCH_K(k, hipLaunchKernelGGL((reduce_kernel<KK, false, 1>), dim3(full_grid(s)), dim3(kThreads), 0,
+                                                  hs, q, (int)k, grad_out + off, accumulate, block_sums, s));
+            return launched();
+        }
+        const uint64_t blocks = reduce_norm_grid(s);
+        AMSP_DISPATCH_K(k, hipLaunchKernelGGL((reduce_kernel<KK, true, kReduceNormRows>), dim3((unsigned)blocks),
+                                              dim3(kThreads), 0, hs, q, (int)k, grad_out + off, accumulate,
+                                              block_sums, s));
+        if (launched() != AMSP_OK) return (int)AMSP_EDEVICE;
+        const int acc = (sqnorm_accumulate || !first) ? 1 : 0;
+        first = false;
+        const double *sums = block_sums;
+        int count = (int)blocks;
+        if (blocks > (uint64_t)kNormBlocks) {
+            // two stages: kSliceBlocks blocks each add one contiguous slice, then one block adds those
+            double *slice_sums = block_sums + blocks;
+            const uint64_t slice = (blocks + kSliceBlocks - 1) / kSliceBlocks;
+            count = (int)((blocks + slice - 1) / slice);
+            hipLaunchKernelGGL(sum_slices_kernel, dim3(count), dim3(kThreads), 0, hs, block_sums, blocks, slice,
+                               slice_sums);
+            if (launched() != AMSP_OK) return (int)AMSP_EDEVICE;
+            sums = slice_sums;
+        }
+        hipLaunchKernelGGL(sqnorm_finish_kernel, dim3(1), dim3(kThreads), 0, hs, sums, count, d_sqnorm, acc);
         return launched();
     });
 }

@@ -92,6 +92,11 @@ def test_argument_validation_without_device():
     assert _status(B.amsp_reduce_grad_shard, [A], 8, 0) == B.AMSP_ENULL
     assert _status(B.amsp_reduce_grad_shard, [A], 8, A + 2) == B.AMSP_EALIGN
     B.amsp_reduce_grad_shard([A], 0, 0, stream=0)
+    need = B.amsp_reduce_workspace_bytes(1 << 20, 0)
+    assert need >= 8 * (1 << 20) // 4096 and B.amsp_reduce_workspace_bytes(1 << 30, 1 << 20) == need
+    assert _status(B.amsp_reduce_grad_shard, [A], 1 << 20, A, d_sqnorm=A, workspace=None) == B.AMSP_ENULL
+    assert _status(B.amsp_reduce_grad_shard, [A], 1 << 20, A, d_sqnorm=A + 4, workspace=A, workspace_bytes=need) == B.AMSP_EALIGN
+    assert _status(B.amsp_reduce_grad_shard, [A], 1 << 20, A, d_sqnorm=A, workspace=A, workspace_bytes=need - 8) == B.AMSP_EWORKSPACE
 
     ws = B.amsp_workspace_bytes()
     assert _status(B.amsp_grad_sqnorm, [A], None, 8, 0, A, workspace_bytes=ws) == B.AMSP_ENULL

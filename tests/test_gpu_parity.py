@@ -138,6 +138,56 @@ def test_reduce_identical_partials_and_accumulate(B, torch_mod):
     assert torch_mod.equal(out, ref)
 
 
+@pytest.mark.parametrize("k,n,shift", [(2, 9_000_003, 0), (8, 1_000_001, 3), (3, 4099, 1), (1, 5, 0)])
+def test_reduce_with_fused_norm(B, torch_mod, k, n, shift):
+    """Step 2 fused into step 1: same gradient bits as the plain reduce, and the squared norm of
+    what was written (9M elements exceed 2048 block sums: the two-stage finish)."""
+    torch = torch_mod
+    w = workloads.get(1)
+    inp = H.host_inputs(w, 4242, n, k=k)
+    dparts = [H.to_dev_bf16(p, pad_front=shift) for p in inp.partials]
+    plain = torch.zeros(shift + n, dtype=torch.float32, device="cuda")[shift:]
+    B.amsp_reduce_grad_shard(dparts, n, plain)
+    for bucket in (0, n // 3 + 1):
+        out = torch.zeros(shift + n, dtype=torch.float32, device="cuda")[shift:]
+        ws = torch.empty(B.amsp_reduce_workspace_bytes(n, bucket) // 8, dtype=torch.float64, device="cuda")
+        d_s = torch.full((1,), 5.0, dtype=torch.float64, device="cuda")
+        B.amsp_reduce_grad_shard(dparts, n, out, bucket_elems=bucket, d_sqnorm=d_s, workspace=ws)
+        assert torch.equal(out, plain)
+        S = oracle.sqnorm(oracle.reduce(inp.partials, threads=4))
+        got = float(d_s.item())
+        assert abs(got - S) <= H.REL_TOL * S
+        B.amsp_reduce_grad_shard(dparts, n, out, bucket_elems=bucket, d_sqnorm=d_s, workspace=ws)
+        assert float(d_s.item()) == got                     # deterministic
+        # second micro-batch: accumulate the gradient, norm of the accumulated buffer, added to the scalar
+        B.amsp_reduce_grad_shard(dparts, n, out, bucket_elems=bucket, accumulate=True, d_sqnorm=d_s,
+                                 sqnorm_accumulate=True, workspace=ws)
+        G2 = 2.0 * oracle.reduce(inp.partials, threads=4)
+        assert np.array_equal(out.cpu().numpy().astype(np.float64), G2)        # 2 g is exact in fp32
+        assert float(d_s.item()) == pytest.approx(got + oracle.sqnorm(G2), rel=1e-12)
+
+
+def test_step_through_materialised_gradient(B, torch_mod):
+    """The other composition of the same steps: reduce with the norm fused in, then AdamW on the
+    fp32 gradient with the cast: same results as the oracle (and as the fused pass)."""
+    torch = torch_mod
+    w = workloads.get(1)
+    n = 500_003
+    inp = H.host_inputs(w, 99, n)
+    hp = H.hparams_of(w, max_norm=0.05)
+    ref = _oracle_step(inp, hp)
+    dparts = [H.to_dev_bf16(p) for p in inp.partials]
+    dp, dm, dv = H.to_dev_f32(inp.p), H.to_dev_f32(inp.m), H.to_dev_f32(inp.v)
+    g32 = torch.empty(n, dtype=torch.float32, device="cuda")
+    out = torch.zeros(n, dtype=torch.int16, device="cuda")
+    ws = torch.empty(B.amsp_reduce_workspace_bytes(n, 0) // 8, dtype=torch.float64, device="cuda")
+    d_s = torch.zeros(1, dtype=torch.float64, device="cuda")
+    B.amsp_reduce_grad_shard(dparts, n, g32, d_sqnorm=d_s, workspace=ws)
+    B.amsp_adamw_step_shard(None, g32, n, dp, dm, dv, out, B.AdamWHparams(d_total_sqnorm=d_s, **hp))
+    got = (dp.cpu().numpy(), dm.cpu().numpy(), dv.cpu().numpy(), H.dev_bits(out), float(d_s.item()))
+    _check_all(got, ref, inp, hp)
+
+
 # ------------------------------------------------------------------ squared norm
 @pytest.mark.parametrize("k", [1, 2, 3, 8, 16])
 def test_sqnorm_against_oracle(B, torch_mod, k):
