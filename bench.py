@@ -4,6 +4,8 @@
 A step is one pass of the whole path over one rank's shard, inputs resident in HBM:
     amsp_grad_sqnorm (k bf16 partials -> squared norm)           2k   bytes/element
     amsp_adamw_step_shard (reduce + clip + AdamW + bf16 cast)    2k+26 bytes/element
+The other composition of the same steps (reduce with the norm fused in -> fp32 gradient ->
+AdamW + cast, 2k+34 bytes/element in all) is timed afterwards and reported as "alt_step".
 Default workload: LLaMA-7B at shard factor 8, rank 3, k = 8 (842,301,952 elements).
 Prints ONE JSON line: throughput in elements/s, the HBM roofline of the fused kernel from
 HIP-event timing of that kernel alone, and the CPU oracle timed on a bounded slice.
@@ -31,7 +33,7 @@ def parse_args():
     ap.add_argument("--config", type=int, default=1, help="workload id 0..4 (default 1: LLaMA-7B, factor 8)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-alt", action="store_true", help="skip the materialised-gradient composition")
-    ap.add_argument("--cpu-sample-elems", type=int, default=256 * 1024 * 1024)
+    ap.add_argument("--cpu-sample-elems", type=int, default=512 * 1024 * 1024)
     ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "fused_adamw_hbm_traffic.txt"),
                     help="rocprofv3 --pmc summary holding the fused kernel's measured HBM bytes per launch")
     ap.add_argument("--calibrate-copy", action="store_true",
