@@ -31,28 +31,33 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
+def _bind(lib):
+    """Declare the C signatures on a loaded library (also used by the tests that load
+    deliberately broken builds of the oracle to show that the pins catch them)."""
+    u64, u32, dbl, flt, vp = ctypes.c_uint64, ctypes.c_uint32, ctypes.c_double, ctypes.c_float, ctypes.c_void_p
+    lib.amsp_oracle_shard_range.argtypes = [u64, u32, u32, ctypes.POINTER(u64), ctypes.POINTER(u64)]
+    lib.amsp_oracle_shard_range.restype = None
+    lib.amsp_oracle_reduce.argtypes = [vp, u32, u64, vp]
+    lib.amsp_oracle_reduce.restype = None
+    lib.amsp_oracle_sqnorm.argtypes = [vp, u64]
+    lib.amsp_oracle_sqnorm.restype = dbl
+    lib.amsp_oracle_clip_scale.argtypes = [dbl, dbl, dbl]
+    lib.amsp_oracle_clip_scale.restype = dbl
+    lib.amsp_oracle_adamw.argtypes = [vp, dbl, vp, vp, vp, u64, flt, flt, flt, flt, flt, u32, vp, vp, vp]
+    lib.amsp_oracle_adamw.restype = None
+    lib.amsp_oracle_bf16_rne.argtypes = [flt]
+    lib.amsp_oracle_bf16_rne.restype = ctypes.c_uint16
+    lib.amsp_oracle_cast.argtypes = [vp, u64, vp]
+    lib.amsp_oracle_cast.restype = None
+    lib.amsp_oracle_round_f32.argtypes = [vp, u64, vp]
+    lib.amsp_oracle_round_f32.restype = None
+    return lib
+
+
 def _load():
     global _lib
     if _lib is None:
-        lib = ctypes.CDLL(build())
-        u64, u32, dbl, flt, vp = ctypes.c_uint64, ctypes.c_uint32, ctypes.c_double, ctypes.c_float, ctypes.c_void_p
-        lib.amsp_oracle_shard_range.argtypes = [u64, u32, u32, ctypes.POINTER(u64), ctypes.POINTER(u64)]
-        lib.amsp_oracle_shard_range.restype = None
-        lib.amsp_oracle_reduce.argtypes = [vp, u32, u64, vp]
-        lib.amsp_oracle_reduce.restype = None
-        lib.amsp_oracle_sqnorm.argtypes = [vp, u64]
-        lib.amsp_oracle_sqnorm.restype = dbl
-        lib.amsp_oracle_clip_scale.argtypes = [dbl, dbl, dbl]
-        lib.amsp_oracle_clip_scale.restype = dbl
-        lib.amsp_oracle_adamw.argtypes = [vp, dbl, vp, vp, vp, u64, flt, flt, flt, flt, flt, u32, vp, vp, vp]
-        lib.amsp_oracle_adamw.restype = None
-        lib.amsp_oracle_bf16_rne.argtypes = [flt]
-        lib.amsp_oracle_bf16_rne.restype = ctypes.c_uint16
-        lib.amsp_oracle_cast.argtypes = [vp, u64, vp]
-        lib.amsp_oracle_cast.restype = None
-        lib.amsp_oracle_round_f32.argtypes = [vp, u64, vp]
-        lib.amsp_oracle_round_f32.restype = None
-        _lib = lib
+        _lib = _bind(ctypes.CDLL(build()))
     return _lib
 
 
