@@ -34,7 +34,7 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-alt", action="store_true", help="skip the materialised-gradient composition")
     ap.add_argument("--cpu-sample-elems", type=int, default=512 * 1024 * 1024)
-    ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "fused_adamw_hbm_traffic.txt"),
+    ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "adamw_kernel_llama7b_s8r3_k8_hbm_traffic.txt"),
                     help="rocprofv3 --pmc summary holding the fused kernel's measured HBM bytes per launch")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a kernel of known traffic, for scaling "
