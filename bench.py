@@ -30,7 +30,7 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=1, help="workload id 0..4 (default 1: LLaMA-7B, factor 8)")
+    ap.add_argument("--config", type=int, default=1, help="workload id 0..5 (default 1: LLaMA-7B, factor 8, k = 8)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-alt", action="store_true", help="skip the materialised-gradient composition")
     ap.add_argument("--cpu-sample-elems", type=int, default=512 * 1024 * 1024)
@@ -123,37 +123,72 @@ def main():
     B.load()
     torch.cuda.set_device(0)
     w = workloads.get(args.config)
-    begin, end = B.amsp_shard_range(w.total_elems, w.shard_factor, w.rank)
-    n = end - begin - w.drop_tail
     k = w.k
-
-    # ---- inputs resident in HBM before the timed region
-    parts = []
-    for j in range(k):
-        t = torch.empty(n, dtype=torch.int16, device="cuda")
-        synth_device.fill_bf16(t, w.key(synth.TENSOR_PARTIAL0 + j), begin, w.sigma_grad)
-        parts.append(t)
-    master = torch.empty(n, dtype=torch.float32, device="cuda")
-    exp_avg = torch.empty(n, dtype=torch.float32, device="cuda")
-    exp_avg_sq = torch.empty(n, dtype=torch.float32, device="cuda")
-    synth_device.fill_f32(master, w.key(synth.TENSOR_MASTER), begin, w.sigma_param)
-    synth_device.fill_f32(exp_avg, w.key(synth.TENSOR_EXP_AVG), begin, w.sigma_m)
-    synth_device.fill_f32(exp_avg_sq, w.key(synth.TENSOR_EXP_AVG_SQ), begin, w.scale_v, absolute=True)
-    param_bf16 = torch.empty(n, dtype=torch.int16, device="cuda")
     workspace = torch.empty(B.amsp_workspace_bytes() // 8, dtype=torch.float64, device="cuda")
     d_sqnorm = torch.zeros(1, dtype=torch.float64, device="cuda")
+
+    def hparams(t):
+        return B.AdamWHparams(lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps, weight_decay=w.weight_decay,
+                              step=t, max_norm=w.max_norm, clip_eps=w.clip_eps, d_total_sqnorm=d_sqnorm)
+
+    # ---- inputs resident in HBM before the timed region
+    if not w.inter_tensor:
+        begin, end = B.amsp_shard_range(w.total_elems, w.shard_factor, w.rank)
+        n = end - begin - w.drop_tail
+        launches = 1 if not w.bucket_elems else -(-n // w.bucket_elems)
+        parts = []
+        for j in range(k):
+            t = torch.empty(n, dtype=torch.int16, device="cuda")
+            synth_device.fill_bf16(t, w.key(synth.TENSOR_PARTIAL0 + j), begin, w.sigma_grad)
+            parts.append(t)
+        master = torch.empty(n, dtype=torch.float32, device="cuda")
+        exp_avg = torch.empty(n, dtype=torch.float32, device="cuda")
+        exp_avg_sq = torch.empty(n, dtype=torch.float32, device="cuda")
+        synth_device.fill_f32(master, w.key(synth.TENSOR_MASTER), begin, w.sigma_param)
+        synth_device.fill_f32(exp_avg, w.key(synth.TENSOR_EXP_AVG), begin, w.sigma_m)
+        synth_device.fill_f32(exp_avg_sq, w.key(synth.TENSOR_EXP_AVG_SQ), begin, w.scale_v, absolute=True)
+        param_bf16 = torch.empty(n, dtype=torch.int16, device="cuda")
+
+        def norm_pass():
+            B.amsp_grad_sqnorm(parts, None, n, d_sqnorm, workspace, bucket_elems=w.bucket_elems)
+
+        def update_pass(t):
+            B.amsp_adamw_step_shard(parts, None, n, master, exp_avg, exp_avg_sq, param_bf16, hparams(t),
+                                    bucket_elems=w.bucket_elems)
+    else:
+        # inter-tensor shards: whole tensors chosen greedily, selected from flat whole-model gradient buffers
+        sizes, total = w.tensor_sizes, w.total_elems
+        owner = B.amsp_partition_tensors(sizes, w.shard_factor)
+        segs, n = B.amsp_owned_segments(sizes, owner, w.rank)
+        begin, launches = 0, len(segs)
+        parts = []
+        for j in range(k):
+            t = torch.empty(total, dtype=torch.int16, device="cuda")
+            synth_device.fill_bf16(t, w.key(synth.TENSOR_PARTIAL0 + j), 0, w.sigma_grad)
+            parts.append(t)
+        master = torch.empty(n, dtype=torch.float32, device="cuda")
+        exp_avg = torch.empty(n, dtype=torch.float32, device="cuda")
+        exp_avg_sq = torch.empty(n, dtype=torch.float32, device="cuda")
+        for f, l, m in segs:
+            synth_device.fill_f32(master[l:l + m], w.key(synth.TENSOR_MASTER), f, w.sigma_param)
+            synth_device.fill_f32(exp_avg[l:l + m], w.key(synth.TENSOR_EXP_AVG), f, w.sigma_m)
+            synth_device.fill_f32(exp_avg_sq[l:l + m], w.key(synth.TENSOR_EXP_AVG_SQ), f, w.scale_v, absolute=True)
+        param_bf16 = torch.empty(total, dtype=torch.int16, device="cuda")
+
+        def norm_pass():
+            B.amsp_grad_sqnorm_segments(parts, total, segs, d_sqnorm, workspace)
+
+        def update_pass(t):
+            B.amsp_adamw_step_segments(parts, total, segs, n, master, exp_avg, exp_avg_sq, param_bf16, hparams(t))
     torch.cuda.synchronize()
 
     def step(t, ev=None):
-        hp = B.AdamWHparams(lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps, weight_decay=w.weight_decay,
-                            step=t, max_norm=w.max_norm, clip_eps=w.clip_eps, d_total_sqnorm=d_sqnorm)
         if ev:
             ev[0].record()
-        B.amsp_grad_sqnorm(parts, None, n, d_sqnorm, workspace, bucket_elems=w.bucket_elems)
+        norm_pass()
         if ev:
             ev[1].record()
-        B.amsp_adamw_step_shard(parts, None, n, master, exp_avg, exp_avg_sq, param_bf16, hp,
-                                bucket_elems=w.bucket_elems)
+        update_pass(t)
         if ev:
             ev[2].record()
 
@@ -179,7 +214,6 @@ def main():
     ms_per_step = wall * 1e3 / args.steps
     norm_ms = sum(e[0].elapsed_time(e[1]) for e in events) / args.steps
     fused_ms = sum(e[1].elapsed_time(e[2]) for e in events) / args.steps
-    launches = 1 if not w.bucket_elems else -(-n // w.bucket_elems)
     fused_bytes = w.bytes_per_elem_fused() * n
     achieved = fused_bytes / (fused_ms * 1e-3) / 1e9
 
@@ -215,10 +249,10 @@ def main():
                       "bytes_per_element": w.bytes_per_elem_norm()},
         "whole_step_GBps": (w.bytes_per_elem_fused() + w.bytes_per_elem_norm()) * n / (ms_per_step * 1e-3) / 1e9,
     }
-    if not args.no_alt:
+    if not args.no_alt and not w.inter_tensor:
         out["alt_step"] = alt_step(args, torch, B, w, n, parts, master, exp_avg, exp_avg_sq, param_bf16, d_sqnorm)
     if not args.no_cpu_baseline:
-        del parts, master, exp_avg, exp_avg_sq, param_bf16
+        del parts, master, exp_avg, exp_avg_sq, param_bf16, norm_pass, update_pass
         out["cpu_baseline"] = cpu_baseline(w, begin, min(args.cpu_sample_elems, n))
     print(json.dumps(out), flush=True)
 

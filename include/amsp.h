@@ -164,6 +164,60 @@ int amsp_adamw_step_shard(const uint16_t *const *partials, uint32_t k, const flo
  */
 int amsp_cast_param_shard(const float *master, uint16_t *param_bf16_out, uint64_t n, void *stream);
 
+/* ------------------------------------------------------------------------------------------------
+ * Inter-tensor shards (Section IV-C.2, second scheme; the one the paper adopts): every parameter
+ * tensor goes, whole, with its optimizer states, to one rank, by a greedy rule that balances the
+ * ranks' memory; after the gradient AllReduce a rank "selects" the gradients of its own tensors
+ * from the flat buffer and drops the rest (Sections IV-C.2 and IV-C.3).  A rank's shard is then a
+ * list of segments of the flat whole-model buffer, and its optimizer states are stored compactly,
+ * segment after segment.
+ */
+typedef struct amsp_segment {
+    uint64_t flat_offset;  /* first element in the flat whole-model buffers (gradients, bf16 params) */
+    uint64_t local_offset; /* first element in the rank's compact master / exp_avg / exp_avg_sq */
+    uint64_t length;       /* elements */
+} amsp_segment;
+
+/*
+ * Greedy assignment of num_tensors tensors (tensor_elems[i] elements each, in model order) to
+ * shard_factor ranks: tensors are visited in order and each goes to the rank that holds the fewest
+ * elements so far, the lowest such rank on a tie (the paper names only "a greedy algorithm to
+ * balance GPU memory usage"; this is the reading taken).  Host only, pure.
+ * owner: host out [num_tensors].  Errors: AMSP_EINVAL (shard_factor == 0), AMSP_ENULL.
+ */
+int amsp_partition_tensors(const uint64_t *tensor_elems, uint32_t num_tensors, uint32_t shard_factor,
+                           uint32_t *owner);
+
+/*
+ * The segments of `rank` under `owner`: its tensors in model order, flat neighbours merged, local
+ * offsets back to back.  segments: host out [capacity] or NULL to only count.  *num_segments and
+ * *local_elems (the rank's shard size) are always written; AMSP_EINVAL if capacity is too small.
+ */
+int amsp_owned_segments(const uint64_t *tensor_elems, const uint32_t *owner, uint32_t num_tensors,
+                        uint32_t rank, amsp_segment *segments, uint32_t capacity,
+                        uint32_t *num_segments, uint64_t *local_elems);
+
+/*
+ * Steps 2 and 1+3+4 over a segment list: as amsp_grad_sqnorm / amsp_adamw_step_shard, one launch
+ * per segment in list order ("select": only owned elements are read; "drop": nothing else is touched).
+ *   partials_flat    host array of k device pointers, each bf16[flat_elems] (flat whole-model
+ *                    gradient buffers: one all-reduced buffer, k = 1, or k partial ones)
+ *   segments         host array [num_segments]; each must lie inside [0, flat_elems) and
+ *                    [0, local_elems), else AMSP_EINVAL and nothing is enqueued
+ *   master_local ... device fp32[local_elems], updated in place
+ *   param_bf16_flat  device bf16[flat_elems] or NULL: the updated parameters land at their flat
+ *                    positions, ready for the per-tensor Broadcast of Section IV-C.2
+ * The squared norm is accumulated in segment order (accumulate = 0 overwrites first).
+ */
+int amsp_grad_sqnorm_segments(const uint16_t *const *partials_flat, uint32_t k, uint64_t flat_elems,
+                              const amsp_segment *segments, uint32_t num_segments,
+                              double *d_sqnorm, int accumulate,
+                              void *workspace, size_t workspace_bytes, void *stream);
+int amsp_adamw_step_segments(const uint16_t *const *partials_flat, uint32_t k, uint64_t flat_elems,
+                             const amsp_segment *segments, uint32_t num_segments, uint64_t local_elems,
+                             float *master_local, float *exp_avg_local, float *exp_avg_sq_local,
+                             uint16_t *param_bf16_flat, const amsp_adamw_hparams *hp, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -172,3 +172,48 @@ def step(partials, p, m, v, *, lr, beta1, beta2, eps, weight_decay, step, max_no
     p32 = round_f32(p1)
     return dict(G=G, sqnorm=S, scale=scale, p=p1, m=m1, v=v1, p_f32=p32, m_f32=round_f32(m1),
                 v_f32=round_f32(v1), p_bf16=cast(p32, threads))
+
+
+# --------------------------------------------------------------------------- inter-tensor shards
+# Section IV-C.2, second scheme: every parameter tensor goes, whole, with its optimizer states,
+# to one rank, "using a greedy algorithm to balance GPU memory usage"; after the gradient
+# AllReduce a rank keeps ("selects") the gradients of the tensors it owns and drops the rest.
+# The paper does not spell the greedy rule out; the reading taken here: tensors are visited in
+# model order and each goes to the rank that holds the fewest elements so far, the lowest such
+# rank on a tie.
+
+def partition_tensors(sizes, shard_factor: int):
+    """owner[i] for every tensor, by the greedy rule above.  Pure integers."""
+    load = [0] * shard_factor
+    owner = []
+    for sz in sizes:
+        r = min(range(shard_factor), key=lambda q: (load[q], q))
+        owner.append(r)
+        load[r] += int(sz)
+    return owner
+
+
+def owned_segments(sizes, owner, rank: int):
+    """Rank's shard as a list of (flat_offset, local_offset, length): its tensors in model order,
+    neighbours in the flat buffer merged, stored back to back in the rank's compact OS buffers.
+    Empty tensors contribute nothing."""
+    segs = []
+    flat = 0
+    local = 0
+    for sz, o in zip(sizes, owner):
+        sz = int(sz)
+        if o == rank and sz > 0:
+            if segs and segs[-1][0] + segs[-1][2] == flat:
+                segs[-1] = (segs[-1][0], segs[-1][1], segs[-1][2] + sz)
+            else:
+                segs.append((flat, local, sz))
+            local += sz
+        flat += sz
+    return segs
+
+
+def select(flat_array: np.ndarray, segments) -> np.ndarray:
+    """The owned elements of a flat (whole-model) array, in compact order: "select & drop"."""
+    if not segments:
+        return flat_array[:0].copy()
+    return np.concatenate([flat_array[f:f + n] for f, _, n in segments])

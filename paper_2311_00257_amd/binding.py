@@ -19,14 +19,19 @@ AMSP_OK, AMSP_EINVAL, AMSP_ENULL, AMSP_EALIGN, AMSP_EWORKSPACE, AMSP_EDEVICE = 0
 AMSP_MAX_K = 32
 
 EXPORTS = ("amsp_status_string", "amsp_workspace_bytes", "amsp_reduce_workspace_bytes", "amsp_shard_range",
-           "amsp_reduce_grad_shard",
-           "amsp_grad_sqnorm", "amsp_adamw_step_shard", "amsp_cast_param_shard")
+           "amsp_reduce_grad_shard", "amsp_grad_sqnorm", "amsp_adamw_step_shard", "amsp_cast_param_shard",
+           "amsp_partition_tensors", "amsp_owned_segments", "amsp_grad_sqnorm_segments",
+           "amsp_adamw_step_segments")
 
 
 class AmspError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
         super().__init__("%s: status %d (%s)" % (where, status, amsp_status_string(status)))
+
+
+class _Segment(ctypes.Structure):
+    _fields_ = [("flat_offset", ctypes.c_uint64), ("local_offset", ctypes.c_uint64), ("length", ctypes.c_uint64)]
 
 
 class _Hparams(ctypes.Structure):
@@ -79,6 +84,13 @@ def load() -> ctypes.CDLL:
         lib.amsp_grad_sqnorm.argtypes = [vp, u32, vp, u64, u64, vp, ci, vp, ctypes.c_size_t, vp]
         lib.amsp_adamw_step_shard.argtypes = [vp, u32, vp, u64, u64, vp, vp, vp, vp, ctypes.POINTER(_Hparams), vp]
         lib.amsp_cast_param_shard.argtypes = [vp, vp, u64, vp]
+        pu64, pu32 = ctypes.POINTER(u64), ctypes.POINTER(u32)
+        lib.amsp_partition_tensors.argtypes = [pu64, u32, u32, pu32]
+        lib.amsp_owned_segments.argtypes = [pu64, pu32, u32, u32, ctypes.POINTER(_Segment), u32, pu32, pu64]
+        lib.amsp_grad_sqnorm_segments.argtypes = [vp, u32, u64, ctypes.POINTER(_Segment), u32, vp, ci, vp,
+                                                  ctypes.c_size_t, vp]
+        lib.amsp_adamw_step_segments.argtypes = [vp, u32, u64, ctypes.POINTER(_Segment), u32, u64, vp, vp, vp, vp,
+                                                 ctypes.POINTER(_Hparams), vp]
         for name in EXPORTS[3:]:
             getattr(lib, name).restype = ci
         _lib = lib
@@ -174,3 +186,57 @@ def amsp_adamw_step_shard(partials, grad_f32, n: int, master, exp_avg, exp_avg_s
 def amsp_cast_param_shard(master, param_bf16_out, n: int, stream=None) -> None:
     _check(load().amsp_cast_param_shard(_ptr(master), _ptr(param_bf16_out), n, _stream(stream)),
            "amsp_cast_param_shard")
+
+
+# ------------------------------------------------------------------ inter-tensor shards
+def _hp_struct(hp: AdamWHparams):
+    return _Hparams(hp.lr, hp.beta1, hp.beta2, hp.eps, hp.weight_decay, hp.step, hp.max_norm, hp.clip_eps,
+                    _ptr(hp.d_total_sqnorm), hp.grad_scale)
+
+
+def _segments(segments):
+    arr = (_Segment * max(len(segments), 1))(*[_Segment(*map(int, s)) for s in segments])
+    return arr, len(segments)
+
+
+def amsp_partition_tensors(tensor_elems: Sequence[int], shard_factor: int):
+    """owner index per tensor (list of int)."""
+    n = len(tensor_elems)
+    sizes = (ctypes.c_uint64 * max(n, 1))(*tensor_elems)
+    owner = (ctypes.c_uint32 * max(n, 1))()
+    _check(load().amsp_partition_tensors(sizes, n, shard_factor, owner), "amsp_partition_tensors")
+    return list(owner[:n])
+
+
+def amsp_owned_segments(tensor_elems: Sequence[int], owner: Sequence[int], rank: int):
+    """([(flat_offset, local_offset, length), ...], local_elems) of `rank`."""
+    n = len(tensor_elems)
+    sizes = (ctypes.c_uint64 * max(n, 1))(*tensor_elems)
+    own = (ctypes.c_uint32 * max(n, 1))(*owner)
+    count, local = ctypes.c_uint32(), ctypes.c_uint64()
+    _check(load().amsp_owned_segments(sizes, own, n, rank, None, 0, ctypes.byref(count), ctypes.byref(local)),
+           "amsp_owned_segments")
+    segs = (_Segment * max(count.value, 1))()
+    _check(load().amsp_owned_segments(sizes, own, n, rank, segs, count.value, ctypes.byref(count),
+                                      ctypes.byref(local)), "amsp_owned_segments")
+    return [(s.flat_offset, s.local_offset, s.length) for s in segs[:count.value]], local.value
+
+
+def amsp_grad_sqnorm_segments(partials_flat, flat_elems: int, segments, d_sqnorm, workspace,
+                              accumulate: bool = False, stream=None, workspace_bytes: Optional[int] = None) -> None:
+    arr, k = _partials(partials_flat)
+    segs, ns = _segments(segments)
+    _check(load().amsp_grad_sqnorm_segments(arr, k, flat_elems, segs, ns, _ptr(d_sqnorm), int(accumulate),
+                                            _ptr(workspace), _nbytes(workspace, workspace_bytes), _stream(stream)),
+           "amsp_grad_sqnorm_segments")
+
+
+def amsp_adamw_step_segments(partials_flat, flat_elems: int, segments, local_elems: int, master_local,
+                             exp_avg_local, exp_avg_sq_local, param_bf16_flat, hp: AdamWHparams, stream=None) -> None:
+    arr, k = _partials(partials_flat)
+    segs, ns = _segments(segments)
+    c = _hp_struct(hp) if hp is not None else None
+    _check(load().amsp_adamw_step_segments(arr, k, flat_elems, segs, ns, local_elems, _ptr(master_local),
+                                           _ptr(exp_avg_local), _ptr(exp_avg_sq_local), _ptr(param_bf16_flat),
+                                           ctypes.byref(c) if c is not None else None, _stream(stream)),
+           "amsp_adamw_step_segments")

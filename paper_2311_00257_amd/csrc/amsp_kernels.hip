@@ -788,4 +788,104 @@ int amsp_adamw_step_shard(const uint16_t *const *partials, uint32_t k, const flo
     });
 }
 
+// ---------------------------------------------------------------- inter-tensor shards
+int amsp_partition_tensors(const uint64_t *tensor_elems, uint32_t num_tensors, uint32_t shard_factor,
+                           uint32_t *owner) {
+    if (shard_factor == 0) return AMSP_EINVAL;
+    if (num_tensors == 0) return AMSP_OK;
+    if (tensor_elems == nullptr || owner == nullptr) return AMSP_ENULL;
+    uint64_t *load = static_cast<uint64_t *>(calloc(shard_factor, sizeof(uint64_t)));
+    if (load == nullptr) return AMSP_EINVAL;
+    for (uint32_t t = 0; t < num_tensors; ++t) {
+        uint32_t best = 0;
+        for (uint32_t r = 1; r < shard_factor; ++r)
+            if (load[r] < load[best]) best = r;   // strict: the lowest rank wins a tie
+        owner[t] = best;
+        load[best] += tensor_elems[t];
+    }
+    free(load);
+    return AMSP_OK;
+}
+
+int amsp_owned_segments(const uint64_t *tensor_elems, const uint32_t *owner, uint32_t num_tensors, uint32_t rank,
+                        amsp_segment *segments, uint32_t capacity, uint32_t *num_segments, uint64_t *local_elems) {
+    if (num_segments == nullptr || local_elems == nullptr) return AMSP_ENULL;
+    if (num_tensors > 0 && (tensor_elems == nullptr || owner == nullptr)) return AMSP_ENULL;
+    uint32_t count = 0;
+    uint64_t flat = 0, local = 0, last_end = 0;
+    for (uint32_t t = 0; t < num_tensors; ++t) {
+        const uint64_t sz = tensor_elems[t];
+        if (owner[t] == rank && sz > 0) {
+            if (count > 0 && last_end == flat) {
+                if (segments != nullptr && count <= capacity) segments[count - 1].length += sz;
+            } else {
+                if (segments != nullptr && count < capacity) segments[count] = amsp_segment{flat, local, sz};
+                ++count;
+            }
+            local += sz;
+            last_end = flat + sz;
+        }
+        flat += sz;
+    }
+    *num_segments = count;
+    *local_elems = local;
+    return (segments != nullptr && count > capacity) ? AMSP_EINVAL : AMSP_OK;
+}
+
+static int check_segments(const amsp_segment *segments, uint32_t num_segments, uint64_t flat_elems,
+                          uint64_t local_elems) {
+    if (num_segments > 0 && segments == nullptr) return AMSP_ENULL;
+    for (uint32_t i = 0; i < num_segments; ++i) {
+        const amsp_segment &g = segments[i];
+        if (g.length > flat_elems || g.flat_offset > flat_elems - g.length) return AMSP_EINVAL;
+        if (g.length > local_elems || g.local_offset > local_elems - g.length) return AMSP_EINVAL;
+    }
+    return AMSP_OK;
+}
+
+int amsp_grad_sqnorm_segments(const uint16_t *const *partials_flat, uint32_t k, uint64_t flat_elems,
+                              const amsp_segment *segments, uint32_t num_segments, double *d_sqnorm, int accumulate,
+                              void *workspace, size_t workspace_bytes, void *stream) {
+    PartialPtrs pp;
+    int rc = check_partials(partials_flat, k, pp);
+    if (rc != AMSP_OK) return rc;
+    rc = check_segments(segments, num_segments, flat_elems, UINT64_MAX);
+    if (rc != AMSP_OK) return rc;
+    bool first = true;
+    for (uint32_t i = 0; i < num_segments; ++i) {
+        if (segments[i].length == 0) continue;
+        PartialPtrs q = offset_partials(pp, k, segments[i].flat_offset);
+        rc = amsp_grad_sqnorm(q.p, k, nullptr, segments[i].length, 0, d_sqnorm, (accumulate || !first) ? 1 : 0,
+                              workspace, workspace_bytes, stream);
+        if (rc != AMSP_OK) return rc;
+        first = false;
+    }
+    if (first)   // nothing owned: same contract as n == 0
+        return amsp_grad_sqnorm(pp.p, k, nullptr, 0, 0, d_sqnorm, accumulate, workspace, workspace_bytes, stream);
+    return AMSP_OK;
+}
+
+int amsp_adamw_step_segments(const uint16_t *const *partials_flat, uint32_t k, uint64_t flat_elems,
+                             const amsp_segment *segments, uint32_t num_segments, uint64_t local_elems,
+                             float *master_local, float *exp_avg_local, float *exp_avg_sq_local,
+                             uint16_t *param_bf16_flat, const amsp_adamw_hparams *hp, void *stream) {
+    PartialPtrs pp;
+    int rc = check_partials(partials_flat, k, pp);
+    if (rc != AMSP_OK) return rc;
+    rc = check_segments(segments, num_segments, flat_elems, local_elems);
+    if (rc != AMSP_OK) return rc;
+    if (hp == nullptr) return AMSP_ENULL;
+    for (uint32_t i = 0; i < num_segments; ++i) {
+        const amsp_segment &g = segments[i];
+        if (g.length == 0) continue;
+        if (master_local == nullptr || exp_avg_local == nullptr || exp_avg_sq_local == nullptr) return AMSP_ENULL;
+        PartialPtrs q = offset_partials(pp, k, g.flat_offset);
+        rc = amsp_adamw_step_shard(q.p, k, nullptr, g.length, 0, master_local + g.local_offset,
+                                   exp_avg_local + g.local_offset, exp_avg_sq_local + g.local_offset,
+                                   param_bf16_flat ? param_bf16_flat + g.flat_offset : nullptr, hp, stream);
+        if (rc != AMSP_OK) return rc;
+    }
+    return AMSP_OK;
+}
+
 }  // extern "C"

@@ -20,6 +20,18 @@ def llama_param_count(layers: int, hidden: int, ffn: int, vocab: int) -> int:
     return 2 * vocab * hidden + layers * per_layer + hidden
 
 
+def llama_tensor_sizes(layers: int, hidden: int, ffn: int, vocab: int):
+    """Element counts of the model's tensors in flat (model) order: embedding; per layer the
+    attention norm gain, four attention matrices, the MLP norm gain and three MLP matrices; the
+    final norm gain; the output head.  Their sum is llama_param_count."""
+    sizes = [vocab * hidden]
+    for _ in range(layers):
+        sizes += [hidden, hidden * hidden, hidden * hidden, hidden * hidden, hidden * hidden,
+                  hidden, hidden * ffn, hidden * ffn, ffn * hidden]
+    sizes += [hidden, vocab * hidden]
+    return sizes
+
+
 @dataclasses.dataclass(frozen=True)
 class Workload:
     config_id: int
@@ -35,6 +47,7 @@ class Workload:
     step: int
     bucket_elems: int = 0      # 0 = the whole shard in one launch
     drop_tail: int = 0         # elements cut from the end of the shard (ragged length)
+    inter_tensor: bool = False  # shard = whole tensors chosen greedily (Section IV-C.2), not a flat range
     sigma_param: float = 0.02
     sigma_m: float = 1e-4
     scale_v: float = 1e-6
@@ -53,6 +66,10 @@ class Workload:
     @property
     def total_elems(self) -> int:
         return llama_param_count(self.layers, self.hidden, self.ffn, self.vocab)
+
+    @property
+    def tensor_sizes(self):
+        return llama_tensor_sizes(self.layers, self.hidden, self.ffn, self.vocab)
 
     def key(self, tensor_id: int) -> int:
         return synth.stream_key(self.seed, tensor_id)
@@ -74,6 +91,9 @@ WORKLOADS = (
     Workload(3, "llama-13b/s16r7/k16", 40, 5120, 13824, 32000, 16, 7, 16, 1e-2, 10),
     Workload(4, "llama-30b/s8r5/k8/bucketed", 60, 6656, 17920, 32000, 8, 5, 8, 1e-3, 10,
              bucket_elems=25_000_001, drop_tail=3),
+    # beyond the five listed workloads: the inter-tensor scheme the paper adopts.  One all-reduced flat
+    # bf16 gradient buffer of the whole model (k = 1), the rank's whole tensors selected from it.
+    Workload(5, "llama-7b/inter-tensor/s8r3/k1", 32, 4096, 11008, 32000, 8, 3, 1, 1e-3, 10, inter_tensor=True),
 )
 
 

@@ -120,6 +120,41 @@ def test_argument_validation_without_device():
     B.amsp_adamw_step_shard([A], None, 0, 0, 0, 0, 0, hp, stream=0)      # n == 0
 
 
+def test_partition_and_segments_bit_exact_against_oracle():
+    rng = np.random.default_rng(3)
+    cases = [(w.tensor_sizes, s) for w in workloads.WORKLOADS for s in (1, 3, 8, 16)]
+    cases += [([int(x) for x in rng.integers(0, 10**9, int(rng.integers(0, 300)))], int(rng.integers(1, 40)))
+              for _ in range(50)]
+    for sizes, s in cases:
+        owner = B.amsp_partition_tensors(sizes, s)
+        assert owner == oracle.partition_tensors(sizes, s)
+        for r in sorted({0, s - 1, s // 2}):
+            segs, local = B.amsp_owned_segments(sizes, owner, r)
+            assert segs == oracle.owned_segments(sizes, owner, r)
+            assert local == sum(n for _, _, n in segs)
+    with pytest.raises(B.AmspError) as ei:
+        B.amsp_partition_tensors([1, 2], 0)
+    assert ei.value.status == B.AMSP_EINVAL
+
+
+def test_segment_validation_without_device():
+    A = 0x10000
+    hp = B.AdamWHparams(**HP)
+    ws = B.amsp_workspace_bytes()
+    # a segment that runs past the flat buffer or past the local buffers is refused before any launch
+    for segs in ([(90, 0, 20)], [(0, 90, 20)], [(2**63, 0, 2**63)], [(0, 0, 10), (95, 10, 10)]):
+        with pytest.raises(B.AmspError) as ei:
+            B.amsp_adamw_step_segments([A], 100, segs, 100, A, A, A, A, hp, stream=0)
+        assert ei.value.status == B.AMSP_EINVAL
+    with pytest.raises(B.AmspError) as ei:
+        B.amsp_grad_sqnorm_segments([A], 100, [(95, 0, 10)], A, A, stream=0, workspace_bytes=ws)
+    assert ei.value.status == B.AMSP_EINVAL
+    with pytest.raises(B.AmspError) as ei:
+        B.amsp_adamw_step_segments([A], 100, [(0, 0, 10)], 100, 0, A, A, A, hp, stream=0)
+    assert ei.value.status == B.AMSP_ENULL
+    B.amsp_adamw_step_segments([A], 100, [], 0, 0, 0, 0, 0, hp, stream=0)          # owns nothing: fine
+
+
 def test_product_package_never_imports_the_oracle():
     pkg = os.path.join(ROOT, "paper_2311_00257_amd")
     for dirpath, _, files in os.walk(pkg):

@@ -122,3 +122,82 @@ def test_workload4_llama30b_bucketed_full():
 
 def test_workload2_llama7b_full_replica_full():
     _run_fullsize(2)
+
+
+def test_workload5_llama7b_inter_tensor_full():
+    """LLaMA-7B, inter-tensor shards at factor 8: rank 3 selects its 31 segments (843 M elements) from
+    one all-reduced flat bf16 gradient buffer of the whole model."""
+    import torch
+
+    from paper_2311_00257_amd import binding as B
+    from paper_2311_00257_amd import synth_device
+
+    w = workloads.get(5)
+    sizes, total = w.tensor_sizes, w.total_elems
+    owner = B.amsp_partition_tensors(sizes, w.shard_factor)
+    assert owner == oracle.partition_tensors(sizes, w.shard_factor)
+    segs, local = B.amsp_owned_segments(sizes, owner, w.rank)
+    assert segs == oracle.owned_segments(sizes, owner, w.rank)
+    torch.cuda.empty_cache()
+    need = total * (2 * w.k + 2) + local * 12 + (1 << 30)
+    free, _ = torch.cuda.mem_get_info()
+    if free < need:
+        pytest.skip("needs %.0f GB of device memory, %.0f free" % (need / 1e9, free / 1e9))
+    print("workload 5 (%s): %d segments, %d of %d elements" % (w.name, len(segs), local, total), flush=True)
+
+    parts = []
+    for j in range(w.k):
+        t = torch.empty(total, dtype=torch.int16, device="cuda")
+        synth_device.fill_bf16(t, w.key(synth.TENSOR_PARTIAL0 + j), 0, w.sigma_grad)
+        parts.append(t)
+    dp = torch.empty(local, dtype=torch.float32, device="cuda")
+    dm = torch.empty(local, dtype=torch.float32, device="cuda")
+    dv = torch.empty(local, dtype=torch.float32, device="cuda")
+    for f, l, n in segs:                                    # compact states: element values follow the flat index
+        synth_device.fill_f32(dp[l:l + n], w.key(synth.TENSOR_MASTER), f, w.sigma_param)
+        synth_device.fill_f32(dm[l:l + n], w.key(synth.TENSOR_EXP_AVG), f, w.sigma_m)
+        synth_device.fill_f32(dv[l:l + n], w.key(synth.TENSOR_EXP_AVG_SQ), f, w.scale_v, absolute=True)
+    out = torch.full((total,), 0x5A5A, dtype=torch.int16, device="cuda")
+    ws = torch.empty(B.amsp_workspace_bytes() // 8, dtype=torch.float64, device="cuda")
+    d_s = torch.zeros(1, dtype=torch.float64, device="cuda")
+    hp = H.hparams_of(w)
+    B.amsp_grad_sqnorm_segments(parts, total, segs, d_s, ws)
+    B.amsp_adamw_step_segments(parts, total, segs, local, dp, dm, dv, out, B.AdamWHparams(d_total_sqnorm=d_s, **hp))
+    torch.cuda.synchronize()
+    S_gpu = float(d_s.item())
+
+    S = 0.0
+    for f, l, n in segs:                                    # the oracle's norm over the selected segments
+        S += _oracle_sqnorm_streamed(w, f, n)
+    assert abs(S_gpu - S) <= H.REL_TOL * S, (S_gpu, S)
+    scale = oracle.clip_scale(S, hp["max_norm"], hp["clip_eps"])
+    assert scale < 1.0
+
+    worst = dict(max_p=0.0, max_m=0.0, max_v=0.0, mismatches=0, elements=0)
+    rng = np.random.default_rng(5)
+    width = 1 << 15
+    for f, l, n in segs:                                    # one window at the start, end and a random place of every segment
+        wd = min(width, n)
+        for a in sorted({0, n - wd, int(rng.integers(0, n - wd + 1))}):
+            inp = H.host_inputs(w, f + a, wd, threads=THREADS)
+            G = oracle.reduce(inp.partials, threads=THREADS)
+            p1, m1, v1 = oracle.adamw(G, scale, inp.p, inp.m, inp.v, lr=hp["lr"], beta1=hp["beta1"],
+                                      beta2=hp["beta2"], eps=hp["eps"], weight_decay=hp["weight_decay"],
+                                      step=hp["step"], threads=THREADS)
+            ref = dict(G=G, scale=scale, p=p1, m=m1, v=v1, p_bf16=oracle.cast(oracle.round_f32(p1)))
+            sl = slice(l + a, l + a + wd)
+            gp = dp[sl].cpu().numpy()
+            st = H.check_state(gp, dm[sl].cpu().numpy(), dv[sl].cpu().numpy(), ref, inp.p, inp.m, hp)
+            bits = H.dev_bits(out[f + a:f + a + wd])
+            worst["mismatches"] += H.check_bf16(bits, ref)
+            assert np.array_equal(bits, oracle.cast(gp))
+            for key in ("max_p", "max_m", "max_v"):
+                worst[key] = max(worst[key], st[key])
+            worst["elements"] += wd
+    assert worst["mismatches"] <= max(3, 1e-4 * worst["elements"])
+    # drop: the elements just outside every segment still hold the fill pattern
+    for f, l, n in segs:
+        for lo, hi in ((max(0, f - 64), f), (f + n, min(total, f + n + 64))):
+            if hi > lo:
+                assert bool(torch.all(out[lo:hi] == 0x5A5A))
+    print("  sqnorm gpu %.12g oracle %.12g scale %.6g; sampled %s" % (S_gpu, S, scale, worst), flush=True)

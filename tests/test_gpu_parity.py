@@ -401,3 +401,38 @@ def test_error_paths_enqueue_nothing(B, torch_mod):
     assert ei.value.status == B.AMSP_ENULL
     _sync()
     assert torch.all(p == 1.0) and torch.all(m == 0.0)
+
+
+# ------------------------------------------------------------------ inter-tensor shards (select & drop)
+@pytest.mark.parametrize("s,k", [(3, 2), (4, 1), (1, 2)])
+def test_inter_tensor_step_on_tiny_llama(B, torch_mod, s, k):
+    """The tiny model's 21 tensors assigned whole to s ranks; every rank selects its tensors'
+    gradients from the flat buffers, updates its compact optimizer states and writes the bf16
+    parameters back to their flat positions; nothing it does not own is touched."""
+    torch = torch_mod
+    w = workloads.get(0)
+    sizes, total = w.tensor_sizes, w.total_elems
+    owner = B.amsp_partition_tensors(sizes, s)
+    assert owner == oracle.partition_tensors(sizes, s)
+    elem_owner = np.repeat(np.array(owner), sizes)
+    flat = H.host_inputs(w, 0, total, k=k)
+    dparts = [H.to_dev_bf16(g) for g in flat.partials]
+    ws = torch.empty(B.amsp_workspace_bytes() // 8, dtype=torch.float64, device="cuda")
+    hp = H.hparams_of(w, max_norm=0.05)
+    for rank in range(s):
+        segs, local = B.amsp_owned_segments(sizes, owner, rank)
+        assert segs == oracle.owned_segments(sizes, owner, rank)
+        inp = H.HostInputs([oracle.select(g, segs) for g in flat.partials], oracle.select(flat.p, segs),
+                           oracle.select(flat.m, segs), oracle.select(flat.v, segs))
+        assert inp.p.size == local
+        ref = _oracle_step(inp, hp)
+        dp, dm, dv = H.to_dev_f32(inp.p), H.to_dev_f32(inp.m), H.to_dev_f32(inp.v)
+        out = torch.full((total,), 0x5A5A, dtype=torch.int16, device="cuda")
+        d_s = torch.zeros(1, dtype=torch.float64, device="cuda")
+        B.amsp_grad_sqnorm_segments(dparts, total, segs, d_s, ws)
+        B.amsp_adamw_step_segments(dparts, total, segs, local, dp, dm, dv, out,
+                                   B.AdamWHparams(d_total_sqnorm=d_s, **hp))
+        out_bits = H.dev_bits(out)
+        got = (dp.cpu().numpy(), dm.cpu().numpy(), dv.cpu().numpy(), oracle.select(out_bits, segs), float(d_s.item()))
+        _check_all(got, ref, inp, hp)
+        assert np.all(out_bits[elem_owner != rank] == 0x5A5A)          # drop: nothing else is written

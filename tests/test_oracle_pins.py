@@ -343,3 +343,74 @@ def test_synth_distribution():
     assert float(np.var(t.astype(np.float64))) == pytest.approx(1.0, abs=2e-3)
     x = synth.fill_f32(synth.stream_key(7, 0), 0, 1 << 20, 1.0)
     assert abs(float(x.mean())) < 5e-3 and float(x.std()) == pytest.approx(1.0, abs=5e-3)
+
+
+# --------------------------------------------------------------------------- inter-tensor shards
+def test_partition_by_hand():
+    # 5,3,3,2,2,1 over two ranks, loads after each step: (5,0) (5,3) (5,6) (7,6) (7,8) (8,8)
+    assert oracle.partition_tensors([5, 3, 3, 2, 2, 1], 2) == [0, 1, 1, 0, 1, 0]
+    assert oracle.partition_tensors([4] * 7, 3) == [0, 1, 2, 0, 1, 2, 0]       # equal sizes: round robin
+    assert oracle.partition_tensors([9, 1, 1, 1], 1) == [0, 0, 0, 0]           # factor 1: Full-Replica
+    assert oracle.partition_tensors([], 4) == []
+    assert oracle.partition_tensors([0, 0, 7], 2) == [0, 0, 0]                 # empty tensors never move the loads
+
+
+def test_partition_balance_bounds():
+    # any list-scheduling assignment obeys max load <= total/s + (1 - 1/s) * largest tensor (Graham),
+    # and on tiny instances stays within (2 - 1/s) of the brute-force optimum
+    import itertools
+
+    rng = np.random.default_rng(8)
+    for _ in range(200):
+        s = int(rng.integers(1, 9))
+        sizes = [int(x) for x in rng.integers(0, 1000, int(rng.integers(1, 60)))]
+        owner = oracle.partition_tensors(sizes, s)
+        assert len(owner) == len(sizes) and all(0 <= o < s for o in owner)
+        loads = [sum(z for z, o in zip(sizes, owner) if o == r) for r in range(s)]
+        assert sum(loads) == sum(sizes)
+        assert max(loads) <= sum(sizes) / s + (1 - 1 / s) * max(sizes) + 1e-9
+    for _ in range(30):
+        s = int(rng.integers(2, 4))
+        sizes = [int(x) for x in rng.integers(1, 50, int(rng.integers(2, 8)))]
+        owner = oracle.partition_tensors(sizes, s)
+        greedy = max(sum(z for z, o in zip(sizes, owner) if o == r) for r in range(s))
+        best = min(max(sum(z for z, o in zip(sizes, asg) if o == r) for r in range(s))
+                   for asg in itertools.product(range(s), repeat=len(sizes)))
+        assert best <= greedy <= (2 - 1 / s) * best
+
+
+def test_partition_llama7b_factor8():
+    w = workloads.get(5)
+    sizes = w.tensor_sizes
+    assert len(sizes) == 291 and sum(sizes) == 6738415616          # 9 tensors per layer + embedding, norm, head
+    owner = oracle.partition_tensors(sizes, 8)
+    loads = [sum(z for z, o in zip(sizes, owner) if o == r) for r in range(8)]
+    assert max(loads) <= sum(sizes) / 8 + max(sizes)
+    assert owner[0] == 0 and owner[1] == 1                          # embedding to rank 0, first norm gain to rank 1
+
+
+def test_owned_segments_and_select():
+    rng = np.random.default_rng(9)
+    sizes = [int(x) for x in rng.integers(0, 40, 50)]
+    s = 4
+    owner = oracle.partition_tensors(sizes, s)
+    total = sum(sizes)
+    elem_owner = np.repeat(np.array(owner), sizes)                  # owner of every flat element
+    flat = np.arange(total, dtype=np.int64) * 10
+    covered = np.zeros(total, dtype=np.int64)
+    for r in range(s):
+        segs = oracle.owned_segments(sizes, owner, r)
+        local = 0
+        prev_end = -1
+        for f, l, n in segs:
+            assert n > 0 and l == local and f > prev_end            # compact, ordered, neighbours merged
+            assert np.all(elem_owner[f:f + n] == r)
+            covered[f:f + n] += 1
+            local += n
+            prev_end = f + n
+        assert local == int(np.sum(elem_owner == r))
+        assert np.array_equal(oracle.select(flat, segs), flat[elem_owner == r])   # select keeps exactly the owned
+    assert np.all(covered == 1)                                     # every element owned exactly once
+    # two owned neighbours become one segment
+    assert oracle.owned_segments([3, 4, 5], [0, 0, 1], 0) == [(0, 0, 7)]
+    assert oracle.owned_segments([3, 4, 5], [0, 1, 0], 0) == [(0, 0, 3), (7, 3, 5)]
