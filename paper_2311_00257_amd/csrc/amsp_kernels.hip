@@ -553,6 +553,39 @@ int add_partial_streams(Stream16 *st, int ns, const PartialPtrs &pp, uint32_t k)
     return ns;
 }
 
+// Block sums of consecutive norm launches (buckets, segments) go side by side into the workspace
+// and are added once, in launch order, by a finishing pass: one finish per ~100 launches instead
+// of one per launch.  Layout: [0, kNormSlots) block sums, then kSliceBlocks stage sums.
+constexpr size_t kNormSlots = 64 * 1024;
+
+int finish_sums(hipStream_t hs, double *sums, uint64_t count, double *stage, double *out, int accumulate);
+
+struct NormBatch {
+    hipStream_t hs;
+    double *sums;
+    double *out;
+    size_t used;
+    bool add;     // whether the next finish adds to *out
+
+    int flush() {
+        if (used == 0) return AMSP_OK;
+        int rc = finish_sums(hs, sums, used, sums + kNormSlots, out, add ? 1 : 0);
+        used = 0;
+        add = true;
+        return rc;
+    }
+    // Room for `blocks` more sums; returns where they go, flushing first when the workspace is full.
+    int reserve(int blocks, double **where) {
+        if (used + (size_t)blocks > kNormSlots) {
+            int rc = flush();
+            if (rc != AMSP_OK) return rc;
+        }
+        *where = sums + used;
+        used += (size_t)blocks;
+        return AMSP_OK;
+    }
+};
+
 #define AMSP_DISPATCH_K(k, CALL)                 \
     switch (k) {                                 \
         case 1: { constexpr int KK = 1; CALL; } break;   \
@@ -562,6 +595,46 @@ int add_partial_streams(Stream16 *st, int ns, const PartialPtrs &pp, uint32_t k)
         case 16: { constexpr int KK = 16; CALL; } break; \
         default: { constexpr int KK = -1; CALL; } break; \
     }
+
+// Adds `count` block sums in index order into *out: one block when they are few, otherwise
+// kSliceBlocks blocks each add a contiguous slice into `stage` and one block adds those.
+int finish_sums(hipStream_t hs, double *sums, uint64_t count, double *stage, double *out, int accumulate) {
+    const double *src = sums;
+    int n = (int)count;
+    if (count > (uint64_t)kNormBlocks) {
+        const uint64_t slice = (count + kSliceBlocks - 1) / kSliceBlocks;
+        n = (int)((count + slice - 1) / slice);
+        hipLaunchKernelGGL(sum_slices_kernel, dim3(n), dim3(kThreads), 0, hs, sums, count, slice, stage);
+        if (launched() != AMSP_OK) return AMSP_EDEVICE;
+        src = stage;
+    }
+    hipLaunchKernelGGL(sqnorm_finish_kernel, dim3(1), dim3(kThreads), 0, hs, src, n, out, accumulate);
+    return launched();
+}
+
+// One norm launch over `len` elements starting at the given pointers, its block sums appended to the batch.
+int norm_launch(NormBatch &batch, const PartialPtrs &q, uint32_t k, const float *gf, uint64_t len) {
+    Stream16 st[AMSP_MAX_K + 1];
+    int ns = add_partial_streams(st, 0, q, k);
+    if (k == 0) st[ns++] = Stream16{gf, 4};
+    // 16-byte accesses in every case: 8 bf16 elements per lane, or 4 of the fp32 gradient
+    const int vec = k == 0 ? 4 : kVecNorm;
+    Span s = make_span(len, st, ns, vec);
+    const int grid = norm_grid(s);
+    double *block_sums = nullptr;
+    int rc = batch.reserve(grid, &block_sums);
+    if (rc != AMSP_OK) return rc;
+    hipStream_t hs = batch.hs;
+#define AMSP_LAUNCH_SQNORM(KV, V)                                                                     \
+    hipLaunchKernelGGL((sqnorm_kernel<KV, V>), dim3(grid), dim3(kNormThreads), 0, hs, q, (int)k, gf, block_sums, s)
+    if (k == 0) {
+        AMSP_LAUNCH_SQNORM(0, 4);
+    } else {
+        AMSP_DISPATCH_K(k, AMSP_LAUNCH_SQNORM(KK, kVecNorm));
+    }
+#undef AMSP_LAUNCH_SQNORM
+    return launched();
+}
 
 }  // namespace
 
@@ -580,7 +653,7 @@ const char *amsp_status_string(int status) {
     }
 }
 
-size_t amsp_workspace_bytes(void) { return (size_t)kNormBlocks * sizeof(double); }
+size_t amsp_workspace_bytes(void) { return (kNormSlots + kSliceBlocks) * sizeof(double); }
 
 int amsp_shard_range(uint64_t total_elems, uint32_t shard_factor, uint32_t rank, uint64_t *begin, uint64_t *end) {
     if (begin == nullptr || end == nullptr) return AMSP_ENULL;
@@ -652,20 +725,7 @@ int amsp_reduce_grad_shard(const uint16_t *const *partials, uint32_t k, uint64_t
         if (launched() != AMSP_OK) return (int)AMSP_EDEVICE;
         const int acc = (sqnorm_accumulate || !first) ? 1 : 0;
         first = false;
-        const double *sums = block_sums;
-        int count = (int)blocks;
-        if (blocks > (uint64_t)kNormBlocks) {
-            // two stages: kSliceBlocks blocks each add one contiguous slice, then one block adds those
-            double *slice_sums = block_sums + blocks;
-            const uint64_t slice = (blocks + kSliceBlocks - 1) / kSliceBlocks;
-            count = (int)((blocks + slice - 1) / slice);
-            hipLaunchKernelGGL(sum_slices_kernel, dim3(count), dim3(kThreads), 0, hs, block_sums, blocks, slice,
-                               slice_sums);
-            if (launched() != AMSP_OK) return (int)AMSP_EDEVICE;
-            sums = slice_sums;
-        }
-        hipLaunchKernelGGL(sqnorm_finish_kernel, dim3(1), dim3(kThreads), 0, hs, sums, count, d_sqnorm, acc);
-        return launched();
+        return finish_sums(hs, block_sums, blocks, block_sums + blocks, d_sqnorm, acc);
     });
 }
 
@@ -683,44 +743,17 @@ int amsp_grad_sqnorm(const uint16_t *const *partials, uint32_t k, const float *g
     if (d_sqnorm == nullptr || workspace == nullptr) return AMSP_ENULL;
     if (misaligned(d_sqnorm, 8) || misaligned(workspace, 8)) return AMSP_EALIGN;
     if (workspace_bytes < amsp_workspace_bytes()) return AMSP_EWORKSPACE;
-    double *block_sums = static_cast<double *>(workspace);
-    hipStream_t hs = (hipStream_t)stream;
+    NormBatch batch{(hipStream_t)stream, static_cast<double *>(workspace), d_sqnorm, 0, accumulate != 0};
     clear_stale_error();
     if (n == 0) {
-        if (!accumulate) {
-            hipLaunchKernelGGL(sqnorm_finish_kernel, dim3(1), dim3(kThreads), 0, hs, block_sums, 0, d_sqnorm, 0);
-            return launched();
-        }
+        if (!accumulate) return finish_sums(batch.hs, batch.sums, 0, batch.sums + kNormSlots, d_sqnorm, 0);
         return AMSP_OK;
     }
-    bool first = true;
-    return for_buckets(n, bucket_elems, [&](uint64_t off, uint64_t len) {
-        PartialPtrs q = offset_partials(pp, k, off);
-        Stream16 st[AMSP_MAX_K + 1];
-        int ns = add_partial_streams(st, 0, q, k);
-        const float *gf = nullptr;
-        if (k == 0) {
-            gf = grad_f32 + off;
-            st[ns++] = Stream16{gf, 4};
-        }
-        // 16-byte accesses in every case: 8 bf16 elements per lane, or 4 of the fp32 gradient
-        const int vec = k == 0 ? 4 : kVecNorm;
-        Span s = make_span(len, st, ns, vec);
-        const int grid = norm_grid(s);
-#define AMSP_LAUNCH_SQNORM(KV, V)                                                                     \
-        hipLaunchKernelGGL((sqnorm_kernel<KV, V>), dim3(grid), dim3(kNormThreads), 0, hs, q, (int)k, gf, block_sums, s)
-        if (k == 0) {
-            AMSP_LAUNCH_SQNORM(0, 4);
-        } else {
-            AMSP_DISPATCH_K(k, AMSP_LAUNCH_SQNORM(KK, kVecNorm));
-        }
-#undef AMSP_LAUNCH_SQNORM
-        if (launched() != AMSP_OK) return (int)AMSP_EDEVICE;
-        const int acc = (accumulate || !first) ? 1 : 0;
-        first = false;
-        hipLaunchKernelGGL(sqnorm_finish_kernel, dim3(1), dim3(kThreads), 0, hs, block_sums, grid, d_sqnorm, acc);
-        return launched();
+    int rc = for_buckets(n, bucket_elems, [&](uint64_t off, uint64_t len) {
+        return norm_launch(batch, offset_partials(pp, k, off), k, k == 0 ? grad_f32 + off : nullptr, len);
     });
+    if (rc != AMSP_OK) return rc;
+    return batch.flush();
 }
 
 int amsp_adamw_step_shard(const uint16_t *const *partials, uint32_t k, const float *grad_f32, uint64_t n,
@@ -851,18 +884,23 @@ int amsp_grad_sqnorm_segments(const uint16_t *const *partials_flat, uint32_t k, 
     if (rc != AMSP_OK) return rc;
     rc = check_segments(segments, num_segments, flat_elems, UINT64_MAX);
     if (rc != AMSP_OK) return rc;
-    bool first = true;
+    if (d_sqnorm == nullptr || workspace == nullptr) return AMSP_ENULL;
+    if (misaligned(d_sqnorm, 8) || misaligned(workspace, 8)) return AMSP_EALIGN;
+    if (workspace_bytes < amsp_workspace_bytes()) return AMSP_EWORKSPACE;
+    NormBatch batch{(hipStream_t)stream, static_cast<double *>(workspace), d_sqnorm, 0, accumulate != 0};
+    clear_stale_error();
+    bool any = false;
     for (uint32_t i = 0; i < num_segments; ++i) {
         if (segments[i].length == 0) continue;
-        PartialPtrs q = offset_partials(pp, k, segments[i].flat_offset);
-        rc = amsp_grad_sqnorm(q.p, k, nullptr, segments[i].length, 0, d_sqnorm, (accumulate || !first) ? 1 : 0,
-                              workspace, workspace_bytes, stream);
+        rc = norm_launch(batch, offset_partials(pp, k, segments[i].flat_offset), k, nullptr, segments[i].length);
         if (rc != AMSP_OK) return rc;
-        first = false;
+        any = true;
     }
-    if (first)   // nothing owned: same contract as n == 0
-        return amsp_grad_sqnorm(pp.p, k, nullptr, 0, 0, d_sqnorm, accumulate, workspace, workspace_bytes, stream);
-    return AMSP_OK;
+    if (!any) {   // nothing owned: same contract as n == 0
+        if (!accumulate) return finish_sums(batch.hs, batch.sums, 0, batch.sums + kNormSlots, d_sqnorm, 0);
+        return AMSP_OK;
+    }
+    return batch.flush();
 }
 
 int amsp_adamw_step_segments(const uint16_t *const *partials_flat, uint32_t k, uint64_t flat_elems,
