@@ -249,6 +249,24 @@ def main():
                       "bytes_per_element": w.bytes_per_elem_norm()},
         "whole_step_GBps": (w.bytes_per_elem_fused() + w.bytes_per_elem_norm()) * n / (ms_per_step * 1e-3) / 1e9,
     }
+    if w.inter_tensor:
+        # the FP8 form of step 4 for inter-tensor shards: per-tensor amax (4 B/elt read), scale, E4M3 codes
+        # (4 B/elt read + 1 written), timed on the state the steps above left
+        fp8 = torch.empty(w.total_elems, dtype=torch.uint8, device="cuda")
+        d_amax = torch.zeros(len(segs), dtype=torch.float32, device="cuda")
+        d_scale = torch.zeros(len(segs), dtype=torch.float32, device="cuda")
+        for _ in range(2):
+            B.amsp_fp8_payload_segments(master, n, segs, w.total_elems, fp8, d_amax, d_scale)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            B.amsp_fp8_payload_segments(master, n, segs, w.total_elems, fp8, d_amax, d_scale)
+        e1.record()
+        torch.cuda.synchronize()
+        fp8_ms = e0.elapsed_time(e1) / args.steps
+        out["fp8_payload"] = {"ms": fp8_ms, "GB/s": 9 * n / (fp8_ms * 1e-3) / 1e9, "bytes_per_element": 9,
+                              "launches": 2 * len(segs) + 2}
+        del fp8
     if not args.no_alt and not w.inter_tensor:
         out["alt_step"] = alt_step(args, torch, B, w, n, parts, master, exp_avg, exp_avg_sq, param_bf16, d_sqnorm)
     if not args.no_cpu_baseline:

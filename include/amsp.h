@@ -218,6 +218,34 @@ int amsp_adamw_step_segments(const uint16_t *const *partials_flat, uint32_t k, u
                              float *master_local, float *exp_avg_local, float *exp_avg_sq_local,
                              uint16_t *param_bf16_flat, const amsp_adamw_hparams *hp, void *stream);
 
+/* ------------------------------------------------------------------------------------------------
+ * FP8 payload with per-tensor scaling factors: Section IV-C.2 adopts inter-tensor shards because
+ * each FP8 tensor travels with its own scale.  The paper fixes no format; this library ships OCP E4M3
+ * (bias 7, 3 mantissa bits, subnormals, no infinities, largest finite 448, NaN = S.1111.111), rounds
+ * to nearest even, saturates beyond +-448, and scales each tensor by 448 / max|p| (1 when that
+ * maximum is 0 or not finite), the maximum, the scale and the product all in fp32.
+ */
+
+/* Step 4 as FP8: param_fp8_out[i] = e4m3(master[i] * *d_scale).  master: device fp32[n];
+ * d_scale: device float; param_fp8_out: device uint8[n] (codes). */
+int amsp_cast_param_fp8_shard(const float *master, uint64_t n, const float *d_scale,
+                              uint8_t *param_fp8_out, void *stream);
+
+/*
+ * Per segment of a rank's compact master: d_amax[i] = max |master| over the segment (exact and
+ * order-free: an integer maximum of the bit patterns; a NaN in the segment yields a NaN),
+ * d_scale[i] = 448 / d_amax[i], and the segment's E4M3 codes written at its flat position.
+ *   master_local    device fp32[local_elems]
+ *   param_fp8_flat  device uint8[flat_elems]; only owned segments are written
+ *   d_amax, d_scale device float[num_segments], written (the scales are what a receiver needs to
+ *                   decode: value = code / scale)
+ * Errors as amsp_adamw_step_segments.
+ */
+int amsp_fp8_payload_segments(const float *master_local, uint64_t local_elems,
+                              const amsp_segment *segments, uint32_t num_segments,
+                              uint64_t flat_elems, uint8_t *param_fp8_flat,
+                              float *d_amax, float *d_scale, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -51,6 +51,16 @@ def _bind(lib):
     lib.amsp_oracle_cast.restype = None
     lib.amsp_oracle_round_f32.argtypes = [vp, u64, vp]
     lib.amsp_oracle_round_f32.restype = None
+    lib.amsp_oracle_e4m3_decode.argtypes = [ctypes.c_uint8]
+    lib.amsp_oracle_e4m3_decode.restype = flt
+    lib.amsp_oracle_e4m3_encode.argtypes = [flt]
+    lib.amsp_oracle_e4m3_encode.restype = ctypes.c_uint8
+    lib.amsp_oracle_absmax.argtypes = [vp, u64]
+    lib.amsp_oracle_absmax.restype = flt
+    lib.amsp_oracle_fp8_scale.argtypes = [flt]
+    lib.amsp_oracle_fp8_scale.restype = flt
+    lib.amsp_oracle_cast_fp8.argtypes = [vp, u64, flt, vp]
+    lib.amsp_oracle_cast_fp8.restype = None
     return lib
 
 
@@ -217,3 +227,42 @@ def select(flat_array: np.ndarray, segments) -> np.ndarray:
     if not segments:
         return flat_array[:0].copy()
     return np.concatenate([flat_array[f:f + n] for f, _, n in segments])
+
+
+# --------------------------------------------------------------------------- FP8 payload
+def e4m3_decode(code: int) -> float:
+    return float(_load().amsp_oracle_e4m3_decode(int(code)))
+
+
+def e4m3_encode(x: float) -> int:
+    return int(_load().amsp_oracle_e4m3_encode(float(np.float32(x))))
+
+
+def absmax(p: np.ndarray) -> float:
+    p = np.ascontiguousarray(p, dtype=np.float32)
+    return float(_load().amsp_oracle_absmax(_ptr(p), p.size))
+
+
+def fp8_scale(amax: float) -> float:
+    return float(_load().amsp_oracle_fp8_scale(float(np.float32(amax))))
+
+
+def cast_fp8(p: np.ndarray, scale: float) -> np.ndarray:
+    """e4m3 codes (uint8) of p * scale, the product and the scale in fp32."""
+    p = np.ascontiguousarray(p, dtype=np.float32)
+    out = np.empty(p.size, dtype=np.uint8)
+    _load().amsp_oracle_cast_fp8(_ptr(p), p.size, float(np.float32(scale)), _ptr(out))
+    return out
+
+
+def fp8_payload_segments(master_local: np.ndarray, segments):
+    """Per segment: amax, scale and codes; returns (codes in compact order, scales list, amax list)."""
+    codes, scales, amaxes = [], [], []
+    for _, l, n in segments:
+        t = master_local[l:l + n]
+        a = absmax(t)
+        sc = fp8_scale(a)
+        amaxes.append(a)
+        scales.append(sc)
+        codes.append(cast_fp8(t, sc))
+    return (np.concatenate(codes) if codes else np.empty(0, np.uint8)), scales, amaxes

@@ -113,3 +113,60 @@ void amsp_oracle_cast(const float *p, uint64_t n, uint16_t *out) {
 void amsp_oracle_round_f32(const double *x, uint64_t n, float *out) {
     for (uint64_t i = 0; i < n; ++i) out[i] = (float)x[i];
 }
+
+/* ---------------------------------------------------------------------------------------------
+ * FP8 payload with per-tensor scaling factors: the reason Section IV-C.2 gives for adopting
+ * inter-tensor shards (each rank owns whole tensors, so one scale per tensor travels with them).
+ * The paper fixes no format; taken here: OCP E4M3 (1 sign, 4 exponent bits with bias 7, 3 mantissa
+ * bits, subnormals, no infinities, largest finite 448, NaN = S.1111.111), round to nearest even,
+ * values beyond the largest finite SATURATE to +-448, and
+ *     scale = 448 / amax(|tensor|)   (1 when amax is 0 or not finite),   code = e4m3(p * scale),
+ * with amax, scale and the product taken in fp32, because they decide an integer code.
+ */
+float amsp_oracle_e4m3_decode(uint8_t c) {
+    int sign = c >> 7, e = (c >> 3) & 0xF, m = c & 7;
+    float v;
+    if (e == 0xF && m == 7) v = NAN;
+    else if (e == 0) v = ldexpf((float)m, -9);                 /* subnormal: m * 2^-9 */
+    else v = ldexpf(1.0f + (float)m / 8.0f, e - 7);
+    return sign ? -v : v;
+}
+
+uint8_t amsp_oracle_e4m3_encode(float x) {
+    uint8_t sign = signbit(x) ? 0x80 : 0x00;
+    if (isnan(x)) return sign | 0x7F;
+    double a = fabs((double)x);
+    if (a >= 464.0) return sign | 0x7E;                        /* 464 is the midpoint above 448: tie goes to even = 448 */
+    if (a == 0.0) return sign;
+    int e;
+    (void)frexp(a, &e);                                        /* a = f * 2^e, f in [0.5, 1) */
+    e -= 1;                                                    /* a in [2^e, 2^(e+1)) */
+    if (e < -6) e = -6;                                        /* subnormal range shares the spacing of 2^-6 */
+    double q = ldexp(1.0, e - 3);                              /* grid spacing */
+    double r = nearbyint(a / q);                               /* exact quotient, ties to even */
+    if (r >= 16.0) { r = 8.0; e += 1; }
+    if (r < 8.0) return sign | (uint8_t)r;                     /* subnormal codes 0..7 */
+    return sign | (uint8_t)(((e + 7) << 3) | ((int)r - 8));
+}
+
+float amsp_oracle_absmax(const float *p, uint64_t n) {
+    float a = 0.0f;
+    for (uint64_t i = 0; i < n; ++i) {
+        float v = fabsf(p[i]);
+        if (v > a || isnan(v)) a = v;                          /* a NaN anywhere makes the result NaN */
+        if (isnan(a)) break;
+    }
+    return a;
+}
+
+float amsp_oracle_fp8_scale(float amax) {
+    if (!(amax > 0.0f) || !isfinite(amax)) return 1.0f;
+    return 448.0f / amax;
+}
+
+void amsp_oracle_cast_fp8(const float *p, uint64_t n, float scale, uint8_t *out) {
+    for (uint64_t i = 0; i < n; ++i) {
+        volatile float x = p[i] * scale;                       /* one fp32 multiply, rounded to fp32 */
+        out[i] = amsp_oracle_e4m3_encode(x);
+    }
+}

@@ -21,7 +21,7 @@ AMSP_MAX_K = 32
 EXPORTS = ("amsp_status_string", "amsp_workspace_bytes", "amsp_reduce_workspace_bytes", "amsp_shard_range",
            "amsp_reduce_grad_shard", "amsp_grad_sqnorm", "amsp_adamw_step_shard", "amsp_cast_param_shard",
            "amsp_partition_tensors", "amsp_owned_segments", "amsp_grad_sqnorm_segments",
-           "amsp_adamw_step_segments")
+           "amsp_adamw_step_segments", "amsp_cast_param_fp8_shard", "amsp_fp8_payload_segments")
 
 
 class AmspError(RuntimeError):
@@ -91,6 +91,8 @@ def load() -> ctypes.CDLL:
                                                   ctypes.c_size_t, vp]
         lib.amsp_adamw_step_segments.argtypes = [vp, u32, u64, ctypes.POINTER(_Segment), u32, u64, vp, vp, vp, vp,
                                                  ctypes.POINTER(_Hparams), vp]
+        lib.amsp_cast_param_fp8_shard.argtypes = [vp, u64, vp, vp, vp]
+        lib.amsp_fp8_payload_segments.argtypes = [vp, u64, ctypes.POINTER(_Segment), u32, u64, vp, vp, vp, vp]
         for name in EXPORTS[3:]:
             getattr(lib, name).restype = ci
         _lib = lib
@@ -240,3 +242,17 @@ def amsp_adamw_step_segments(partials_flat, flat_elems: int, segments, local_ele
                                            _ptr(exp_avg_local), _ptr(exp_avg_sq_local), _ptr(param_bf16_flat),
                                            ctypes.byref(c) if c is not None else None, _stream(stream)),
            "amsp_adamw_step_segments")
+
+
+# ------------------------------------------------------------------ FP8 payload
+def amsp_cast_param_fp8_shard(master, n: int, d_scale, param_fp8_out, stream=None) -> None:
+    _check(load().amsp_cast_param_fp8_shard(_ptr(master), n, _ptr(d_scale), _ptr(param_fp8_out), _stream(stream)),
+           "amsp_cast_param_fp8_shard")
+
+
+def amsp_fp8_payload_segments(master_local, local_elems: int, segments, flat_elems: int, param_fp8_flat, d_amax,
+                              d_scale, stream=None) -> None:
+    segs, ns = _segments(segments)
+    _check(load().amsp_fp8_payload_segments(_ptr(master_local), local_elems, segs, ns, flat_elems,
+                                            _ptr(param_fp8_flat), _ptr(d_amax), _ptr(d_scale), _stream(stream)),
+           "amsp_fp8_payload_segments")

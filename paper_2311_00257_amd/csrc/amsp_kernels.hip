@@ -417,6 +417,101 @@ __global__ void __launch_bounds__(kThreads) adamw_kernel(PartialPtrs pp, int k, 
     }
 }
 
+// ---------------------------------------------------------------- FP8 (E4M3) payload
+// fp32 -> OCP E4M3 on the bit pattern: round to nearest even, saturate at +-448, NaN -> S.1111.111.
+__device__ __forceinline__ uint32_t f32_to_e4m3(float x) {
+    const uint32_t u = __float_as_uint(x);
+    const uint32_t sign = (u >> 24) & 0x80u;
+    const uint32_t a = u & 0x7FFFFFFFu;
+    uint32_t code;
+    if (a > 0x7F800000u) {
+        code = 0x7Fu;                                   // NaN
+    } else if (a >= 0x43E80000u) {
+        code = 0x7Eu;                                   // |x| >= 464 (midpoint above 448, tie to even) and Inf: 448
+    } else if (a < 0x3C800000u) {
+        // below 2^-6: multiples of 2^-9; |x| * 512 is exact in fp32 and rintf rounds ties to even
+        code = (uint32_t)rintf(__uint_as_float(a) * 512.0f);   // 0..8, where 8 is the smallest normal
+    } else {
+        const uint32_t r = a + 0x7FFFFu + ((a >> 20) & 1u);    // round to 3 mantissa bits, ties to even
+        code = (r >> 20) - (120u << 3);                        // re-bias the exponent from 127 to 7
+    }
+    return sign | code;
+}
+
+// |x| as an ordered integer: for non-negative floats the bit patterns order like the values, with
+// Inf above every finite value and NaN patterns above Inf, so an integer max is exact,
+// order-independent and lets a NaN win.
+__device__ __forceinline__ uint32_t abs_bits(float x) { return __float_as_uint(x) & 0x7FFFFFFFu; }
+
+__global__ void __launch_bounds__(kThreads) fill_u32_kernel(uint32_t *p, uint32_t count, uint32_t value) {
+    for (uint32_t i = blockIdx.x * kThreads + threadIdx.x; i < count; i += gridDim.x * kThreads) p[i] = value;
+}
+
+// Largest |x| of a range into *slot (integer atomic max: deterministic).  Persistent read-only
+// grid like the norm pass.
+__global__ void __launch_bounds__(kNormThreads) absmax_kernel(const float *__restrict__ x, Span s,
+                                                              uint32_t *__restrict__ slot) {
+    constexpr int VEC = 4;
+    const uint64_t first = (uint64_t)blockIdx.x * kNormThreads + threadIdx.x;
+    const uint64_t stride = (uint64_t)gridDim.x * kNormThreads;
+    uint32_t m = 0;
+    if (s.vectorised) {
+        for (uint64_t v = first; v < s.nvec; v += stride) {
+            float t[VEC];
+            ld_f32<VEC>(x, s.head + v * VEC, t);
+#pragma unroll
+            for (int c = 0; c < VEC; ++c) m = max(m, abs_bits(t[c]));
+        }
+        uint64_t i;
+        if (blockIdx.x == 0 && threadIdx.x < 2 * (VEC - 1) && edge_index<VEC>(s, threadIdx.x, i))
+            m = max(m, abs_bits(x[i]));
+    } else {
+        for (uint64_t i = first; i < s.n; i += stride) m = max(m, abs_bits(x[i]));
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) m = max(m, (uint32_t)__shfl_down((int)m, off, 64));
+    __shared__ uint32_t wave_max[kNormThreads / 64];
+    if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int w = 1; w < kNormThreads / 64; ++w) m = max(m, wave_max[w]);
+        atomicMax(slot, m);
+    }
+}
+
+// scale[i] = 448 / amax[i] in fp32 (correctly rounded division); 1 when amax is 0, Inf or NaN.
+__global__ void __launch_bounds__(kThreads) fp8_scale_kernel(const float *__restrict__ amax, float *__restrict__ scale,
+                                                             uint32_t count) {
+    for (uint32_t i = blockIdx.x * kThreads + threadIdx.x; i < count; i += gridDim.x * kThreads) {
+        const float a = amax[i];
+        scale[i] = (a > 0.0f && a < __uint_as_float(0x7F800000u)) ? 448.0f / a : 1.0f;
+    }
+}
+
+__global__ void __launch_bounds__(kThreads) cast_fp8_kernel(const float *__restrict__ master,
+                                                            const float *__restrict__ d_scale,
+                                                            uint8_t *__restrict__ out, Span s) {
+    constexpr int VEC = 4;
+    const float scale = *d_scale;
+    if (s.vectorised) {
+        for (uint64_t v = global_thread(); v < s.nvec; v += grid_threads()) {
+            const uint64_t e = s.head + v * VEC;
+            float x[VEC];
+            ld_f32<VEC>(master, e, x);
+            uint32_t w = 0;
+#pragma unroll
+            for (int c = 0; c < VEC; ++c) w |= f32_to_e4m3(x[c] * scale) << (8 * c);
+            st_stream(reinterpret_cast<uint32_t *>(out + e), w);
+        }
+        uint64_t i;
+        if (blockIdx.x == 0 && threadIdx.x < 2 * (VEC - 1) && edge_index<VEC>(s, threadIdx.x, i))
+            out[i] = (uint8_t)f32_to_e4m3(master[i] * scale);
+    } else {
+        for (uint64_t i = global_thread(); i < s.n; i += grid_threads()) out[i] = (uint8_t)f32_to_e4m3(master[i] * scale);
+    }
+}
+
 // ---------------------------------------------------------------- host side
 struct Stream16 {
     const void *ptr;
@@ -921,6 +1016,52 @@ int amsp_adamw_step_segments(const uint16_t *const *partials_flat, uint32_t k, u
         rc = amsp_adamw_step_shard(q.p, k, nullptr, g.length, 0, master_local + g.local_offset,
                                    exp_avg_local + g.local_offset, exp_avg_sq_local + g.local_offset,
                                    param_bf16_flat ? param_bf16_flat + g.flat_offset : nullptr, hp, stream);
+        if (rc != AMSP_OK) return rc;
+    }
+    return AMSP_OK;
+}
+
+// ---------------------------------------------------------------- FP8 payload entry points
+int amsp_cast_param_fp8_shard(const float *master, uint64_t n, const float *d_scale, uint8_t *param_fp8_out,
+                              void *stream) {
+    if (n == 0) return AMSP_OK;
+    if (master == nullptr || d_scale == nullptr || param_fp8_out == nullptr) return AMSP_ENULL;
+    if (misaligned(master, 4) || misaligned(d_scale, 4)) return AMSP_EALIGN;
+    Stream16 st[2] = {{master, 4}, {param_fp8_out, 1}};
+    Span s = make_span(n, st, 2, 4);
+    clear_stale_error();
+    hipLaunchKernelGGL(cast_fp8_kernel, dim3(full_grid(s)), dim3(kThreads), 0, (hipStream_t)stream, master, d_scale,
+                       param_fp8_out, s);
+    return launched();
+}
+
+int amsp_fp8_payload_segments(const float *master_local, uint64_t local_elems, const amsp_segment *segments,
+                              uint32_t num_segments, uint64_t flat_elems, uint8_t *param_fp8_flat, float *d_amax,
+                              float *d_scale, void *stream) {
+    int rc = check_segments(segments, num_segments, flat_elems, local_elems);
+    if (rc != AMSP_OK) return rc;
+    if (num_segments == 0) return AMSP_OK;
+    if (master_local == nullptr || param_fp8_flat == nullptr || d_amax == nullptr || d_scale == nullptr) return AMSP_ENULL;
+    if (misaligned(master_local, 4) || misaligned(d_amax, 4) || misaligned(d_scale, 4)) return AMSP_EALIGN;
+    hipStream_t hs = (hipStream_t)stream;
+    uint32_t *slots = reinterpret_cast<uint32_t *>(d_amax);
+    clear_stale_error();
+    hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(kThreads), 0, hs, slots, num_segments, 0u);
+    if (launched() != AMSP_OK) return AMSP_EDEVICE;
+    for (uint32_t i = 0; i < num_segments; ++i) {
+        if (segments[i].length == 0) continue;
+        const float *x = master_local + segments[i].local_offset;
+        Stream16 st[1] = {{x, 4}};
+        Span s = make_span(segments[i].length, st, 1, 4);
+        hipLaunchKernelGGL(absmax_kernel, dim3(norm_grid(s)), dim3(kNormThreads), 0, hs, x, s, slots + i);
+        if (launched() != AMSP_OK) return AMSP_EDEVICE;
+    }
+    hipLaunchKernelGGL(fp8_scale_kernel, dim3(1), dim3(kThreads), 0, hs, d_amax, d_scale, num_segments);
+    if (launched() != AMSP_OK) return AMSP_EDEVICE;
+    for (uint32_t i = 0; i < num_segments; ++i) {
+        if (segments[i].length == 0) continue;
+        rc = amsp_cast_param_fp8_shard(master_local + segments[i].local_offset, segments[i].length, d_scale + i,
+                                       param_fp8_flat + segments[i].flat_offset, stream);
         if (rc != AMSP_OK) return rc;
     }
     return AMSP_OK;

@@ -153,6 +153,16 @@ def test_segment_validation_without_device():
         B.amsp_adamw_step_segments([A], 100, [(0, 0, 10)], 100, 0, A, A, A, hp, stream=0)
     assert ei.value.status == B.AMSP_ENULL
     B.amsp_adamw_step_segments([A], 100, [], 0, 0, 0, 0, 0, hp, stream=0)          # owns nothing: fine
+    with pytest.raises(B.AmspError) as ei:
+        B.amsp_fp8_payload_segments(A, 100, [(95, 0, 10)], 100, A, A, A, stream=0)
+    assert ei.value.status == B.AMSP_EINVAL
+    with pytest.raises(B.AmspError) as ei:
+        B.amsp_fp8_payload_segments(A, 100, [(0, 0, 10)], 100, A, 0, A, stream=0)
+    assert ei.value.status == B.AMSP_ENULL
+    with pytest.raises(B.AmspError) as ei:
+        B.amsp_cast_param_fp8_shard(A, 10, 0, A, stream=0)
+    assert ei.value.status == B.AMSP_ENULL
+    B.amsp_cast_param_fp8_shard(0, 0, 0, 0, stream=0)
 
 
 def test_product_package_never_imports_the_oracle():

@@ -436,3 +436,69 @@ def test_inter_tensor_step_on_tiny_llama(B, torch_mod, s, k):
         got = (dp.cpu().numpy(), dm.cpu().numpy(), dv.cpu().numpy(), oracle.select(out_bits, segs), float(d_s.item()))
         _check_all(got, ref, inp, hp)
         assert np.all(out_bits[elem_owner != rank] == 0x5A5A)          # drop: nothing else is written
+
+
+# ------------------------------------------------------------------ FP8 (E4M3) payload
+def test_fp8_cast_every_pattern_class(B, torch_mod):
+    """amsp_cast_param_fp8_shard against the oracle, bit for bit: all 65,536 high halves of fp32
+    with several low halves (ties, just above and below), at three scales (the product is fp32)."""
+    torch = torch_mod
+    hi = np.arange(65536, dtype=np.uint32) << 16
+    lows = np.array([0x0000, 0x0001, 0x7FFF, 0x8000, 0x8001, 0xFFFF], dtype=np.uint32)
+    x = (hi[:, None] | lows[None, :]).reshape(-1).view(np.float32)
+    d = H.to_dev_f32(x)
+    for scale in (1.0, 0.37, 1e6):
+        d_scale = torch.tensor([scale], dtype=torch.float32, device="cuda")
+        out = torch.zeros(x.size, dtype=torch.uint8, device="cuda")
+        B.amsp_cast_param_fp8_shard(d, x.size, d_scale, out)
+        assert np.array_equal(out.cpu().numpy(), oracle.cast_fp8(x, scale))
+
+
+@pytest.mark.parametrize("n,shift", [(1, 0), (5, 3), (2049, 1), (100_003, 0), (100_003, 2)])
+def test_fp8_cast_sizes_and_phases(B, torch_mod, n, shift):
+    torch = torch_mod
+    x = synth.fill_f32(3, 50, n, 100.0)
+    d = H.to_dev_f32(x, pad_front=shift)
+    d_scale = torch.tensor([1.7], dtype=torch.float32, device="cuda")
+    out = torch.full((shift + n + 8,), 0xA5, dtype=torch.uint8, device="cuda")
+    B.amsp_cast_param_fp8_shard(d, n, d_scale, out[shift:])
+    got = out.cpu().numpy()
+    assert np.array_equal(got[shift:shift + n], oracle.cast_fp8(x, 1.7))
+    assert np.all(got[:shift] == 0xA5) and np.all(got[shift + n:] == 0xA5)
+
+
+def test_fp8_payload_of_inter_tensor_shard(B, torch_mod):
+    """Per-tensor amax, scale and E4M3 codes of a rank's segments, after a real update."""
+    torch = torch_mod
+    w = workloads.get(0)
+    sizes, total = w.tensor_sizes, w.total_elems
+    owner = B.amsp_partition_tensors(sizes, 3)
+    flat = H.host_inputs(w, 0, total, k=1)
+    for rank in range(3):
+        segs, local = B.amsp_owned_segments(sizes, owner, rank)
+        master = oracle.select(flat.p, segs)
+        dp = H.to_dev_f32(master)
+        out = torch.full((total,), 0xA5, dtype=torch.uint8, device="cuda")
+        d_amax = torch.full((len(segs),), -1.0, dtype=torch.float32, device="cuda")
+        d_scale = torch.zeros(len(segs), dtype=torch.float32, device="cuda")
+        B.amsp_fp8_payload_segments(dp, local, segs, total, out, d_amax, d_scale)
+        codes, scales, amaxes = oracle.fp8_payload_segments(master, segs)
+        assert d_amax.cpu().numpy().tolist() == [float(np.float32(a)) for a in amaxes]       # bit-exact maxima
+        assert d_scale.cpu().numpy().tolist() == [float(np.float32(s)) for s in scales]      # and scales
+        got = out.cpu().numpy()
+        assert np.array_equal(oracle.select(got, segs), codes)                                # codes bit-exact
+        elem_owner = np.repeat(np.array(owner), sizes)
+        assert np.all(got[elem_owner != rank] == 0xA5)
+    # a NaN and an all-zero tensor: scale 1 on both sides
+    t = np.zeros(5000, dtype=np.float32)
+    t[2500:] = synth.fill_f32(9, 0, 2500, 1.0)
+    t[4000] = np.nan
+    segs = [(0, 0, 2500), (2500, 2500, 2500)]
+    out = torch.zeros(5000, dtype=torch.uint8, device="cuda")
+    d_amax = torch.zeros(2, dtype=torch.float32, device="cuda")
+    d_scale = torch.zeros(2, dtype=torch.float32, device="cuda")
+    B.amsp_fp8_payload_segments(H.to_dev_f32(t), 5000, segs, 5000, out, d_amax, d_scale)
+    a = d_amax.cpu().numpy()
+    assert a[0] == 0.0 and np.isnan(a[1]) and d_scale.cpu().numpy().tolist() == [1.0, 1.0]
+    codes, _, _ = oracle.fp8_payload_segments(t, segs)
+    assert np.array_equal(out.cpu().numpy(), codes)

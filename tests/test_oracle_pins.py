@@ -414,3 +414,76 @@ def test_owned_segments_and_select():
     # two owned neighbours become one segment
     assert oracle.owned_segments([3, 4, 5], [0, 0, 1], 0) == [(0, 0, 7)]
     assert oracle.owned_segments([3, 4, 5], [0, 1, 0], 0) == [(0, 0, 3), (7, 3, 5)]
+
+
+# --------------------------------------------------------------------------- FP8 (E4M3) payload
+def test_e4m3_golden_vectors(golden_dir):
+    rows = [l.split() for l in open(os.path.join(golden_dir, "e4m3_vectors.txt")) if l.strip() and l[0] != "#"]
+    assert len(rows) >= 20
+    for r in rows:
+        assert oracle.e4m3_encode(float(r[0])) == int(r[1], 16), r
+
+
+def test_e4m3_code_table_by_formula():
+    # decode by the format's definition written independently here, then encode back
+    for c in range(256):
+        s, e, m = c >> 7, (c >> 3) & 15, c & 7
+        if e == 15 and m == 7:
+            assert math.isnan(oracle.e4m3_decode(c))
+            continue
+        want = (m * 2.0 ** -9) if e == 0 else (1 + m / 8) * 2.0 ** (e - 7)
+        want = -want if s else want
+        assert oracle.e4m3_decode(c) == want
+        assert oracle.e4m3_encode(want) == c                      # every representable value is a fixed point
+    assert max(oracle.e4m3_decode(c) for c in range(0x7F)) == 448.0
+    assert oracle.e4m3_encode(float("nan")) & 0x7F == 0x7F
+    assert oracle.e4m3_encode(float("inf")) == 0x7E and oracle.e4m3_encode(float("-inf")) == 0xFE
+
+
+def test_e4m3_is_nearest_with_ties_to_even_and_matches_torch_in_range():
+    import torch
+
+    rng = np.random.default_rng(12)
+    x = (rng.standard_normal(400_000) * np.exp(rng.uniform(-9, 6.2, 400_000))).astype(F32)
+    grid = np.array(sorted({oracle.e4m3_decode(c) for c in range(0x7F)}))          # the non-negative values
+    # all midpoints of the grid (exactly representable in fp32) join the sample: the tie cases
+    mids = ((grid[:-1] + grid[1:]) / 2).astype(F32)
+    x = np.concatenate([x, mids, -mids])
+    codes = oracle.cast_fp8(x, 1.0)
+    back = np.array([oracle.e4m3_decode(int(c)) for c in range(256)])[codes]
+    a = np.minimum(np.abs(x.astype(np.float64)), 448.0)                              # saturation
+    dist = np.abs(np.abs(back) - a)
+    best = np.min(np.abs(grid[None, :] - a[:, None]) if x.size < 5000 else
+                  np.abs(grid[np.clip(np.searchsorted(grid, a)[:, None] + np.array([-1, 0])[None, :], 0, grid.size - 1)]
+                         - a[:, None]), axis=1)
+    assert np.all(dist == best)                                                      # nearest grid value
+    tie = np.isin(np.abs(x), mids) & (np.abs(x) < 464)
+    assert np.all((codes[tie] & 1) == 0)                                             # ties land on even codes
+    assert np.all((codes >> 7) == np.signbit(x))
+    inr = np.abs(x) <= 464
+    ref = torch.from_numpy(x[inr].copy()).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    assert np.array_equal(codes[inr], ref)                                           # library routine, in range
+
+
+def test_fp8_scale_and_payload_rules():
+    rng = np.random.default_rng(13)
+    t = (rng.standard_normal(10_000) * 0.02).astype(F32)
+    a = oracle.absmax(t)
+    assert a == float(np.max(np.abs(t)))
+    sc = oracle.fp8_scale(a)
+    assert sc == float(F32(448.0) / F32(a))
+    codes = oracle.cast_fp8(t, sc)
+    i = int(np.argmax(np.abs(t)))
+    assert codes[i] & 0x7F == 0x7E                                   # the largest element lands on +-448
+    dec = np.array([oracle.e4m3_decode(int(c)) for c in range(256)])[codes] / sc
+    assert np.max(np.abs(dec - t)) <= a / 448 * 16 + 1e-12           # half the top binade's spacing (32) in scaled units
+    assert oracle.fp8_scale(0.0) == 1.0 and oracle.fp8_scale(float("inf")) == 1.0 and oracle.fp8_scale(float("nan")) == 1.0
+    assert math.isnan(oracle.absmax(np.array([1.0, float("nan"), 3.0], dtype=F32)))
+    assert oracle.absmax(np.zeros(0, dtype=F32)) == 0.0
+    assert oracle.absmax(np.array([1.0, -5.0, 3.0], dtype=F32)) == 5.0      # magnitude, not signed maximum
+    # stale scale (too large): values beyond 448 saturate instead of wrapping or turning into NaN
+    assert list(oracle.cast_fp8(np.array([1.0, -1.0], dtype=F32), 1e6)) == [0x7E, 0xFE]
+    segs = [(100, 0, 3000), (5000, 3000, 7000)]
+    codes2, scales, amaxes = oracle.fp8_payload_segments(t, segs)
+    assert amaxes == [oracle.absmax(t[:3000]), oracle.absmax(t[3000:])] and codes2.size == 10_000
+    assert np.array_equal(codes2[3000:], oracle.cast_fp8(t[3000:], scales[1]))

@@ -40,6 +40,15 @@ MUTATIONS = [
     ("cast: truncation", "u += 0x7FFFu + keep_lsb;", ""),
     ("cast: NaN not handled", "if ((u & 0x7FFFFFFFu) > 0x7F800000u)", "if (0)"),
     ("cast: NaN loses its sign", "(((u >> 16) & 0x8000u) | 0x7FC0u)", "(0x7FC0u)"),
+    ("e4m3: wrong exponent bias", "return sign | (uint8_t)(((e + 7) << 3) | ((int)r - 8));", "return sign | (uint8_t)(((e + 8) << 3) | ((int)r - 8));"),
+    ("e4m3: subnormal spacing of the wrong binade", "if (e < -6) e = -6;", "if (e < -7) e = -7;"),
+    ("e4m3: mantissa carry not propagated", "if (r >= 16.0) { r = 8.0; e += 1; }", "if (r >= 16.0) { r = 15.0; }"),
+    ("e4m3: no saturation at the tie above 448", "if (a >= 464.0) return sign | 0x7E;", "if (a >= 480.0) return sign | 0x7E;"),
+    ("e4m3: truncation instead of nearest", "double r = nearbyint(a / q);", "double r = floor(a / q);"),
+    ("e4m3: decode of subnormals off by one binade", "v = ldexpf((float)m, -9);", "v = ldexpf((float)m, -10);"),
+    ("fp8: scale maps amax to 240", "return 448.0f / amax;", "return 240.0f / amax;"),
+    ("fp8: signed max instead of max magnitude", "float v = fabsf(p[i]);", "float v = p[i];"),
+    ("fp8: scale not applied", "volatile float x = p[i] * scale;", "volatile float x = p[i];"),
 ]
 
 PIN_TESTS = [getattr(pins, n) for n in dir(pins) if n.startswith("test_") and "synth" not in n]
