@@ -36,6 +36,8 @@
  *   - `bucket_elems` (Section IV-C.2: gradients are synchronised in buckets of size U; here
  *     counted in elements): 0 processes [0,n) in one launch; U > 0 processes the buckets
  *     [bU, min((b+1)U, n)) in order, one launch each, as they would arrive.
+ *   - One launch covers at most (2^31 - 1) * 64 elements (about 5.5e11, more than fits the device);
+ *     a longer range, or a longer bucket, is AMSP_EINVAL.
  *   - n == 0 is valid: AMSP_OK, nothing launched (amsp_grad_sqnorm still writes 0 when
  *     accumulate == 0).
  *   - The reduction order over j = 0..k-1 is fixed and fp32, identical in every entry point,

@@ -35,12 +35,13 @@
 
 namespace {
 
-constexpr int kThreads = 256;          // 4 waves of 64
+constexpr int kThreads = 256;          // helper kernels (finishing sums, fills): 4 waves of 64
+constexpr int kRwThreads = 64;         // the kernels that read and write run one-wave workgroups
 constexpr int kVecRW = 4;              // elements per lane per stream in the kernels that write
 constexpr int kVecNorm = 8;            // elements per lane per stream in the norm pass
 constexpr int kNormThreads = 1024;     // the norm pass runs 16-wave blocks, two per CU
 constexpr int kNormBlocks = 2048;      // upper bound of the norm pass's grid; sizes its workspace
-constexpr uint64_t kMaxGrid = 1u << 30;
+constexpr uint64_t kMaxGrid = (1ull << 31) - 1;
 
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -129,21 +130,31 @@ __device__ __forceinline__ void widen_add(const W &w, float (&g)[VEC]) {
     for (int c = 0; c < VEC / 2; ++c) { g[2 * c] += bf16_lo(w[c]); g[2 * c + 1] += bf16_hi(w[c]); }
 }
 
+// Keeps the compiler from sinking loads below this point: everything loaded so far is in flight
+// before any arithmetic that waits on part of it.
+__device__ __forceinline__ void loads_issued() {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);   // nothing may be scheduled across: arithmetic stays below the loads
+}
+
 template <int K, int VEC>
 __device__ __forceinline__ void grad_vec(const PartialPtrs &pp, int k, const float *gf32, uint64_t e,
                                          float (&g)[VEC]) {
     typedef typename Bf16Words<VEC>::type W;
     if constexpr (K == 0) {
         ld_f32<VEC>(gf32, e, g);
+        loads_issued();
     } else if constexpr (K > 0) {
         W w[K];
 #pragma unroll
         for (int j = 0; j < K; ++j) w[j] = ld_stream(reinterpret_cast<const W *>(pp.p[j] + e));
+        loads_issued();
         widen_first<VEC>(w[0], g);
 #pragma unroll
         for (int j = 1; j < K; ++j) widen_add<VEC>(w[j], g);
     } else {
         W w = ld_stream(reinterpret_cast<const W *>(pp.p[0] + e));
+        loads_issued();
         widen_first<VEC>(w, g);
 #pragma unroll 4
         for (int j = 1; j < k; ++j) {
@@ -166,45 +177,54 @@ __device__ __forceinline__ float grad1(const PartialPtrs &pp, int k, const float
     }
 }
 
-// A launch covers n elements: `head` leading ones (< VEC) up to the element at which every
-// stream reaches the alignment its vector access needs, nvec groups of VEC taken with vector
-// accesses, and a tail of < VEC.  Head and tail are the "edge", done element-wise by the first
-// lanes of block 0.  When the streams have no common phase the host sets vectorised = 0 and
-// every element goes through the element-wise loop.
+// A launch covers n elements: `head` leading ones up to the element at which every stream is
+// aligned (to a 128-byte line when the streams allow it, so that every wave's piece of every stream
+// is whole lines; else to its vector access), nvec groups of VEC taken with vector accesses, and
+// `tail` < VEC trailing ones.  Head and tail are the "edge", done element-wise by block 0.  When the
+// streams have no common phase the host sets vectorised = 0 and every element goes through the
+// element-wise loop.
 struct Span {
     uint64_t n;
     uint64_t nvec;
     uint32_t head;
+    uint32_t tail;
     uint32_t vectorised;
 };
 
+// Element index of the t-th edge element, t < head + tail.
 template <int VEC>
-__device__ __forceinline__ bool edge_index(const Span &s, uint32_t t, uint64_t &i) {
-    if (t < s.head) { i = t; return true; }
-    uint64_t j = (uint64_t)s.head + s.nvec * VEC + (t - s.head);
-    if (j < s.n) { i = j; return true; }
-    return false;
+__device__ __forceinline__ uint64_t edge_elem(const Span &s, uint32_t t) {
+    return t < s.head ? (uint64_t)t : (uint64_t)s.head + s.nvec * VEC + (t - s.head);
 }
 
-__device__ __forceinline__ uint64_t global_thread() { return (uint64_t)blockIdx.x * kThreads + threadIdx.x; }
-__device__ __forceinline__ uint64_t grid_threads() { return (uint64_t)gridDim.x * kThreads; }
+// The read+write kernels are straight-line code: the grid covers the range exactly once, with
+// one-wave workgroups (one vector per lane) on the vector path and 256-thread workgroups (one
+// element per lane) on the element-wise path.  Nothing in them asks for blockDim or gridDim: those
+// live in the dispatch packet, and fetching them would put one more memory round trip in front of
+// the wave's loads.
+__device__ __forceinline__ uint64_t vector_index() { return (uint64_t)blockIdx.x * kRwThreads + threadIdx.x; }
+__device__ __forceinline__ uint64_t element_index() { return (uint64_t)blockIdx.x * kThreads + threadIdx.x; }
 
 // ---------------------------------------------------------------- step 4: cast
 __global__ void __launch_bounds__(kThreads) cast_kernel(const float *__restrict__ master,
                                                         uint16_t *__restrict__ out, Span s) {
     constexpr int VEC = kVecRW;
     if (s.vectorised) {
-        for (uint64_t v = global_thread(); v < s.nvec; v += grid_threads()) {
+        const uint64_t v = vector_index();
+        if (v < s.nvec) {
             const uint64_t e = s.head + v * VEC;
             float x[VEC];
             ld_f32<VEC>(master, e, x);
             st_bf16<VEC>(out, e, x);
         }
-        uint64_t i;
-        if (blockIdx.x == 0 && threadIdx.x < 2 * (VEC - 1) && edge_index<VEC>(s, threadIdx.x, i))
-            out[i] = (uint16_t)f32_to_bf16(master[i]);
+        if (blockIdx.x == 0)
+            for (uint32_t t = threadIdx.x; t < s.head + s.tail; t += kRwThreads) {
+                const uint64_t i = edge_elem<VEC>(s, t);
+                out[i] = (uint16_t)f32_to_bf16(master[i]);
+            }
     } else {
-        for (uint64_t i = global_thread(); i < s.n; i += grid_threads()) out[i] = (uint16_t)f32_to_bf16(master[i]);
+        const uint64_t i = element_index();
+        if (i < s.n) out[i] = (uint16_t)f32_to_bf16(master[i]);
     }
 }
 
@@ -225,8 +245,7 @@ __device__ __forceinline__ double block_sum(double acc) {
     double t = 0.0;
     if (threadIdx.x == 0) {
         t = wave_part[0];
-#pragma unroll
-        for (int w = 1; w < THREADS / 64; ++w) t += wave_part[w];
+        for (int w = 1; w < (int)(blockDim.x >> 6); ++w) t += wave_part[w];   // THREADS bounds blockDim.x
     }
     return t;
 }
@@ -241,48 +260,50 @@ __global__ void __launch_bounds__(kThreads) reduce_kernel(PartialPtrs pp, int k,
     constexpr int VEC = kVecRW;
     double acc = 0.0;
     if (s.vectorised) {
-        const uint64_t block_vecs = (uint64_t)ROWS * kThreads;
-        for (uint64_t v0 = blockIdx.x * block_vecs + threadIdx.x; v0 < s.nvec; v0 += gridDim.x * block_vecs) {
-            float g[ROWS][VEC];
+        const uint64_t v0 = (uint64_t)blockIdx.x * (ROWS * kRwThreads) + threadIdx.x;
+        float g[ROWS][VEC];
 #pragma unroll
-            for (int r = 0; r < ROWS; ++r) {
-                const uint64_t v = v0 + (uint64_t)r * kThreads;
-                if (v < s.nvec) {
-                    const uint64_t e = s.head + v * VEC;
-                    grad_vec<K, VEC>(pp, k, nullptr, e, g[r]);
-                    if (accumulate) {
-                        float o[VEC];
-                        ld_f32<VEC>(out, e, o);
+        for (int r = 0; r < ROWS; ++r) {
+            const uint64_t v = v0 + (uint64_t)r * kRwThreads;
+            if (v < s.nvec) {
+                const uint64_t e = s.head + v * VEC;
+                float o[VEC];
+                if (accumulate) ld_f32<VEC>(out, e, o);   // issued ahead of the partial loads
+                grad_vec<K, VEC>(pp, k, nullptr, e, g[r]);
+                if (accumulate) {
 #pragma unroll
-                        for (int c = 0; c < VEC; ++c) g[r][c] = o[c] + g[r][c];
-                    }
-                }
-            }
-#pragma unroll
-            for (int r = 0; r < ROWS; ++r) {
-                const uint64_t v = v0 + (uint64_t)r * kThreads;
-                if (v < s.nvec) {
-                    st_f32<VEC>(out, s.head + v * VEC, g[r]);
-                    if constexpr (NORM) {
-#pragma unroll
-                        for (int c = 0; c < VEC; ++c) acc = fma((double)g[r][c], (double)g[r][c], acc);
-                    }
+                    for (int c = 0; c < VEC; ++c) g[r][c] = o[c] + g[r][c];
                 }
             }
         }
-        uint64_t i;
-        if (blockIdx.x == 0 && threadIdx.x < 2 * (VEC - 1) && edge_index<VEC>(s, threadIdx.x, i)) {
-            float g = grad1<K>(pp, k, nullptr, i);
-            if (accumulate) g = out[i] + g;
-            out[i] = g;
-            if constexpr (NORM) acc = fma((double)g, (double)g, acc);
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) {
+            const uint64_t v = v0 + (uint64_t)r * kRwThreads;
+            if (v < s.nvec) {
+                st_f32<VEC>(out, s.head + v * VEC, g[r]);
+                if constexpr (NORM) {
+#pragma unroll
+                    for (int c = 0; c < VEC; ++c) acc = fma((double)g[r][c], (double)g[r][c], acc);
+                }
+            }
         }
+        if (blockIdx.x == 0)
+            for (uint32_t t = threadIdx.x; t < s.head + s.tail; t += kRwThreads) {
+                const uint64_t i = edge_elem<VEC>(s, t);
+                float g1 = grad1<K>(pp, k, nullptr, i);
+                if (accumulate) g1 = out[i] + g1;
+                out[i] = g1;
+                if constexpr (NORM) acc = fma((double)g1, (double)g1, acc);
+            }
     } else {
-        for (uint64_t i = global_thread(); i < s.n; i += grid_threads()) {
-            float g = grad1<K>(pp, k, nullptr, i);
-            if (accumulate) g = out[i] + g;
-            out[i] = g;
-            if constexpr (NORM) acc = fma((double)g, (double)g, acc);
+        // element-wise path: with the norm the grid is capped (a fixed number of block sums), so loop
+        const uint64_t stride = NORM ? (uint64_t)gridDim.x * kThreads : ~0ull;
+        for (uint64_t i = element_index(); i < s.n; i += stride) {
+            float g1 = grad1<K>(pp, k, nullptr, i);
+            if (accumulate) g1 = out[i] + g1;
+            out[i] = g1;
+            if constexpr (NORM) acc = fma((double)g1, (double)g1, acc);
+            if constexpr (!NORM) break;
         }
     }
     if constexpr (NORM) {
@@ -309,11 +330,11 @@ __global__ void __launch_bounds__(kNormThreads) sqnorm_kernel(PartialPtrs pp, in
 #pragma unroll
             for (int c = 0; c < VEC; ++c) acc = fma((double)g[c], (double)g[c], acc);
         }
-        uint64_t i;
-        if (blockIdx.x == 0 && threadIdx.x < 2 * (VEC - 1) && edge_index<VEC>(s, threadIdx.x, i)) {
-            double g = (double)grad1<K>(pp, k, gf32, i);
-            acc = fma(g, g, acc);
-        }
+        if (blockIdx.x == 0)
+            for (uint32_t t = threadIdx.x; t < s.head + s.tail; t += kNormThreads) {
+                const double g = (double)grad1<K>(pp, k, gf32, edge_elem<VEC>(s, t));
+                acc = fma(g, g, acc);
+            }
     } else {
         for (uint64_t i = first; i < s.n; i += stride) {
             double g = (double)grad1<K>(pp, k, gf32, i);
@@ -359,10 +380,15 @@ struct AdamConsts {
     const double *d_total_sqnorm;
 };
 
-__device__ __forceinline__ float clip_scale(const AdamConsts &c) {
+// The squared norm is fetched first (a scalar load that overlaps everything after it); the scale is
+// worked out from it later, in double, once the wave's vector loads are in flight.
+__device__ __forceinline__ double load_sqnorm(const AdamConsts &c) {
+    return (c.d_total_sqnorm != nullptr && c.max_norm > 0.0f) ? *c.d_total_sqnorm : -1.0;
+}
+__device__ __forceinline__ float clip_scale(const AdamConsts &c, double sqnorm) {
     double s = (double)c.grad_scale;
-    if (c.d_total_sqnorm != nullptr && c.max_norm > 0.0f) {
-        double clip = (double)c.max_norm / (sqrt(*c.d_total_sqnorm) + (double)c.clip_eps);
+    if (sqnorm >= 0.0) {
+        double clip = (double)c.max_norm / (sqrt(sqnorm) + (double)c.clip_eps);
         s *= clip < 1.0 ? clip : 1.0;
     }
     return (float)s;
@@ -384,15 +410,18 @@ __global__ void __launch_bounds__(kThreads) adamw_kernel(PartialPtrs pp, int k, 
                                                          float *__restrict__ exp_avg_sq, uint16_t *__restrict__ out,
                                                          AdamConsts c, Span s) {
     constexpr int VEC = kVecRW;
-    const float scale = clip_scale(c);
+    const double sqnorm = load_sqnorm(c);
     if (s.vectorised) {
-        for (uint64_t vi = global_thread(); vi < s.nvec; vi += grid_threads()) {
+        const uint64_t vi = vector_index();
+        if (vi < s.nvec) {
             const uint64_t e = s.head + vi * VEC;
             float g[VEC], p[VEC], m[VEC], v[VEC];
-            grad_vec<K, VEC>(pp, k, gf32, e, g);
+            // every load of the vector is in flight before anything waits: one memory round trip
             ld_f32<VEC>(master, e, p);
             ld_f32<VEC>(exp_avg, e, m);
             ld_f32<VEC>(exp_avg_sq, e, v);
+            grad_vec<K, VEC>(pp, k, gf32, e, g);
+            const float scale = clip_scale(c, sqnorm);
 #pragma unroll
             for (int q = 0; q < VEC; ++q) adamw1(c, scale, g[q], p[q], m[q], v[q]);
             st_f32<VEC>(master, e, p);
@@ -400,16 +429,23 @@ __global__ void __launch_bounds__(kThreads) adamw_kernel(PartialPtrs pp, int k, 
             st_f32<VEC>(exp_avg_sq, e, v);
             if constexpr (WRITE_BF16) st_bf16<VEC>(out, e, p);
         }
-    }
-    const bool edge = s.vectorised != 0;
-    if (edge && blockIdx.x != 0) return;
-    const uint64_t first = edge ? threadIdx.x : global_thread();
-    const uint64_t count = edge ? 2 * (VEC - 1) : s.n;
-    for (uint64_t t = first; t < count; t += edge ? (uint64_t)kThreads : grid_threads()) {
-        uint64_t i = t;
-        if (edge && !edge_index<VEC>(s, (uint32_t)t, i)) continue;
+        if (blockIdx.x != 0) return;
+        const float scale = clip_scale(c, sqnorm);
+        for (uint32_t t = threadIdx.x; t < s.head + s.tail; t += kRwThreads) {
+            const uint64_t i = edge_elem<VEC>(s, t);
+            float p = master[i], m = exp_avg[i], v = exp_avg_sq[i];
+            adamw1(c, scale, grad1<K>(pp, k, gf32, i), p, m, v);
+            master[i] = p;
+            exp_avg[i] = m;
+            exp_avg_sq[i] = v;
+            if constexpr (WRITE_BF16) out[i] = (uint16_t)f32_to_bf16(p);
+        }
+    } else {
+        const uint64_t i = element_index();
+        if (i >= s.n) return;
         float p = master[i], m = exp_avg[i], v = exp_avg_sq[i];
-        adamw1(c, scale, grad1<K>(pp, k, gf32, i), p, m, v);
+        const float g = grad1<K>(pp, k, gf32, i);
+        adamw1(c, clip_scale(c, sqnorm), g, p, m, v);
         master[i] = p;
         exp_avg[i] = m;
         exp_avg_sq[i] = v;
@@ -462,9 +498,8 @@ __global__ void __launch_bounds__(kNormThreads) absmax_kernel(const float *__res
 #pragma unroll
             for (int c = 0; c < VEC; ++c) m = max(m, abs_bits(t[c]));
         }
-        uint64_t i;
-        if (blockIdx.x == 0 && threadIdx.x < 2 * (VEC - 1) && edge_index<VEC>(s, threadIdx.x, i))
-            m = max(m, abs_bits(x[i]));
+        if (blockIdx.x == 0)
+            for (uint32_t t = threadIdx.x; t < s.head + s.tail; t += kNormThreads) m = max(m, abs_bits(x[edge_elem<VEC>(s, t)]));
     } else {
         for (uint64_t i = first; i < s.n; i += stride) m = max(m, abs_bits(x[i]));
     }
@@ -495,7 +530,8 @@ __global__ void __launch_bounds__(kThreads) cast_fp8_kernel(const float *__restr
     constexpr int VEC = 4;
     const float scale = *d_scale;
     if (s.vectorised) {
-        for (uint64_t v = global_thread(); v < s.nvec; v += grid_threads()) {
+        const uint64_t v = vector_index();
+        if (v < s.nvec) {
             const uint64_t e = s.head + v * VEC;
             float x[VEC];
             ld_f32<VEC>(master, e, x);
@@ -504,11 +540,14 @@ __global__ void __launch_bounds__(kThreads) cast_fp8_kernel(const float *__restr
             for (int c = 0; c < VEC; ++c) w |= f32_to_e4m3(x[c] * scale) << (8 * c);
             st_stream(reinterpret_cast<uint32_t *>(out + e), w);
         }
-        uint64_t i;
-        if (blockIdx.x == 0 && threadIdx.x < 2 * (VEC - 1) && edge_index<VEC>(s, threadIdx.x, i))
-            out[i] = (uint8_t)f32_to_e4m3(master[i] * scale);
+        if (blockIdx.x == 0)
+            for (uint32_t t = threadIdx.x; t < s.head + s.tail; t += kRwThreads) {
+                const uint64_t i = edge_elem<VEC>(s, t);
+                out[i] = (uint8_t)f32_to_e4m3(master[i] * scale);
+            }
     } else {
-        for (uint64_t i = global_thread(); i < s.n; i += grid_threads()) out[i] = (uint8_t)f32_to_e4m3(master[i] * scale);
+        const uint64_t i = element_index();
+        if (i < s.n) out[i] = (uint8_t)f32_to_e4m3(master[i] * scale);
     }
 }
 
@@ -518,14 +557,14 @@ struct Stream16 {
     uint32_t elem;   // bytes per element: 2 or 4
 };
 
-// Smallest head in 0..vec-1 at which every stream is aligned for its vector access
-// (vec * elem bytes, at most 16), or -1.
-int common_head(const Stream16 *st, int ns, int vec) {
-    for (int h = 0; h < vec; ++h) {
+// Smallest head below `limit` at which every stream sits on a multiple of min(align, vec * elem)
+// bytes (align = 16: its vector access; align = 128: a whole line), or -1.
+int common_head(const Stream16 *st, int ns, int vec, uintptr_t align, int limit) {
+    for (int h = 0; h < limit; ++h) {
         bool ok = true;
         for (int i = 0; i < ns && ok; ++i) {
-            uintptr_t need = (uintptr_t)vec * st[i].elem;
-            if (need > 16) need = 16;
+            uintptr_t need = align;
+            if (align <= 16 && (uintptr_t)vec * st[i].elem < need) need = (uintptr_t)vec * st[i].elem;
             ok = ((reinterpret_cast<uintptr_t>(st[i].ptr) + (uintptr_t)h * st[i].elem) & (need - 1)) == 0;
         }
         if (ok) return h;
@@ -534,22 +573,88 @@ int common_head(const Stream16 *st, int ns, int vec) {
 }
 
 Span make_span(uint64_t n, const Stream16 *st, int ns, int vec) {
-    Span s{n, 0, 0, 0};
-    int h = common_head(st, ns, vec);
+    Span s{n, 0, 0, 0, 0};
+    uint32_t smallest = 4;
+    for (int i = 0; i < ns; ++i)
+        if (st[i].elem < smallest) smallest = st[i].elem;
+    int h = common_head(st, ns, vec, 128, (int)(128 / smallest));   // line-aligned pieces when the streams allow it
+    if (h < 0 || n < (uint64_t)h + vec) h = common_head(st, ns, vec, 16, vec);
     if (h >= 0 && n >= (uint64_t)h + vec) {
         s.head = (uint32_t)h;
         s.nvec = (n - (uint64_t)h) / vec;
+        s.tail = (uint32_t)(n - (uint64_t)h - s.nvec * vec);
         s.vectorised = 1;
     }
     return s;
 }
 
-// One lane per vector (or per element on the element-wise path), the whole range in one grid.
-int full_grid(const Span &s) {
-    uint64_t work = s.vectorised ? s.nvec : s.n;
-    uint64_t blocks = (work + kThreads - 1) / kThreads;
-    if (blocks > kMaxGrid) blocks = kMaxGrid;   // the kernels loop, so a capped grid is still correct
-    return blocks == 0 ? 1 : (int)blocks;
+// One lane per vector in one-wave workgroups under the occupancy cap, or, on the element-wise path,
+// one lane per element in 256-thread workgroups; the whole range in one grid either way.
+struct RwLaunch {
+    dim3 grid, block;
+    unsigned lds;
+};
+
+unsigned occupancy_lds(unsigned load_bytes_per_lane);
+
+RwLaunch rw_launch(const Span &s, unsigned load_bytes_per_lane) {
+    const uint64_t work = s.vectorised ? s.nvec : s.n;
+    const unsigned threads = s.vectorised ? kRwThreads : kThreads;
+    uint64_t blocks = (work + threads - 1) / threads;   // <= kMaxGrid: the entry points refuse larger launches
+    if (blocks == 0) blocks = 1;
+    return RwLaunch{dim3((unsigned)blocks), dim3(threads), s.vectorised ? occupancy_lds(load_bytes_per_lane) : 0u};
+}
+
+// Reduce with the norm fused in: one block per kReduceNormRows * 256 vectors on the vector path,
+// a capped grid-stride grid on the element-wise path; every block leaves one double.
+constexpr int kReduceNormRows = 4;
+constexpr int kSliceBlocks = 256;
+
+uint64_t reduce_norm_grid(const Span &s) {
+    uint64_t blocks;
+    if (s.vectorised) {
+        const uint64_t per = (uint64_t)kReduceNormRows * kRwThreads;
+        blocks = (s.nvec + per - 1) / per;
+    } else {
+        blocks = (s.n + kThreads - 1) / kThreads;
+        if (blocks > (uint64_t)kNormBlocks) blocks = kNormBlocks;
+    }
+    return blocks == 0 ? 1 : blocks;
+}
+
+// Upper bound of reduce_norm_grid over every alignment of a launch of `len` elements.
+uint64_t reduce_norm_blocks_max(uint64_t len) {
+    const uint64_t per = (uint64_t)kReduceNormRows * kRwThreads * kVecRW;
+    uint64_t blocks = len / per + 2;
+    if (blocks < (uint64_t)kNormBlocks) blocks = kNormBlocks;
+    return blocks;
+}
+
+// Occupancy cap of the read+write kernels.  With one-wave workgroups and only as many waves resident
+// per CU as it takes to keep ~56 KiB of loads in flight (8 waves for the k = 8 fused step), the same
+// kernels move 5-12 % more bytes per second than at full occupancy (32 waves): fewer waves in flight
+// keep the window of addresses being read and written at any moment small, and reads and writes
+// disturb each other less.  The cap is imposed by giving every workgroup an unused slice of the CU's
+// 160 KiB of LDS.  `load_bytes_per_lane` is what one lane has in flight before it waits.
+int rw_waves_per_cu(unsigned load_bytes_per_lane) {
+    static int inflight_kib = 0, min_waves = 0;
+    if (inflight_kib == 0) {   // developer knobs for sweeps
+        const char *a = getenv("AMSP_INFLIGHT_KIB"), *b = getenv("AMSP_MIN_WAVES");
+        int x = a ? atoi(a) : 0, y = b ? atoi(b) : 0;
+        min_waves = (y >= 3 && y <= 32) ? y : 8;
+        inflight_kib = (x >= 8 && x <= 1024) ? x : 56;
+    }
+    const unsigned per_wave = 64u * load_bytes_per_lane;
+    int waves = (int)(((unsigned)inflight_kib * 1024u + per_wave - 1) / per_wave);
+    if (waves < min_waves) waves = min_waves;
+    return waves > 32 ? 32 : waves;
+}
+
+// Bytes of dynamic LDS per one-wave workgroup so that at most that many of them fit a CU.
+unsigned occupancy_lds(unsigned load_bytes_per_lane) {
+    const int waves = rw_waves_per_cu(load_bytes_per_lane);
+    if (waves >= 32) return 0;
+    return (unsigned)((160 * 1024 / waves) & ~255);
 }
 
 int cu_count() {
@@ -564,32 +669,6 @@ int cu_count() {
     return cached[dev];
 }
 
-// Reduce with the norm fused in: one block per kReduceNormRows * 256 vectors on the vector path,
-// a capped grid-stride grid on the element-wise path; every block leaves one double.
-constexpr int kReduceNormRows = 4;
-constexpr int kSliceBlocks = 256;
-
-uint64_t reduce_norm_grid(const Span &s) {
-    uint64_t blocks;
-    if (s.vectorised) {
-        const uint64_t per = (uint64_t)kReduceNormRows * kThreads;
-        blocks = (s.nvec + per - 1) / per;
-    } else {
-        blocks = (s.n + kThreads - 1) / kThreads;
-        if (blocks > (uint64_t)kNormBlocks) blocks = kNormBlocks;
-    }
-    if (blocks > kMaxGrid) blocks = kMaxGrid;
-    return blocks == 0 ? 1 : blocks;
-}
-
-// Upper bound of reduce_norm_grid over every alignment of a launch of `len` elements.
-uint64_t reduce_norm_blocks_max(uint64_t len) {
-    const uint64_t per = (uint64_t)kReduceNormRows * kThreads * kVecRW;
-    uint64_t blocks = len / per + 2;
-    if (blocks < (uint64_t)kNormBlocks) blocks = kNormBlocks;
-    return blocks;
-}
-
 // The norm pass: two 1024-thread blocks per CU (what a CU holds), at most kNormBlocks.
 int norm_grid(const Span &s) {
     uint64_t work = s.vectorised ? s.nvec : s.n;
@@ -598,6 +677,13 @@ int norm_grid(const Span &s) {
     if (cap > kNormBlocks) cap = kNormBlocks;
     if (blocks > cap) blocks = cap;
     return blocks == 0 ? 1 : (int)blocks;
+}
+
+// One launch covers at most this many elements (one wave per 256 of them in a grid of < 2^31 blocks):
+// about 5.5e11, beyond any buffer that fits the device.
+constexpr uint64_t kMaxLaunchElems = kMaxGrid * (uint64_t)kRwThreads;
+bool too_long(uint64_t n, uint64_t bucket_elems) {
+    return ((bucket_elems != 0 && bucket_elems < n) ? bucket_elems : n) > kMaxLaunchElems;
 }
 
 bool misaligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
@@ -681,13 +767,26 @@ struct NormBatch {
     }
 };
 
+// Every k up to 16 has its own instantiation (all k loads of a vector in flight at once); larger k
+// take the run-time loop.
 #define AMSP_DISPATCH_K(k, CALL)                 \
     switch (k) {                                 \
         case 1: { constexpr int KK = 1; CALL; } break;   \
         case 2: { constexpr int KK = 2; CALL; } break;   \
+        case 3: { constexpr int KK = 3; CALL; } break;   \
         case 4: { constexpr int KK = 4; CALL; } break;   \
+        case 5: { constexpr int KK = 5; CALL; } break;   \
+        case 6: { constexpr int KK = 6; CALL; } break;   \
+        case 7: { constexpr int KK = 7; CALL; } break;   \
         case 8: { constexpr int KK = 8; CALL; } break;   \
-        case 16: { constexpr int KK = 16; CALL; } break; \
+        case 9: { constexpr int KK = 9; CALL; } break;   \
+        case 10: { constexpr int KK = 10; CALL; } break;   \
+        case 11: { constexpr int KK = 11; CALL; } break;   \
+        case 12: { constexpr int KK = 12; CALL; } break;   \
+        case 13: { constexpr int KK = 13; CALL; } break;   \
+        case 14: { constexpr int KK = 14; CALL; } break;   \
+        case 15: { constexpr int KK = 15; CALL; } break;   \
+        case 16: { constexpr int KK = 16; CALL; } break;   \
         default: { constexpr int KK = -1; CALL; } break; \
     }
 
@@ -762,12 +861,14 @@ int amsp_shard_range(uint64_t total_elems, uint32_t shard_factor, uint32_t rank,
 
 int amsp_cast_param_shard(const float *master, uint16_t *param_bf16_out, uint64_t n, void *stream) {
     if (n == 0) return AMSP_OK;
+    if (too_long(n, 0)) return AMSP_EINVAL;
     if (master == nullptr || param_bf16_out == nullptr) return AMSP_ENULL;
     if (misaligned(master, 4) || misaligned(param_bf16_out, 2)) return AMSP_EALIGN;
     Stream16 st[2] = {{master, 4}, {param_bf16_out, 2}};
     Span s = make_span(n, st, 2, kVecRW);
     clear_stale_error();
-    hipLaunchKernelGGL(cast_kernel, dim3(full_grid(s)), dim3(kThreads), 0, (hipStream_t)stream, master, param_bf16_out, s);
+    const RwLaunch L = rw_launch(s, 16);
+    hipLaunchKernelGGL(cast_kernel, L.grid, L.block, L.lds, (hipStream_t)stream, master, param_bf16_out, s);
     return launched();
 }
 
@@ -798,6 +899,7 @@ int amsp_reduce_grad_shard(const uint16_t *const *partials, uint32_t k, uint64_t
         }
         return AMSP_OK;
     }
+    if (too_long(n, bucket_elems)) return AMSP_EINVAL;
     if (grad_out == nullptr) return AMSP_ENULL;
     if (misaligned(grad_out, 4)) return AMSP_EALIGN;
     bool first = true;
@@ -809,14 +911,17 @@ int amsp_reduce_grad_shard(const uint16_t *const *partials, uint32_t k, uint64_t
         Span s = make_span(len, st, ns, kVecRW);
         clear_stale_error();
         if (!norm) {
-            AMSP_DISPATCH_K(k, hipLaunchKernelGGL((reduce_kernel<KK, false, 1>), dim3(full_grid(s)), dim3(kThreads), 0,
-                                                  hs, q, (int)k, grad_out + off, accumulate, block_sums, s));
+            const RwLaunch L = rw_launch(s, 8 * k + (accumulate ? 16 : 0));
+            AMSP_DISPATCH_K(k, hipLaunchKernelGGL((reduce_kernel<KK, false, 1>), L.grid, L.block, L.lds, hs, q, (int)k,
+                                                  grad_out + off, accumulate, block_sums, s));
             return launched();
         }
         const uint64_t blocks = reduce_norm_grid(s);
         AMSP_DISPATCH_K(k, hipLaunchKernelGGL((reduce_kernel<KK, true, kReduceNormRows>), dim3((unsigned)blocks),
-                                              dim3(kThreads), 0, hs, q, (int)k, grad_out + off, accumulate,
-                                              block_sums, s));
+                                              dim3(s.vectorised ? kRwThreads : kThreads),
+                                              s.vectorised ? occupancy_lds(kReduceNormRows * (8 * k + (accumulate ? 16 : 0))) : 0u,
+                                              hs, q, (int)k,
+                                              grad_out + off, accumulate, block_sums, s));
         if (launched() != AMSP_OK) return (int)AMSP_EDEVICE;
         const int acc = (sqnorm_accumulate || !first) ? 1 : 0;
         first = false;
@@ -867,6 +972,7 @@ int amsp_adamw_step_shard(const uint16_t *const *partials, uint32_t k, const flo
         !(hp->beta2 >= 0.0f && hp->beta2 < 1.0f) || hp->eps < 0.0f)
         return AMSP_EINVAL;
     if (n == 0) return AMSP_OK;
+    if (too_long(n, bucket_elems)) return AMSP_EINVAL;
     if (master == nullptr || exp_avg == nullptr || exp_avg_sq == nullptr) return AMSP_ENULL;
     if (k == 0 && grad_f32 == nullptr) return AMSP_ENULL;
     if (misaligned(master, 4) || misaligned(exp_avg, 4) || misaligned(exp_avg_sq, 4) ||
@@ -899,12 +1005,14 @@ int amsp_adamw_step_shard(const uint16_t *const *partials, uint32_t k, const flo
         uint16_t *out = param_bf16_out ? param_bf16_out + off : nullptr;
         if (out) st[ns++] = Stream16{out, 2};
         Span s = make_span(len, st, ns, kVecRW);
-        const dim3 grid(full_grid(s)), block(kThreads);
+        const RwLaunch L = rw_launch(s, (k != 0 ? 8 * k : 16) + 48);
+        const dim3 grid = L.grid, block = L.block;
+        const unsigned lds = L.lds;
         clear_stale_error();
 #define AMSP_LAUNCH_ADAMW(KV)                                                                              \
-        if (out) hipLaunchKernelGGL((adamw_kernel<KV, true>), grid, block, 0, hs, q, (int)k, gf, master + off, \
+        if (out) hipLaunchKernelGGL((adamw_kernel<KV, true>), grid, block, lds, hs, q, (int)k, gf, master + off, \
                                     exp_avg + off, exp_avg_sq + off, out, c, s);                            \
-        else hipLaunchKernelGGL((adamw_kernel<KV, false>), grid, block, 0, hs, q, (int)k, gf, master + off,  \
+        else hipLaunchKernelGGL((adamw_kernel<KV, false>), grid, block, lds, hs, q, (int)k, gf, master + off, \
                                 exp_avg + off, exp_avg_sq + off, out, c, s)
         if (k == 0) {
             AMSP_LAUNCH_ADAMW(0);
@@ -1025,13 +1133,14 @@ int amsp_adamw_step_segments(const uint16_t *const *partials_flat, uint32_t k, u
 int amsp_cast_param_fp8_shard(const float *master, uint64_t n, const float *d_scale, uint8_t *param_fp8_out,
                               void *stream) {
     if (n == 0) return AMSP_OK;
+    if (too_long(n, 0)) return AMSP_EINVAL;
     if (master == nullptr || d_scale == nullptr || param_fp8_out == nullptr) return AMSP_ENULL;
     if (misaligned(master, 4) || misaligned(d_scale, 4)) return AMSP_EALIGN;
     Stream16 st[2] = {{master, 4}, {param_fp8_out, 1}};
     Span s = make_span(n, st, 2, 4);
     clear_stale_error();
-    hipLaunchKernelGGL(cast_fp8_kernel, dim3(full_grid(s)), dim3(kThreads), 0, (hipStream_t)stream, master, d_scale,
-                       param_fp8_out, s);
+    const RwLaunch L = rw_launch(s, 16);
+    hipLaunchKernelGGL(cast_fp8_kernel, L.grid, L.block, L.lds, (hipStream_t)stream, master, d_scale, param_fp8_out, s);
     return launched();
 }
 
