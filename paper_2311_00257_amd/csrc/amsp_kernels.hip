@@ -7,10 +7,19 @@
 //     owns 4 consecutive elements per stream (8-byte bf16 and 16-byte fp32 accesses, so a wave
 //     instruction covers 512 B or 1 KiB without gaps).  Letting a lane own 8 elements makes
 //     its fp32 accesses two 16-byte pieces 32 bytes apart and costs 10-20 % of bandwidth.
-//   - Kernels that read AND write run one vector per lane on a grid that covers the whole
-//     range ("full grid"): the hardware dispatcher then hands out the range in address order
-//     and balances the CUs.  The same kernels as persistent grid-stride loops reach ~4.5 TB/s
+//   - Kernels that read AND write are straight-line code, one vector per lane, on a grid that
+//     covers the whole range once: the hardware dispatcher hands out the range in address order
+//     and balances the CUs.  The same body as a persistent grid-stride loop reaches ~4.5 TB/s
 //     instead of ~5.8 TB/s on the k = 8 fused step.
+//   - Those kernels run one-wave (64-thread) workgroups under an occupancy cap: only as many
+//     waves per CU as keep ~56 KiB of loads in flight (8 for k = 8, where the hardware would take
+//     32).  That brings the k = 8 fused step from ~5.8 to 6.4-6.5 TB/s.  The cap is an unused slice
+//     of LDS per workgroup.  With so few waves, nothing may stand between a wave's start and its
+//     loads: no blockDim/gridDim (a dispatch-packet fetch), the clip scale worked out after the
+//     loads are in flight, and a scheduling barrier that keeps all k + 3 loads ahead of the first
+//     wait.
+//   - The head peeled off a misaligned range brings every stream to a 128-byte line, so that each
+//     wave's piece of each stream is whole lines.
 //   - The read-only norm pass is the opposite case: a persistent grid of exactly the resident
 //     size (two 1024-thread blocks per CU) with a grid-stride loop and 16-byte loads reads at
 //     6.6-6.9 TB/s, more than any full-grid or 256-thread variant, and its per-block sums fit a
