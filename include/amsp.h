@@ -60,7 +60,8 @@ enum {
     AMSP_ENULL = -2,      /* a required pointer is NULL */
     AMSP_EALIGN = -3,     /* a pointer is not aligned to its element size */
     AMSP_EWORKSPACE = -4, /* workspace smaller than the entry point's requirement */
-    AMSP_EDEVICE = -5     /* a HIP call failed */
+    AMSP_EDEVICE = -5,    /* a HIP call failed */
+    AMSP_ENOPLAN = -6     /* amsp_plan_sharding: no sharding fits the memory limit and the table */
 };
 
 #define AMSP_MAX_K 32u
@@ -247,6 +248,57 @@ int amsp_fp8_payload_segments(const float *master_local, uint64_t local_elems,
                               const amsp_segment *segments, uint32_t num_segments,
                               uint64_t flat_elems, uint8_t *param_fp8_flat,
                               float *d_amax, float *d_scale, void *stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * Sharding planner (Section V-B).  Chooses the device meshes s_p, s_g, s_os = (GPUs per node) x
+ * (nodes) over which parameters, gradients and optimizer states are sharded: the feasible tuple of
+ * least per-step communication time
+ *     T_comm = T_p + T_g + T_os^0 + T_os^1                                   (Section IV-C)
+ *     T_p    = M L sum_i ( 2 t(AG, 2 Phi_i, s_p) + t(RS, 2 Phi_i, s_p) )
+ *     T_os^0 = 2 Phi / (U s_p) * t(AR, U, s_dp / s_p)
+ *     T_os^1 = s_os / s_p * t(BC, 2 Phi / s_os, s_os / s_p)
+ *     T_g    = (M - 1) 2 Phi / (U s_p) * t(AR, U, s_g / s_p)
+ * with t(o, v, mesh) = v / w(o, v, mesh) from a profiled bandwidth table (Section IV-A; linear in v
+ * between profiled sizes, end values outside; a one-GPU mesh costs 0), subject to
+ *     2 Phi/s_p + 2 Phi/s_g + 12 Phi/s_os + activations + temporaries <= GPU memory   (Eq. 2, IV-D)
+ *     1 <= s_p <= s_g <= s_os <= s_dp in each mesh dimension                          (Eq. 3, 4)
+ *     every factor divides s_dp in its dimension                                      (Eq. 5, 6)
+ *     a component spans nodes only once it spans the whole node                       (Eq. 7)
+ *     s_g in {s_p, s_os}                                                              (Section IV-C.3)
+ * and s_dp = gpus_per_node x nodes.  Where the paper is silent: a mesh missing from the table makes a
+ * tuple unusable; ties go to the tuple that is first in lexicographic order of
+ * (s_p^0, s_p^1, s_g^0, s_g^1, s_os^0, s_os^1).  Host only, pure; every pointer is host memory.
+ */
+enum { AMSP_OP_ALLGATHER = 0, AMSP_OP_REDUCESCATTER = 1, AMSP_OP_ALLREDUCE = 2, AMSP_OP_BROADCAST = 3 };
+
+typedef struct amsp_bw_sample {   /* one profiled point: effective bandwidth of `op` on mesh p0 x p1 */
+    uint32_t op, p0, p1;
+    double bytes;                 /* message size v */
+    double bytes_per_s;           /* w(op, v, p0 x p1) */
+} amsp_bw_sample;
+
+typedef struct amsp_plan_problem {
+    double phi;                   /* parameters of the model */
+    uint32_t layers;              /* L */
+    uint32_t modules_per_layer;   /* K */
+    const double *module_params;  /* Phi_i, host array [modules_per_layer] */
+    uint32_t micro_batches;       /* M >= 1 */
+    double bucket_bytes;          /* U > 0 */
+    uint32_t gpus_per_node;       /* R = s_dp^0 */
+    uint32_t nodes;               /* N = s_dp^1 */
+    double gpu_memory_bytes, activation_bytes, tmp_bytes;
+} amsp_plan_problem;
+
+typedef struct amsp_plan {
+    uint32_t sp0, sp1, sg0, sg1, sos0, sos1;
+    double t_p, t_g, t_os0, t_os1, t_comm; /* seconds */
+    double d_modelstate;                   /* bytes per GPU */
+} amsp_plan;
+
+/* best: host out.  feasible_count: host out or NULL, the number of tuples that passed every constraint
+ * and could be priced.  Errors: AMSP_ENULL, AMSP_EINVAL (zero R, N, M, Phi or U), AMSP_ENOPLAN. */
+int amsp_plan_sharding(const amsp_plan_problem *problem, const amsp_bw_sample *table, uint32_t rows,
+                       amsp_plan *best, uint32_t *feasible_count);
 
 #ifdef __cplusplus
 }

@@ -15,13 +15,15 @@ from typing import Optional, Sequence
 
 from . import build as _build
 
-AMSP_OK, AMSP_EINVAL, AMSP_ENULL, AMSP_EALIGN, AMSP_EWORKSPACE, AMSP_EDEVICE = 0, -1, -2, -3, -4, -5
+AMSP_OK, AMSP_EINVAL, AMSP_ENULL, AMSP_EALIGN, AMSP_EWORKSPACE, AMSP_EDEVICE, AMSP_ENOPLAN = 0, -1, -2, -3, -4, -5, -6
+AMSP_OP_ALLGATHER, AMSP_OP_REDUCESCATTER, AMSP_OP_ALLREDUCE, AMSP_OP_BROADCAST = 0, 1, 2, 3
 AMSP_MAX_K = 32
 
 EXPORTS = ("amsp_status_string", "amsp_workspace_bytes", "amsp_reduce_workspace_bytes", "amsp_shard_range",
            "amsp_reduce_grad_shard", "amsp_grad_sqnorm", "amsp_adamw_step_shard", "amsp_cast_param_shard",
            "amsp_partition_tensors", "amsp_owned_segments", "amsp_grad_sqnorm_segments",
-           "amsp_adamw_step_segments", "amsp_cast_param_fp8_shard", "amsp_fp8_payload_segments")
+           "amsp_adamw_step_segments", "amsp_cast_param_fp8_shard", "amsp_fp8_payload_segments",
+           "amsp_plan_sharding")
 
 
 class AmspError(RuntimeError):
@@ -32,6 +34,24 @@ class AmspError(RuntimeError):
 
 class _Segment(ctypes.Structure):
     _fields_ = [("flat_offset", ctypes.c_uint64), ("local_offset", ctypes.c_uint64), ("length", ctypes.c_uint64)]
+
+
+class _BwSample(ctypes.Structure):
+    _fields_ = [("op", ctypes.c_uint32), ("p0", ctypes.c_uint32), ("p1", ctypes.c_uint32),
+                ("bytes", ctypes.c_double), ("bytes_per_s", ctypes.c_double)]
+
+
+class _PlanProblem(ctypes.Structure):
+    _fields_ = [("phi", ctypes.c_double), ("layers", ctypes.c_uint32), ("modules_per_layer", ctypes.c_uint32),
+                ("module_params", ctypes.POINTER(ctypes.c_double)), ("micro_batches", ctypes.c_uint32),
+                ("bucket_bytes", ctypes.c_double), ("gpus_per_node", ctypes.c_uint32), ("nodes", ctypes.c_uint32),
+                ("gpu_memory_bytes", ctypes.c_double), ("activation_bytes", ctypes.c_double),
+                ("tmp_bytes", ctypes.c_double)]
+
+
+class _Plan(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_uint32) for n in ("sp0", "sp1", "sg0", "sg1", "sos0", "sos1")] + \
+               [(n, ctypes.c_double) for n in ("t_p", "t_g", "t_os0", "t_os1", "t_comm", "d_modelstate")]
 
 
 class _Hparams(ctypes.Structure):
@@ -93,6 +113,8 @@ def load() -> ctypes.CDLL:
                                                  ctypes.POINTER(_Hparams), vp]
         lib.amsp_cast_param_fp8_shard.argtypes = [vp, u64, vp, vp, vp]
         lib.amsp_fp8_payload_segments.argtypes = [vp, u64, ctypes.POINTER(_Segment), u32, u64, vp, vp, vp, vp]
+        lib.amsp_plan_sharding.argtypes = [ctypes.POINTER(_PlanProblem), ctypes.POINTER(_BwSample), u32,
+                                           ctypes.POINTER(_Plan), pu32]
         for name in EXPORTS[3:]:
             getattr(lib, name).restype = ci
         _lib = lib
@@ -256,3 +278,22 @@ def amsp_fp8_payload_segments(master_local, local_elems: int, segments, flat_ele
     _check(load().amsp_fp8_payload_segments(_ptr(master_local), local_elems, segs, ns, flat_elems,
                                             _ptr(param_fp8_flat), _ptr(d_amax), _ptr(d_scale), _stream(stream)),
            "amsp_fp8_payload_segments")
+
+
+# ------------------------------------------------------------------ sharding planner
+def amsp_plan_sharding(phi: float, layers: int, module_params: Sequence[float], micro_batches: int,
+                       bucket_bytes: float, gpus_per_node: int, nodes: int, gpu_memory_bytes: float,
+                       activation_bytes: float, tmp_bytes: float, table):
+    """table: iterable of (op, p0, p1, bytes, bytes_per_s).  Returns (plan dict, feasible_count);
+    raises AmspError(AMSP_ENOPLAN) when nothing fits."""
+    mods = (ctypes.c_double * max(len(module_params), 1))(*module_params)
+    rows = [_BwSample(int(o), int(a), int(b), float(v), float(w)) for (o, a, b, v, w) in table]
+    arr = (_BwSample * max(len(rows), 1))(*rows)
+    pb = _PlanProblem(phi, layers, len(module_params), mods, micro_batches, bucket_bytes, gpus_per_node, nodes,
+                      gpu_memory_bytes, activation_bytes, tmp_bytes)
+    best, count = _Plan(), ctypes.c_uint32()
+    _check(load().amsp_plan_sharding(ctypes.byref(pb), arr, len(rows), ctypes.byref(best), ctypes.byref(count)),
+           "amsp_plan_sharding")
+    return (dict(s=(best.sp0, best.sp1, best.sg0, best.sg1, best.sos0, best.sos1), t_p=best.t_p, t_g=best.t_g,
+                 t_os0=best.t_os0, t_os1=best.t_os1, t_comm=best.t_comm, d_modelstate=best.d_modelstate),
+            count.value)

@@ -1,7 +1,7 @@
 """Builds the HIP shared libraries in-tree for gfx950 with hipcc.
 
 ``python -m paper_2311_00257_amd.build`` compiles
-  csrc/amsp_kernels.hip -> libamsp.so        (the C-ABI library declared in include/amsp.h)
+  csrc/amsp_kernels.hip + csrc/amsp_planner.cpp -> libamsp.so   (the C-ABI library of include/amsp.h)
   csrc/synth_fill.hip   -> libamsp_synth.so  (device fill kernels of the input generator)
 hipcc cross-compiles without a GPU.
 """
@@ -25,8 +25,8 @@ HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
                "-Wall", "-Wno-unused-command-line-argument", "-I", INCLUDE]
 
-TARGETS = ((os.path.join(CSRC, "amsp_kernels.hip"), LIB_AMSP),
-           (os.path.join(CSRC, "synth_fill.hip"), LIB_SYNTH))
+TARGETS = (((os.path.join(CSRC, "amsp_kernels.hip"), os.path.join(CSRC, "amsp_planner.cpp")), LIB_AMSP),
+           ((os.path.join(CSRC, "synth_fill.hip"),), LIB_SYNTH))
 
 
 def hipcc() -> str:
@@ -37,9 +37,9 @@ def hipcc() -> str:
 
 
 def build_all(extra_flags=(), verbose: bool = True) -> None:
-    for src, out in TARGETS:
+    for srcs, out in TARGETS:
         tmp = out + ".tmp%d" % os.getpid()
-        cmd = [hipcc(), *HIPCC_FLAGS, *extra_flags, "-o", tmp, src]
+        cmd = [hipcc(), *HIPCC_FLAGS, *extra_flags, "-o", tmp, *srcs]
         if verbose:
             print(" ".join(cmd), flush=True)
         subprocess.check_call(cmd)

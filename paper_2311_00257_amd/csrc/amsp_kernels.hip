@@ -852,6 +852,7 @@ const char *amsp_status_string(int status) {
         case AMSP_EALIGN: return "pointer not aligned to its element size";
         case AMSP_EWORKSPACE: return "workspace too small";
         case AMSP_EDEVICE: return "HIP call failed";
+        case AMSP_ENOPLAN: return "no sharding plan is feasible";
         default: return "unknown status";
     }
 }

@@ -97,3 +97,73 @@ def test_planted_mistake_is_caught(name, old, new, golden_dir):
         finally:
             oracle._lib = good
     assert failed, "no pin noticed: " + name
+
+
+# --------------------------------------------------------------------------- the planner oracle
+import importlib.util
+import sys
+import types
+
+import test_planner as planner_pins
+
+PLANNER_SRC = open(os.path.join(os.path.dirname(oracle.__file__), "planner.py")).read()
+
+PLANNER_MUTATIONS = [
+    ("T_p: AllGather counted once", "t_p += 2 * ag + rs", "t_p += ag + rs"),
+    ("T_p: not multiplied by the layers", "t_p *= M * L", "t_p *= M"),
+    ("T_g: every micro-batch instead of all but the last", "t_g = (M - 1) * 2 * phi", "t_g = M * 2 * phi"),
+    ("T_os0: bucket count ignores s_p", "t_os0 = 2 * phi / (U * sp) * ar_os", "t_os0 = 2 * phi / U * ar_os"),
+    ("T_os1: one broadcast instead of s_os/s_p", "t_os1 = so / sp * bc", "t_os1 = bc"),
+    ("T_os1: broadcast of the whole model", "coll_time(table, BC, 2 * phi / so,", "coll_time(table, BC, 2 * phi,"),
+    ("memory: optimizer states counted as 8 bytes", "+ 12 * phi / so", "+ 8 * phi / so"),
+    ("memory: activations ignored", 'c["d_modelstate"] + activation + tmp > gpu_memory', 'c["d_modelstate"] > gpu_memory'),
+    ("constraint: s_g free between s_p and s_os", "if (sg0, sg1) != (sp0, sp1) and (sg0, sg1) != (so0, so1):", "if False:"),
+    ("constraint: nodes before the node is full", "if any(b > 1 and a != R for a, b in", "if any(False for a, b in"),
+    ("constraint: factors need not divide", "if any(R % a for a in (sp0, sg0, so0)) or any(N % a for a in (sp1, sg1, so1)):", "if False:"),
+    ("constraint: chain s_p <= s_g <= s_os not enforced", "if not (1 <= sp0 <= sg0 <= so0 <= R and 1 <= sp1 <= sg1 <= so1 <= N):", "if not (1 <= sp0 <= R and 1 <= so0 <= R and 1 <= sp1 <= N and 1 <= so1 <= N):"),
+    ("AllReduce mesh: the sharded group instead of its complement", "coll_time(table, AR, U, R // sp0, N // sp1)", "coll_time(table, AR, U, sp0, sp1)"),
+    ("interpolation: nearest lower sample", "return w0 if b1 == b0 else w0 + (w1 - w0) * (v - b0) / (b1 - b0)", "return w0"),
+    ("one-GPU mesh priced from the table", "if p0 * p1 == 1:\n        return 0.0", "if False:\n        return 0.0"),
+    ("tie: last tuple wins", 'if best is None or c["t_comm"] < best["t_comm"]:', 'if best is None or c["t_comm"] <= best["t_comm"]:'),
+]
+
+PLANNER_PINS = [getattr(planner_pins, n) for n in dir(planner_pins)
+                if n.startswith("test_") and "library" not in n]
+
+
+def _run_planner_pins(golden_dir):
+    failed = []
+    for fn in PLANNER_PINS:
+        marks = [m for m in getattr(fn, "pytestmark", []) if m.name == "parametrize"]
+        arg_sets = [{}]
+        if marks:
+            names = [a.strip() for a in marks[0].args[0].split(",")]
+            arg_sets = [dict(zip(names, v if isinstance(v, tuple) else (v,))) for v in marks[0].args[1]]
+        for kwargs in arg_sets:
+            kwargs = dict(kwargs)
+            if "golden_dir" in fn.__code__.co_varnames[:fn.__code__.co_argcount]:
+                kwargs["golden_dir"] = golden_dir
+            try:
+                fn(**kwargs)
+            except Exception:
+                failed.append(fn.__name__)
+                break
+    return failed
+
+
+def test_unmutated_planner_passes_this_harness(golden_dir):
+    assert _run_planner_pins(golden_dir) == []
+
+
+@pytest.mark.parametrize("name,old,new", PLANNER_MUTATIONS, ids=[m[0] for m in PLANNER_MUTATIONS])
+def test_planted_planner_mistake_is_caught(name, old, new, golden_dir):
+    assert PLANNER_SRC.count(old) == 1, "mutation target must occur exactly once: %r" % old
+    broken = types.ModuleType("broken_planner")
+    exec(compile(PLANNER_SRC.replace(old, new), "broken_planner.py", "exec"), broken.__dict__)
+    good = planner_pins.P
+    planner_pins.P = broken
+    try:
+        failed = _run_planner_pins(golden_dir)
+    finally:
+        planner_pins.P = good
+    assert failed, "no pin noticed: " + name
