@@ -33,6 +33,8 @@
 #include <stdio.h>
 #include <stdlib.h>
 
+#include <atomic>
+
 #include "amsp.h"
 
 #ifndef AMSP_NT_LOAD
@@ -645,17 +647,19 @@ uint64_t reduce_norm_blocks_max(uint64_t len) {
 // keep the window of addresses being read and written at any moment small, and reads and writes
 // disturb each other less.  The cap is imposed by giving every workgroup an unused slice of the CU's
 // 160 KiB of LDS.  `load_bytes_per_lane` is what one lane has in flight before it waits.
+struct RwKnobs {
+    int inflight_kib, min_waves;
+};
+RwKnobs read_rw_knobs() {   // developer knobs for sweeps; read once (thread-safe static below)
+    const char *a = getenv("AMSP_INFLIGHT_KIB"), *b = getenv("AMSP_MIN_WAVES");
+    const int x = a ? atoi(a) : 0, y = b ? atoi(b) : 0;
+    return RwKnobs{(x >= 8 && x <= 1024) ? x : 56, (y >= 3 && y <= 32) ? y : 8};
+}
 int rw_waves_per_cu(unsigned load_bytes_per_lane) {
-    static int inflight_kib = 0, min_waves = 0;
-    if (inflight_kib == 0) {   // developer knobs for sweeps
-        const char *a = getenv("AMSP_INFLIGHT_KIB"), *b = getenv("AMSP_MIN_WAVES");
-        int x = a ? atoi(a) : 0, y = b ? atoi(b) : 0;
-        min_waves = (y >= 3 && y <= 32) ? y : 8;
-        inflight_kib = (x >= 8 && x <= 1024) ? x : 56;
-    }
+    static const RwKnobs knobs = read_rw_knobs();
     const unsigned per_wave = 64u * load_bytes_per_lane;
-    int waves = (int)(((unsigned)inflight_kib * 1024u + per_wave - 1) / per_wave);
-    if (waves < min_waves) waves = min_waves;
+    int waves = (int)(((unsigned)knobs.inflight_kib * 1024u + per_wave - 1) / per_wave);
+    if (waves < knobs.min_waves) waves = knobs.min_waves;
     return waves > 32 ? 32 : waves;
 }
 
@@ -667,15 +671,15 @@ unsigned occupancy_lds(unsigned load_bytes_per_lane) {
 }
 
 int cu_count() {
-    static int cached[64] = {0};
+    static std::atomic<int> cached[64];   // per device; zero until first asked (any thread may fill it: same value)
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
-    if (cached[dev] == 0) {
-        int n = 0;
+    int n = cached[dev].load(std::memory_order_relaxed);
+    if (n == 0) {
         if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
-        cached[dev] = n;
+        cached[dev].store(n, std::memory_order_relaxed);
     }
-    return cached[dev];
+    return n;
 }
 
 // The norm pass: two 1024-thread blocks per CU (what a CU holds), at most kNormBlocks.
