@@ -290,7 +290,7 @@ def main():
         out["fp8_payload"] = {"ms": fp8_ms, "GB/s": 9 * n / (fp8_ms * 1e-3) / 1e9, "bytes_per_element": 9,
                               "launches": 2 * len(segs) + 2}
         del fp8
-    if not args.no_ceilings:
+    if not args.no_ceilings and not args.calibrate_copy:   # keep the calibration run to one known copy
         out["ceilings"] = ceilings(torch, out, master, n)
     if not args.no_alt and not w.inter_tensor:
         out["alt_step"] = alt_step(args, torch, B, w, n, parts, master, exp_avg, exp_avg_sq, param_bf16, d_sqnorm)
