@@ -95,8 +95,10 @@ int amsp_shard_range(uint64_t total_elems, uint32_t shard_factor, uint32_t rank,
  *   d_sqnorm    device double or NULL.  Not NULL: *d_sqnorm (=|+=) sum_i grad_out[i]^2 of the
  *               values just written (after `accumulate`), in fp64 in a fixed order, added in
  *               bucket order; sqnorm_accumulate 0 overwrites, 1 adds to the value already there
- *   workspace   device, >= amsp_reduce_workspace_bytes(n, bucket_elems), 8-byte aligned, used only
- *               when d_sqnorm != NULL (else may be NULL); no initialisation needed, clobbered
+ *   workspace   device, >= amsp_reduce_workspace_bytes(n, bucket_elems) (about n/1024 doubles: the
+ *               block sums of every bucket side by side, added once after the last bucket),
+ *               8-byte aligned, used only when d_sqnorm != NULL (else may be NULL); no
+ *               initialisation needed, clobbered
  */
 size_t amsp_reduce_workspace_bytes(uint64_t n, uint64_t bucket_elems);
 int amsp_reduce_grad_shard(const uint16_t *const *partials, uint32_t k, uint64_t n,

@@ -335,7 +335,43 @@ __global__ void __launch_bounds__(kNormThreads) sqnorm_kernel(PartialPtrs pp, in
     const uint64_t stride = (uint64_t)gridDim.x * kNormThreads;
     double acc = 0.0;
     if (s.vectorised) {
-        for (uint64_t v = first; v < s.nvec; v += stride) {
+        uint64_t v = first;
+        // With one or two streams a single vector per lane leaves too little in flight: take U vectors,
+        // a grid stride apart, per trip, all their loads issued before the first is used.
+        constexpr int U = (K == 0 || K == 1) ? 4 : (K == 2 ? 2 : 1);
+        if constexpr (U > 1) {
+            constexpr int KS = K == 0 ? 1 : K;
+            typedef typename Bf16Words<VEC == 8 ? 8 : 4>::type W;
+            for (; v + (U - 1) * stride < s.nvec; v += U * stride) {
+                f32x4 a[U];
+                W w[U][KS];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const uint64_t e = s.head + (v + u * stride) * VEC;
+                    if constexpr (K == 0) {
+                        a[u] = ld_stream(reinterpret_cast<const f32x4 *>(gf32 + e));
+                    } else {
+#pragma unroll
+                        for (int j = 0; j < KS; ++j) w[u][j] = ld_stream(reinterpret_cast<const W *>(pp.p[j] + e));
+                    }
+                }
+                loads_issued();
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    float g[VEC];
+                    if constexpr (K == 0) {
+                        g[0] = a[u].x; g[1] = a[u].y; g[2] = a[u].z; g[3] = a[u].w;
+                    } else {
+                        widen_first<VEC>(w[u][0], g);
+#pragma unroll
+                        for (int j = 1; j < KS; ++j) widen_add<VEC>(w[u][j], g);
+                    }
+#pragma unroll
+                    for (int c = 0; c < VEC; ++c) acc = fma((double)g[c], (double)g[c], acc);
+                }
+            }
+        }
+        for (; v < s.nvec; v += stride) {
             float g[VEC];
             grad_vec<K, VEC>(pp, k, gf32, s.head + v * VEC, g);
 #pragma unroll
@@ -636,9 +672,17 @@ uint64_t reduce_norm_grid(const Span &s) {
 // Upper bound of reduce_norm_grid over every alignment of a launch of `len` elements.
 uint64_t reduce_norm_blocks_max(uint64_t len) {
     const uint64_t per = (uint64_t)kReduceNormRows * kRwThreads * kVecRW;
-    uint64_t blocks = len / per + 2;
-    if (blocks < (uint64_t)kNormBlocks) blocks = kNormBlocks;
-    return blocks;
+    const uint64_t vector_path = len / per + 2;
+    uint64_t element_path = (len + kThreads - 1) / kThreads;
+    if (element_path > (uint64_t)kNormBlocks) element_path = kNormBlocks;
+    return vector_path > element_path ? vector_path : element_path;
+}
+
+// Block sums of every bucket of a call lie side by side and are added once, after the last bucket.
+uint64_t reduce_norm_slots(uint64_t n, uint64_t bucket_elems) {
+    if (bucket_elems == 0 || bucket_elems >= n) return reduce_norm_blocks_max(n);
+    const uint64_t full = n / bucket_elems, rest = n % bucket_elems;
+    return full * reduce_norm_blocks_max(bucket_elems) + (rest ? reduce_norm_blocks_max(rest) : 0);
 }
 
 // Occupancy cap of the read+write kernels.  With one-wave workgroups and only as many waves resident
@@ -887,8 +931,7 @@ int amsp_cast_param_shard(const float *master, uint16_t *param_bf16_out, uint64_
 }
 
 size_t amsp_reduce_workspace_bytes(uint64_t n, uint64_t bucket_elems) {
-    const uint64_t launch = (bucket_elems != 0 && bucket_elems < n) ? bucket_elems : n;
-    return (size_t)(reduce_norm_blocks_max(launch) + kSliceBlocks) * sizeof(double);
+    return (size_t)(reduce_norm_slots(n, bucket_elems) + kSliceBlocks) * sizeof(double);
 }
 
 int amsp_reduce_grad_shard(const uint16_t *const *partials, uint32_t k, uint64_t n, uint64_t bucket_elems,
@@ -916,8 +959,8 @@ int amsp_reduce_grad_shard(const uint16_t *const *partials, uint32_t k, uint64_t
     if (too_long(n, bucket_elems)) return AMSP_EINVAL;
     if (grad_out == nullptr) return AMSP_ENULL;
     if (misaligned(grad_out, 4)) return AMSP_EALIGN;
-    bool first = true;
-    return for_buckets(n, bucket_elems, [&](uint64_t off, uint64_t len) {
+    uint64_t used = 0;   // block sums written so far, bucket after bucket
+    rc = for_buckets(n, bucket_elems, [&](uint64_t off, uint64_t len) {
         PartialPtrs q = offset_partials(pp, k, off);
         Stream16 st[AMSP_MAX_K + 1];
         int ns = add_partial_streams(st, 0, q, k);
@@ -935,12 +978,13 @@ int amsp_reduce_grad_shard(const uint16_t *const *partials, uint32_t k, uint64_t
                                               dim3(s.vectorised ? kRwThreads : kThreads),
                                               s.vectorised ? occupancy_lds(kReduceNormRows * (8 * k + (accumulate ? 16 : 0))) : 0u,
                                               hs, q, (int)k,
-                                              grad_out + off, accumulate, block_sums, s));
-        if (launched() != AMSP_OK) return (int)AMSP_EDEVICE;
-        const int acc = (sqnorm_accumulate || !first) ? 1 : 0;
-        first = false;
-        return finish_sums(hs, block_sums, blocks, block_sums + blocks, d_sqnorm, acc);
+                                              grad_out + off, accumulate, block_sums + used, s));
+        used += blocks;
+        return launched();
     });
+    if (rc != AMSP_OK || !norm) return rc;
+    // one finishing pass per call: the sums of all buckets in bucket order
+    return finish_sums(hs, block_sums, used, block_sums + used, d_sqnorm, sqnorm_accumulate ? 1 : 0);
 }
 
 int amsp_grad_sqnorm(const uint16_t *const *partials, uint32_t k, const float *grad_f32, uint64_t n,
