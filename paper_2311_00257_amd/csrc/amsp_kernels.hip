@@ -263,39 +263,28 @@ __device__ __forceinline__ double block_sum(double acc) {
 
 // ---------------------------------------------------------------- step 1: reduce
 // NORM: also sum the squares of the values written, one double per block into block_sums
-// (step 2 fused into step 1 for callers that keep the fp32 gradient).  A block then covers
-// ROWS * 256 consecutive vectors, which keeps the number of block sums at n / 4096.
-template <int K, bool NORM, int ROWS>
+// (step 2 fused into step 1 for callers that keep the fp32 gradient): one per 256 elements on the
+// vector path (a one-wave block), a capped number on the element-wise path.
+template <int K, bool NORM>
 __global__ void __launch_bounds__(kThreads) reduce_kernel(PartialPtrs pp, int k, float *__restrict__ out,
                                                           int accumulate, double *__restrict__ block_sums, Span s) {
     constexpr int VEC = kVecRW;
     double acc = 0.0;
     if (s.vectorised) {
-        const uint64_t v0 = (uint64_t)blockIdx.x * (ROWS * kRwThreads) + threadIdx.x;
-        float g[ROWS][VEC];
+        const uint64_t v = vector_index();
+        if (v < s.nvec) {
+            const uint64_t e = s.head + v * VEC;
+            float g[VEC], o[VEC];
+            if (accumulate) ld_f32<VEC>(out, e, o);   // issued ahead of the partial loads
+            grad_vec<K, VEC>(pp, k, nullptr, e, g);
+            if (accumulate) {
 #pragma unroll
-        for (int r = 0; r < ROWS; ++r) {
-            const uint64_t v = v0 + (uint64_t)r * kRwThreads;
-            if (v < s.nvec) {
-                const uint64_t e = s.head + v * VEC;
-                float o[VEC];
-                if (accumulate) ld_f32<VEC>(out, e, o);   // issued ahead of the partial loads
-                grad_vec<K, VEC>(pp, k, nullptr, e, g[r]);
-                if (accumulate) {
-#pragma unroll
-                    for (int c = 0; c < VEC; ++c) g[r][c] = o[c] + g[r][c];
-                }
+                for (int c = 0; c < VEC; ++c) g[c] = o[c] + g[c];
             }
-        }
+            st_f32<VEC>(out, e, g);
+            if constexpr (NORM) {
 #pragma unroll
-        for (int r = 0; r < ROWS; ++r) {
-            const uint64_t v = v0 + (uint64_t)r * kRwThreads;
-            if (v < s.nvec) {
-                st_f32<VEC>(out, s.head + v * VEC, g[r]);
-                if constexpr (NORM) {
-#pragma unroll
-                    for (int c = 0; c < VEC; ++c) acc = fma((double)g[r][c], (double)g[r][c], acc);
-                }
+                for (int c = 0; c < VEC; ++c) acc = fma((double)g[c], (double)g[c], acc);
             }
         }
         if (blockIdx.x == 0)
@@ -306,6 +295,10 @@ __global__ void __launch_bounds__(kThreads) reduce_kernel(PartialPtrs pp, int k,
                 out[i] = g1;
                 if constexpr (NORM) acc = fma((double)g1, (double)g1, acc);
             }
+        if constexpr (NORM) {
+            acc = wave_sum(acc);   // the block is one wave
+            if (threadIdx.x == 0) block_sums[blockIdx.x] = acc;
+        }
     } else {
         // element-wise path: with the norm the grid is capped (a fixed number of block sums), so loop
         const uint64_t stride = NORM ? (uint64_t)gridDim.x * kThreads : ~0ull;
@@ -316,10 +309,10 @@ __global__ void __launch_bounds__(kThreads) reduce_kernel(PartialPtrs pp, int k,
             if constexpr (NORM) acc = fma((double)g1, (double)g1, acc);
             if constexpr (!NORM) break;
         }
-    }
-    if constexpr (NORM) {
-        const double t = block_sum<kThreads>(acc);
-        if (threadIdx.x == 0) block_sums[blockIdx.x] = t;
+        if constexpr (NORM) {
+            const double t = block_sum<kThreads>(acc);
+            if (threadIdx.x == 0) block_sums[blockIdx.x] = t;
+        }
     }
 }
 
@@ -642,26 +635,29 @@ struct RwLaunch {
     unsigned lds;
 };
 
-unsigned occupancy_lds(unsigned load_bytes_per_lane);
+unsigned occupancy_lds(unsigned load_bytes_per_lane, int inflight_kib);
+struct RwKnobs;
+const RwKnobs &rw_knobs();
+int adamw_inflight_kib();
+int reduce_inflight_kib();
 
-RwLaunch rw_launch(const Span &s, unsigned load_bytes_per_lane) {
+RwLaunch rw_launch(const Span &s, unsigned load_bytes_per_lane, int inflight_kib) {
     const uint64_t work = s.vectorised ? s.nvec : s.n;
     const unsigned threads = s.vectorised ? kRwThreads : kThreads;
     uint64_t blocks = (work + threads - 1) / threads;   // <= kMaxGrid: the entry points refuse larger launches
     if (blocks == 0) blocks = 1;
-    return RwLaunch{dim3((unsigned)blocks), dim3(threads), s.vectorised ? occupancy_lds(load_bytes_per_lane) : 0u};
+    return RwLaunch{dim3((unsigned)blocks), dim3(threads),
+                    s.vectorised ? occupancy_lds(load_bytes_per_lane, inflight_kib) : 0u};
 }
 
-// Reduce with the norm fused in: one block per kReduceNormRows * 256 vectors on the vector path,
-// a capped grid-stride grid on the element-wise path; every block leaves one double.
-constexpr int kReduceNormRows = 4;
+// Reduce with the norm fused in: every block leaves one double.  One-wave blocks of one vector per
+// lane on the vector path (a sum per 256 elements), a capped grid-stride grid on the element-wise path.
 constexpr int kSliceBlocks = 256;
 
 uint64_t reduce_norm_grid(const Span &s) {
     uint64_t blocks;
     if (s.vectorised) {
-        const uint64_t per = (uint64_t)kReduceNormRows * kRwThreads;
-        blocks = (s.nvec + per - 1) / per;
+        blocks = (s.nvec + kRwThreads - 1) / kRwThreads;
     } else {
         blocks = (s.n + kThreads - 1) / kThreads;
         if (blocks > (uint64_t)kNormBlocks) blocks = kNormBlocks;
@@ -670,13 +666,7 @@ uint64_t reduce_norm_grid(const Span &s) {
 }
 
 // Upper bound of reduce_norm_grid over every alignment of a launch of `len` elements.
-uint64_t reduce_norm_blocks_max(uint64_t len) {
-    const uint64_t per = (uint64_t)kReduceNormRows * kRwThreads * kVecRW;
-    const uint64_t vector_path = len / per + 2;
-    uint64_t element_path = (len + kThreads - 1) / kThreads;
-    if (element_path > (uint64_t)kNormBlocks) element_path = kNormBlocks;
-    return vector_path > element_path ? vector_path : element_path;
-}
+uint64_t reduce_norm_blocks_max(uint64_t len) { return len / ((uint64_t)kRwThreads * kVecRW) + 2; }
 
 // Block sums of every bucket of a call lie side by side and are added once, after the last bucket.
 uint64_t reduce_norm_slots(uint64_t n, uint64_t bucket_elems) {
@@ -686,33 +676,45 @@ uint64_t reduce_norm_slots(uint64_t n, uint64_t bucket_elems) {
 }
 
 // Occupancy cap of the read+write kernels.  With one-wave workgroups and only as many waves resident
-// per CU as it takes to keep ~56 KiB of loads in flight (8 waves for the k = 8 fused step), the same
-// kernels move 5-12 % more bytes per second than at full occupancy (32 waves): fewer waves in flight
-// keep the window of addresses being read and written at any moment small, and reads and writes
-// disturb each other less.  The cap is imposed by giving every workgroup an unused slice of the CU's
-// 160 KiB of LDS.  `load_bytes_per_lane` is what one lane has in flight before it waits.
+// per CU as it takes to keep a target amount of loads in flight, the same kernels move 5-12 % more
+// bytes per second than at full occupancy (32 waves): fewer waves in flight keep the window of
+// addresses being read and written at any moment small, and reads and writes disturb each other
+// less.  Measured targets: ~56 KiB per CU for the AdamW kernels (8 waves for the k = 8 fused step),
+// ~96 KiB for the reduction (24 waves at k = 8, 12 at k = 16), whose writes are a small share.  The
+// cap is imposed by giving every workgroup an unused slice of the CU's 160 KiB of LDS.
+// `load_bytes_per_lane` is what one lane has in flight before it waits.
 struct RwKnobs {
-    int inflight_kib, min_waves;
+    int inflight_kib, min_waves, reduce_inflight_kib;
 };
 RwKnobs read_rw_knobs() {   // developer knobs for sweeps; read once (thread-safe static below)
-    const char *a = getenv("AMSP_INFLIGHT_KIB"), *b = getenv("AMSP_MIN_WAVES");
-    const int x = a ? atoi(a) : 0, y = b ? atoi(b) : 0;
-    return RwKnobs{(x >= 8 && x <= 1024) ? x : 56, (y >= 3 && y <= 32) ? y : 8};
+    auto knob = [](const char *name, int lo, int hi, int dflt) {
+        const char *v = getenv(name);
+        const int x = v ? atoi(v) : 0;
+        return (x >= lo && x <= hi) ? x : dflt;
+    };
+    return RwKnobs{knob("AMSP_INFLIGHT_KIB", 8, 1024, 56), knob("AMSP_MIN_WAVES", 3, 32, 8),
+                   knob("AMSP_REDUCE_INFLIGHT_KIB", 8, 1024, 96)};
 }
-int rw_waves_per_cu(unsigned load_bytes_per_lane) {
+const RwKnobs &rw_knobs() {
     static const RwKnobs knobs = read_rw_knobs();
+    return knobs;
+}
+int rw_waves_per_cu(unsigned load_bytes_per_lane, int inflight_kib) {
     const unsigned per_wave = 64u * load_bytes_per_lane;
-    int waves = (int)(((unsigned)knobs.inflight_kib * 1024u + per_wave - 1) / per_wave);
-    if (waves < knobs.min_waves) waves = knobs.min_waves;
+    int waves = (int)(((unsigned)inflight_kib * 1024u + per_wave - 1) / per_wave);
+    if (waves < rw_knobs().min_waves) waves = rw_knobs().min_waves;
     return waves > 32 ? 32 : waves;
 }
 
 // Bytes of dynamic LDS per one-wave workgroup so that at most that many of them fit a CU.
-unsigned occupancy_lds(unsigned load_bytes_per_lane) {
-    const int waves = rw_waves_per_cu(load_bytes_per_lane);
+unsigned occupancy_lds(unsigned load_bytes_per_lane, int inflight_kib) {
+    const int waves = rw_waves_per_cu(load_bytes_per_lane, inflight_kib);
     if (waves >= 32) return 0;
     return (unsigned)((160 * 1024 / waves) & ~255);
 }
+
+int adamw_inflight_kib() { return rw_knobs().inflight_kib; }
+int reduce_inflight_kib() { return rw_knobs().reduce_inflight_kib; }
 
 int cu_count() {
     static std::atomic<int> cached[64];   // per device; zero until first asked (any thread may fill it: same value)
@@ -925,7 +927,7 @@ int amsp_cast_param_shard(const float *master, uint16_t *param_bf16_out, uint64_
     Stream16 st[2] = {{master, 4}, {param_bf16_out, 2}};
     Span s = make_span(n, st, 2, kVecRW);
     clear_stale_error();
-    const RwLaunch L = rw_launch(s, 16);
+    const RwLaunch L = rw_launch(s, 16, adamw_inflight_kib());
     hipLaunchKernelGGL(cast_kernel, L.grid, L.block, L.lds, (hipStream_t)stream, master, param_bf16_out, s);
     return launched();
 }
@@ -967,18 +969,15 @@ int amsp_reduce_grad_shard(const uint16_t *const *partials, uint32_t k, uint64_t
         st[ns++] = Stream16{grad_out + off, 4};
         Span s = make_span(len, st, ns, kVecRW);
         clear_stale_error();
+        const RwLaunch L = rw_launch(s, 8 * k + (accumulate ? 16 : 0), reduce_inflight_kib());
         if (!norm) {
-            const RwLaunch L = rw_launch(s, 8 * k + (accumulate ? 16 : 0));
-            AMSP_DISPATCH_K(k, hipLaunchKernelGGL((reduce_kernel<KK, false, 1>), L.grid, L.block, L.lds, hs, q, (int)k,
+            AMSP_DISPATCH_K(k, hipLaunchKernelGGL((reduce_kernel<KK, false>), L.grid, L.block, L.lds, hs, q, (int)k,
                                                   grad_out + off, accumulate, block_sums, s));
             return launched();
         }
-        const uint64_t blocks = reduce_norm_grid(s);
-        AMSP_DISPATCH_K(k, hipLaunchKernelGGL((reduce_kernel<KK, true, kReduceNormRows>), dim3((unsigned)blocks),
-                                              dim3(s.vectorised ? kRwThreads : kThreads),
-                                              s.vectorised ? occupancy_lds(kReduceNormRows * (8 * k + (accumulate ? 16 : 0))) : 0u,
-                                              hs, q, (int)k,
-                                              grad_out + off, accumulate, block_sums + used, s));
+        const uint64_t blocks = reduce_norm_grid(s);   // == L.grid.x on the vector path, capped on the other
+        AMSP_DISPATCH_K(k, hipLaunchKernelGGL((reduce_kernel<KK, true>), dim3((unsigned)blocks), L.block, L.lds, hs, q,
+                                              (int)k, grad_out + off, accumulate, block_sums + used, s));
         used += blocks;
         return launched();
     });
@@ -1063,7 +1062,7 @@ int amsp_adamw_step_shard(const uint16_t *const *partials, uint32_t k, const flo
         uint16_t *out = param_bf16_out ? param_bf16_out + off : nullptr;
         if (out) st[ns++] = Stream16{out, 2};
         Span s = make_span(len, st, ns, kVecRW);
-        const RwLaunch L = rw_launch(s, (k != 0 ? 8 * k : 16) + 48);
+        const RwLaunch L = rw_launch(s, (k != 0 ? 8 * k : 16) + 48, adamw_inflight_kib());
         const dim3 grid = L.grid, block = L.block;
         const unsigned lds = L.lds;
         clear_stale_error();
@@ -1197,7 +1196,7 @@ int amsp_cast_param_fp8_shard(const float *master, uint64_t n, const float *d_sc
     Stream16 st[2] = {{master, 4}, {param_fp8_out, 1}};
     Span s = make_span(n, st, 2, 4);
     clear_stale_error();
-    const RwLaunch L = rw_launch(s, 16);
+    const RwLaunch L = rw_launch(s, 16, adamw_inflight_kib());
     hipLaunchKernelGGL(cast_fp8_kernel, L.grid, L.block, L.lds, (hipStream_t)stream, master, d_scale, param_fp8_out, s);
     return launched();
 }
