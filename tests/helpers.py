@@ -100,10 +100,12 @@ def _bf16_neighbours(bits: np.ndarray):
     return f
 
 
-def check_bf16(got_bits: np.ndarray, ref: dict, tol: float = REL_TOL) -> int:
+def check_bf16(got_bits: np.ndarray, ref: dict, inp_p: np.ndarray, tol: float = REL_TOL) -> int:
     """bf16 parameters: identical to bf16(fp32(p')) of the oracle, except that where the
-    oracle's double p' lies within `tol` (relative) of the midpoint of two adjacent bf16
-    values the other neighbour is accepted (a difference of exactly one bf16 step).
+    oracle's double p' lies within the fp32 tolerance of the midpoint of two adjacent bf16
+    values the other neighbour is accepted (a difference of exactly one bf16 step).  The fp32
+    tolerance is check_state's: `tol` relative to max(|p'|, |p|, |p' - p|), so that a p' that is
+    small only because p and the step cancelled is not held to `tol` of its own size.
     Returns the number of such mismatches."""
     want = ref["p_bf16"]
     bad = np.nonzero(got_bits != want)[0]
@@ -116,7 +118,9 @@ def check_bf16(got_bits: np.ndarray, ref: dict, tol: float = REL_TOL) -> int:
     step = np.abs((got_bits[bad] & 0x7FFF).astype(np.int64) - (want[bad] & 0x7FFF).astype(np.int64))
     same_sign = (got_bits[bad] >> 15) == (want[bad] >> 15)
     mid = 0.5 * (g + w)
-    near = np.abs(ref["p"][bad] - mid) <= tol * np.abs(ref["p"][bad])
+    p_in = inp_p[bad].astype(np.float64)
+    scale = np.maximum(np.abs(ref["p"][bad]), np.maximum(np.abs(p_in), np.abs(ref["p"][bad] - p_in)))
+    near = np.abs(ref["p"][bad] - mid) <= tol * scale
     ok = (step == 1) & same_sign & near
     assert np.all(ok), "bf16 mismatches away from a rounding boundary: %d of %d (first index %d)" % (
         int(np.sum(~ok)), bad.size, int(bad[np.argmin(ok)]))

@@ -262,7 +262,7 @@ def _check_all(got, ref, inp, hp):
     assert abs(S - ref["sqnorm"]) <= H.REL_TOL * ref["sqnorm"]
     stats = H.check_state(p, m, v, ref, inp.p, inp.m, hp)
     if bits is not None:
-        stats["bf16_boundary_mismatches"] = H.check_bf16(bits, ref)
+        stats["bf16_boundary_mismatches"] = H.check_bf16(bits, ref, inp.p)
         assert np.array_equal(bits, oracle.cast(p))        # the cast of the GPU's own fp32 is bit-exact
         assert stats["bf16_boundary_mismatches"] <= max(3, 1e-4 * p.size)
     return stats

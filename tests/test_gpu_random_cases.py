@@ -1,0 +1,173 @@
+"""Seeded random sweep of the step through the C ABI against the oracle: lengths around the
+vector, wave and line boundaries, every k (compile-time instantiations and the run-time
+loop), per-stream alignment shifts (a common phase -> vector path, mixed phases -> the
+element-wise path), bucket lengths, with and without the bf16 output, the clip threshold,
+the fused form and the one through a materialised (and accumulated) fp32 gradient."""
+from __future__ import annotations
+
+import sys
+
+import numpy as np
+import pytest
+
+import helpers as H
+import oracle
+from paper_2311_00257_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    import torch
+
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    from paper_2311_00257_amd import binding
+
+    binding.load()
+    return binding
+
+
+@pytest.fixture(scope="module")
+def torch_mod():
+    import torch
+
+    return torch
+
+EDGE_LENGTHS = (1, 2, 3, 4, 5, 63, 64, 65, 127, 128, 129, 255, 256, 257, 1023, 1024, 1025, 4095, 4097)
+
+
+def _case(rng: np.random.Generator, idx: int) -> dict:
+    n = int(rng.choice(EDGE_LENGTHS)) if rng.random() < 0.4 else int(rng.integers(1, 40_000))
+    k = int(rng.choice([1, 2, 3, 4, 5, 6, 7, 8, 9, 12, 15, 16, 17, 24, 31, 32]))
+    common = int(rng.integers(0, 70))
+    mixed = rng.random() < 0.2
+    return dict(idx=idx, n=n, k=k,
+                shifts=[int(rng.integers(0, 9)) if mixed else common for _ in range(k + 4)],
+                bucket=int(rng.choice([0, 0, 1 if n <= 3000 else 251, 7 if n <= 20_000 else 999, 250, 1025, 4099]))
+                if n > 1 else 0,
+                with_bf16=bool(rng.random() < 0.8),
+                max_norm=float(rng.choice([0.0, 1e-3, 0.05, 1e9])),
+                form=str(rng.choice(["fused", "fused", "materialised", "accumulated"])),
+                step=int(rng.choice([1, 2, 10, 1000])),
+                index0=int(rng.integers(0, 1 << 40)))
+
+
+def _run(B, torch, c: dict):
+    w = workloads.get(0)
+    n, k = c["n"], c["k"]
+    inp = H.host_inputs(w, c["index0"], n, k=k, threads=1)
+    hp = H.hparams_of(w, max_norm=c["max_norm"], step=c["step"])
+    sh = c["shifts"]
+    dparts = [H.to_dev_bf16(p, pad_front=sh[j]) for j, p in enumerate(inp.partials)]
+    dp, dm, dv = (H.to_dev_f32(x, pad_front=sh[k + i]) for i, x in enumerate((inp.p, inp.m, inp.v)))
+    out = torch.full((sh[k + 3] + n,), 0x5A5A, dtype=torch.int16, device="cuda")[sh[k + 3]:] if c["with_bf16"] else None
+    d_s = torch.full((1,), -7.0, dtype=torch.float64, device="cuda")
+    if c["form"] == "fused":
+        ws = torch.empty(B.amsp_workspace_bytes() // 8, dtype=torch.float64, device="cuda")
+        B.amsp_grad_sqnorm(dparts, None, n, d_s, ws, bucket_elems=c["bucket"])
+        B.amsp_adamw_step_shard(dparts, None, n, dp, dm, dv, out, B.AdamWHparams(d_total_sqnorm=d_s, **hp),
+                                bucket_elems=c["bucket"])
+        ref = oracle.step(inp.partials, inp.p, inp.m, inp.v, threads=1, **hp)
+    else:
+        ws = torch.empty(B.amsp_reduce_workspace_bytes(n, c["bucket"]) // 8, dtype=torch.float64, device="cuda")
+        g32 = torch.full((sh[0] + n,), 123.0, dtype=torch.float32, device="cuda")[sh[0]:]
+        if c["form"] == "accumulated":
+            # two micro-batches: the first k//2 partials overwrite, the rest are added, the norm is of the total
+            half = max(1, k // 2)
+            B.amsp_reduce_grad_shard(dparts[:half], n, g32, bucket_elems=c["bucket"])
+            if half < k:
+                B.amsp_reduce_grad_shard(dparts[half:], n, g32, bucket_elems=c["bucket"], accumulate=True,
+                                         d_sqnorm=d_s, workspace=ws)
+            else:
+                wn = torch.empty(B.amsp_workspace_bytes() // 8, dtype=torch.float64, device="cuda")
+                B.amsp_grad_sqnorm(None, g32, n, d_s, wn)
+        else:
+            B.amsp_reduce_grad_shard(dparts, n, g32, bucket_elems=c["bucket"], d_sqnorm=d_s, workspace=ws)
+        B.amsp_adamw_step_shard(None, g32, n, dp, dm, dv, out, B.AdamWHparams(d_total_sqnorm=d_s, **hp),
+                                bucket_elems=c["bucket"])
+        ref = oracle.step(inp.partials, inp.p, inp.m, inp.v, threads=1, **hp)
+    torch.cuda.synchronize()
+    return inp, hp, ref, (dp.cpu().numpy(), dm.cpu().numpy(), dv.cpu().numpy(),
+                          H.dev_bits(out) if out is not None else None, float(d_s.item()))
+
+
+def test_random_cases_against_oracle(B, torch_mod):
+    rng = np.random.default_rng(2311_00257)
+    worst = dict(max_p=0.0, max_m=0.0, max_v=0.0)
+    for idx in range(400):
+        c = _case(rng, idx)
+        print("case", c, flush=True)
+        sys.stdout.flush()
+        inp, hp, ref, (p, m, v, bits, S) = _run(B, torch_mod, c)
+        # the two-micro-batch sum rounds once more in fp32 than the oracle's exact sum: still far inside the bar
+        assert abs(S - ref["sqnorm"]) <= H.REL_TOL * ref["sqnorm"], (c, S, ref["sqnorm"])
+        stats = H.check_state(p, m, v, ref, inp.p, inp.m, hp)
+        for key in worst:
+            worst[key] = max(worst[key], stats[key])
+        if bits is not None:
+            assert np.array_equal(bits, oracle.cast(p)), c
+            assert H.check_bf16(bits, ref, inp.p) <= max(3, 1e-4 * p.size), c
+    print("worst scaled relative errors over the sweep:", worst)
+
+
+def test_random_inter_tensor_models(B, torch_mod):
+    """Random models (tensor lengths from 0 to a few thousand, odd ones included) split whole-tensor
+    over random shard factors: partition and segment lists equal the oracle's, every rank's select,
+    update and write-back match it, what a rank does not own is never written, and the FP8 payload
+    (per-tensor amax, scale, codes) is bit-exact."""
+    torch = torch_mod
+    rng = np.random.default_rng(2311_00258)
+    w = workloads.get(0)
+    ws = torch.empty(B.amsp_workspace_bytes() // 8, dtype=torch.float64, device="cuda")
+    for idx in range(24):
+        nt = int(rng.integers(1, 40))
+        sizes = [int(rng.choice([0, 1, 3, 64, 255, 256, 1000, 4096, 4097, int(rng.integers(1, 9000))])) for _ in range(nt)]
+        total = sum(sizes)
+        s = int(rng.integers(1, 7))
+        k = int(rng.choice([1, 2, 8, 17]))
+        print("model", idx, "sizes", sizes, "s", s, "k", k, flush=True)
+        owner = B.amsp_partition_tensors(sizes, s)
+        assert owner == oracle.partition_tensors(sizes, s)
+        if total == 0:
+            continue
+        elem_owner = np.repeat(np.array(owner), sizes)
+        flat = H.host_inputs(w, int(rng.integers(0, 1 << 40)), total, k=k, threads=1)
+        dparts = [H.to_dev_bf16(g) for g in flat.partials]
+        hp = H.hparams_of(w, max_norm=float(rng.choice([0.0, 0.01, 1e9])))
+        for rank in range(s):
+            segs, local = B.amsp_owned_segments(sizes, owner, rank)
+            assert segs == oracle.owned_segments(sizes, owner, rank)
+            assert local == int(np.sum(elem_owner == rank))
+            inp = H.HostInputs([oracle.select(g, segs) for g in flat.partials], oracle.select(flat.p, segs),
+                               oracle.select(flat.m, segs), oracle.select(flat.v, segs))
+            dp, dm, dv = H.to_dev_f32(inp.p), H.to_dev_f32(inp.m), H.to_dev_f32(inp.v)
+            out = torch.full((total,), 0x5A5A, dtype=torch.int16, device="cuda")
+            d_s = torch.full((1,), -3.0, dtype=torch.float64, device="cuda")
+            B.amsp_grad_sqnorm_segments(dparts, total, segs, d_s, ws)
+            B.amsp_adamw_step_segments(dparts, total, segs, local, dp, dm, dv, out,
+                                       B.AdamWHparams(d_total_sqnorm=d_s, **hp))
+            torch.cuda.synchronize()
+            out_bits = H.dev_bits(out)
+            assert np.all(out_bits[elem_owner != rank] == 0x5A5A)
+            if local == 0:
+                assert float(d_s.item()) == 0.0
+                continue
+            ref = oracle.step(inp.partials, inp.p, inp.m, inp.v, threads=1, **hp)
+            assert abs(float(d_s.item()) - ref["sqnorm"]) <= H.REL_TOL * ref["sqnorm"]
+            p = dp.cpu().numpy()
+            H.check_state(p, dm.cpu().numpy(), dv.cpu().numpy(), ref, inp.p, inp.m, hp)
+            mine = oracle.select(out_bits, segs)
+            assert np.array_equal(mine, oracle.cast(p))
+            H.check_bf16(mine, ref, inp.p)
+            # FP8 payload of the updated shard
+            fp8 = torch.full((total,), 0xA5, dtype=torch.uint8, device="cuda")
+            d_amax = torch.full((len(segs),), -1.0, dtype=torch.float32, device="cuda")
+            d_scale = torch.zeros(len(segs), dtype=torch.float32, device="cuda")
+            B.amsp_fp8_payload_segments(dp, local, segs, total, fp8, d_amax, d_scale)
+            codes, scales, amaxes = oracle.fp8_payload_segments(p, segs)
+            assert d_amax.cpu().numpy().tolist() == [float(np.float32(a)) for a in amaxes]
+            assert d_scale.cpu().numpy().tolist() == [float(np.float32(x)) for x in scales]
+            got = fp8.cpu().numpy()
+            assert np.array_equal(oracle.select(got, segs), codes)
+            assert np.all(got[elem_owner != rank] == 0xA5)
