@@ -12,8 +12,8 @@
 //     and balances the CUs.  The same body as a persistent grid-stride loop reaches ~4.5 TB/s
 //     instead of ~5.8 TB/s on the k = 8 fused step.
 //   - Those kernels run one-wave (64-thread) workgroups under an occupancy cap: only as many
-//     waves per CU as keep ~56 KiB of loads in flight (8 for k = 8, where the hardware would take
-//     32).  That brings the k = 8 fused step from ~5.8 to 6.4-6.5 TB/s.  The cap is an unused slice
+//     waves per CU as keep ~40 KiB of loads in flight, at least 8 (8 for k = 8, where the hardware
+//     would take 32).  That brings the k = 8 fused step from ~5.8 to 6.4-6.5 TB/s.  The cap is an unused slice
 //     of LDS per workgroup.  With so few waves, nothing may stand between a wave's start and its
 //     loads: no blockDim/gridDim (a dispatch-packet fetch), the clip scale worked out after the
 //     loads are in flight, and a scheduling barrier that keeps all k + 3 loads ahead of the first
@@ -679,8 +679,9 @@ uint64_t reduce_norm_slots(uint64_t n, uint64_t bucket_elems) {
 // per CU as it takes to keep a target amount of loads in flight, the same kernels move 5-12 % more
 // bytes per second than at full occupancy (32 waves): fewer waves in flight keep the window of
 // addresses being read and written at any moment small, and reads and writes disturb each other
-// less.  Measured targets: ~56 KiB per CU for the AdamW kernels (8 waves for the k = 8 fused step),
-// ~96 KiB for the reduction (24 waves at k = 8, 12 at k = 16), whose writes are a small share.  The
+// less.  Measured targets: ~40 KiB per CU for the AdamW kernels but never fewer than 8 waves (10 waves
+// for an fp32 gradient, 12 for k = 1, 8 from k = 4 on), ~96 KiB for the reduction (24 waves at k = 8,
+// 12 at k = 16), whose writes are a small share.  The
 // cap is imposed by giving every workgroup an unused slice of the CU's 160 KiB of LDS.
 // `load_bytes_per_lane` is what one lane has in flight before it waits.
 struct RwKnobs {
@@ -692,7 +693,7 @@ RwKnobs read_rw_knobs() {   // developer knobs for sweeps; read once (thread-saf
         const int x = v ? atoi(v) : 0;
         return (x >= lo && x <= hi) ? x : dflt;
     };
-    return RwKnobs{knob("AMSP_INFLIGHT_KIB", 8, 1024, 56), knob("AMSP_MIN_WAVES", 3, 32, 8),
+    return RwKnobs{knob("AMSP_INFLIGHT_KIB", 8, 1024, 40), knob("AMSP_MIN_WAVES", 3, 32, 8),
                    knob("AMSP_REDUCE_INFLIGHT_KIB", 8, 1024, 96)};
 }
 const RwKnobs &rw_knobs() {
