@@ -693,7 +693,7 @@ RwKnobs read_rw_knobs() {   // developer knobs for sweeps; read once (thread-saf
         const int x = v ? atoi(v) : 0;
         return (x >= lo && x <= hi) ? x : dflt;
     };
-    return RwKnobs{knob("AMSP_INFLIGHT_KIB", 8, 1024, 40), knob("AMSP_MIN_WAVES", 3, 32, 8),
+    return RwKnobs{knob("AMSP_INFLIGHT_KIB", 8, 1024, 40), knob("AMSP_MIN_WAVES", 4, 32, 8),
                    knob("AMSP_REDUCE_INFLIGHT_KIB", 8, 1024, 96)};
 }
 const RwKnobs &rw_knobs() {
@@ -703,7 +703,10 @@ const RwKnobs &rw_knobs() {
 int rw_waves_per_cu(unsigned load_bytes_per_lane, int inflight_kib) {
     const unsigned per_wave = 64u * load_bytes_per_lane;
     int waves = (int)(((unsigned)inflight_kib * 1024u + per_wave - 1) / per_wave);
-    if (waves < rw_knobs().min_waves) waves = rw_knobs().min_waves;
+    // the floor: 8 waves, 7 once a wave loads more than 8 KiB (fused step from k = 9 on; k = 16 reads
+    // 6,330 GB/s at 7 waves against 6,010-6,270 at 8, while k = 8 is best at 8)
+    const int floor = per_wave > 8192u ? rw_knobs().min_waves - 1 : rw_knobs().min_waves;
+    if (waves < floor) waves = floor;
     return waves > 32 ? 32 : waves;
 }
 
