@@ -289,6 +289,27 @@ def main():
         fp8_ms = e0.elapsed_time(e1) / args.steps
         out["fp8_payload"] = {"ms": fp8_ms, "GB/s": 9 * n / (fp8_ms * 1e-3) / 1e9, "bytes_per_element": 9,
                               "launches": 2 * len(segs) + 2}
+        # the whole step shipping FP8 instead of bf16: norm pass, update with the per-tensor maxima taken
+        # inside it and no bf16 output (2k + 24 B/elt), scales and E4M3 codes (4 read + 1 written)
+        amax_ws = torch.empty(B.amsp_amax_workspace_bytes(len(segs)) // 4, dtype=torch.int32, device="cuda")
+
+        def fp8_step(t):
+            norm_pass()
+            B.amsp_adamw_step_segments(parts, total, segs, n, master, exp_avg, exp_avg_sq, None, hparams(t),
+                                       d_amax=d_amax, amax_workspace=amax_ws)
+            B.amsp_fp8_payload_segments(master, n, segs, w.total_elems, fp8, d_amax, d_scale, amax_ready=True)
+        for i in range(2):
+            fp8_step(w.step + i)
+        e0.record()
+        for i in range(args.steps):
+            fp8_step(w.step + 2 + i)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / args.steps
+        bpe = 2 * k + 2 * k + 24 + 5
+        out["fp8_step"] = {"composition": "norm -> AdamW with fused per-tensor amax, no bf16 -> scales + E4M3 codes",
+                           "ms_per_step": ms, "value": n / (ms * 1e-3), "unit": "elements/s",
+                           "bytes_per_element": bpe, "GB/s": bpe * n / (ms * 1e-3) / 1e9}
         del fp8
     if not args.no_ceilings and not args.calibrate_copy:   # keep the calibration run to one known copy
         out["ceilings"] = ceilings(torch, out, master, n)

@@ -212,6 +212,12 @@ int amsp_owned_segments(const uint64_t *tensor_elems, const uint32_t *owner, uin
  *   master_local ... device fp32[local_elems], updated in place
  *   param_bf16_flat  device bf16[flat_elems] or NULL: the updated parameters land at their flat
  *                    positions, ready for the per-tensor Broadcast of Section IV-C.2
+ *   d_amax           device float[num_segments] or NULL.  Not NULL: d_amax[i] = max |p'| over segment i
+ *                    of the parameters just written (as amsp_fp8_payload_segments computes it, taken
+ *                    inside the update so that the FP8 payload needs no pass of its own for it);
+ *                    entries of empty segments are 0
+ *   amax_workspace   device, >= amsp_amax_workspace_bytes(num_segments), 4-byte aligned, used only
+ *                    when d_amax != NULL (else may be NULL); no initialisation needed, clobbered
  * The squared norm is accumulated in segment order (accumulate = 0 overwrites first).
  */
 int amsp_grad_sqnorm_segments(const uint16_t *const *partials_flat, uint32_t k, uint64_t flat_elems,
@@ -221,7 +227,9 @@ int amsp_grad_sqnorm_segments(const uint16_t *const *partials_flat, uint32_t k, 
 int amsp_adamw_step_segments(const uint16_t *const *partials_flat, uint32_t k, uint64_t flat_elems,
                              const amsp_segment *segments, uint32_t num_segments, uint64_t local_elems,
                              float *master_local, float *exp_avg_local, float *exp_avg_sq_local,
-                             uint16_t *param_bf16_flat, const amsp_adamw_hparams *hp, void *stream);
+                             uint16_t *param_bf16_flat, float *d_amax, void *amax_workspace,
+                             size_t amax_workspace_bytes, const amsp_adamw_hparams *hp, void *stream);
+size_t amsp_amax_workspace_bytes(uint32_t num_segments);
 
 /* ------------------------------------------------------------------------------------------------
  * FP8 payload with per-tensor scaling factors: Section IV-C.2 adopts inter-tensor shards because
@@ -244,12 +252,14 @@ int amsp_cast_param_fp8_shard(const float *master, uint64_t n, const float *d_sc
  *   param_fp8_flat  device uint8[flat_elems]; only owned segments are written
  *   d_amax, d_scale device float[num_segments], written (the scales are what a receiver needs to
  *                   decode: value = code / scale)
+ *   amax_ready      0: the maxima are computed here (one more read of the master).  1: d_amax already
+ *                   holds them, as amsp_adamw_step_segments left them for this segment list
  * Errors as amsp_adamw_step_segments.
  */
 int amsp_fp8_payload_segments(const float *master_local, uint64_t local_elems,
                               const amsp_segment *segments, uint32_t num_segments,
                               uint64_t flat_elems, uint8_t *param_fp8_flat,
-                              float *d_amax, float *d_scale, void *stream);
+                              float *d_amax, int amax_ready, float *d_scale, void *stream);
 
 /* ------------------------------------------------------------------------------------------------
  * Sharding planner (Section V-B).  Chooses the device meshes s_p, s_g, s_os = (GPUs per node) x

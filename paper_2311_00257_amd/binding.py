@@ -19,8 +19,8 @@ AMSP_OK, AMSP_EINVAL, AMSP_ENULL, AMSP_EALIGN, AMSP_EWORKSPACE, AMSP_EDEVICE, AM
 AMSP_OP_ALLGATHER, AMSP_OP_REDUCESCATTER, AMSP_OP_ALLREDUCE, AMSP_OP_BROADCAST = 0, 1, 2, 3
 AMSP_MAX_K = 32
 
-EXPORTS = ("amsp_status_string", "amsp_workspace_bytes", "amsp_reduce_workspace_bytes", "amsp_shard_range",
-           "amsp_reduce_grad_shard", "amsp_grad_sqnorm", "amsp_adamw_step_shard", "amsp_cast_param_shard",
+EXPORTS = ("amsp_status_string", "amsp_workspace_bytes", "amsp_reduce_workspace_bytes",
+           "amsp_amax_workspace_bytes", "amsp_shard_range", "amsp_reduce_grad_shard", "amsp_grad_sqnorm", "amsp_adamw_step_shard", "amsp_cast_param_shard",
            "amsp_partition_tensors", "amsp_owned_segments", "amsp_grad_sqnorm_segments",
            "amsp_adamw_step_segments", "amsp_cast_param_fp8_shard", "amsp_fp8_payload_segments",
            "amsp_plan_sharding")
@@ -110,12 +110,15 @@ def load() -> ctypes.CDLL:
         lib.amsp_grad_sqnorm_segments.argtypes = [vp, u32, u64, ctypes.POINTER(_Segment), u32, vp, ci, vp,
                                                   ctypes.c_size_t, vp]
         lib.amsp_adamw_step_segments.argtypes = [vp, u32, u64, ctypes.POINTER(_Segment), u32, u64, vp, vp, vp, vp,
-                                                 ctypes.POINTER(_Hparams), vp]
+                                                 vp, vp, ctypes.c_size_t, ctypes.POINTER(_Hparams), vp]
+        lib.amsp_amax_workspace_bytes.argtypes = [u32]
+        lib.amsp_amax_workspace_bytes.restype = ctypes.c_size_t
         lib.amsp_cast_param_fp8_shard.argtypes = [vp, u64, vp, vp, vp]
-        lib.amsp_fp8_payload_segments.argtypes = [vp, u64, ctypes.POINTER(_Segment), u32, u64, vp, vp, vp, vp]
+        lib.amsp_fp8_payload_segments.argtypes = [vp, u64, ctypes.POINTER(_Segment), u32, u64, vp, vp, ctypes.c_int,
+                                                  vp, vp]
         lib.amsp_plan_sharding.argtypes = [ctypes.POINTER(_PlanProblem), ctypes.POINTER(_BwSample), u32,
                                            ctypes.POINTER(_Plan), pu32]
-        for name in EXPORTS[3:]:
+        for name in EXPORTS[4:]:
             getattr(lib, name).restype = ci
         _lib = lib
     return _lib
@@ -256,14 +259,21 @@ def amsp_grad_sqnorm_segments(partials_flat, flat_elems: int, segments, d_sqnorm
 
 
 def amsp_adamw_step_segments(partials_flat, flat_elems: int, segments, local_elems: int, master_local,
-                             exp_avg_local, exp_avg_sq_local, param_bf16_flat, hp: AdamWHparams, stream=None) -> None:
+                             exp_avg_local, exp_avg_sq_local, param_bf16_flat, hp: AdamWHparams, stream=None,
+                             d_amax=None, amax_workspace=None) -> None:
     arr, k = _partials(partials_flat)
     segs, ns = _segments(segments)
     c = _hp_struct(hp) if hp is not None else None
     _check(load().amsp_adamw_step_segments(arr, k, flat_elems, segs, ns, local_elems, _ptr(master_local),
                                            _ptr(exp_avg_local), _ptr(exp_avg_sq_local), _ptr(param_bf16_flat),
+                                           _ptr(d_amax), _ptr(amax_workspace),
+                                           _nbytes(amax_workspace, None),
                                            ctypes.byref(c) if c is not None else None, _stream(stream)),
            "amsp_adamw_step_segments")
+
+
+def amsp_amax_workspace_bytes(num_segments: int) -> int:
+    return int(load().amsp_amax_workspace_bytes(num_segments))
 
 
 # ------------------------------------------------------------------ FP8 payload
@@ -273,10 +283,11 @@ def amsp_cast_param_fp8_shard(master, n: int, d_scale, param_fp8_out, stream=Non
 
 
 def amsp_fp8_payload_segments(master_local, local_elems: int, segments, flat_elems: int, param_fp8_flat, d_amax,
-                              d_scale, stream=None) -> None:
+                              d_scale, stream=None, amax_ready: bool = False) -> None:
     segs, ns = _segments(segments)
     _check(load().amsp_fp8_payload_segments(_ptr(master_local), local_elems, segs, ns, flat_elems,
-                                            _ptr(param_fp8_flat), _ptr(d_amax), _ptr(d_scale), _stream(stream)),
+                                            _ptr(param_fp8_flat), _ptr(d_amax), 1 if amax_ready else 0,
+                                            _ptr(d_scale), _stream(stream)),
            "amsp_fp8_payload_segments")
 
 

@@ -444,13 +444,53 @@ __device__ __forceinline__ void adamw1(const AdamConsts &c, float scale, float g
     p = fmaf(-c.lr, fmaf(c.wd, p, u), p);
 }
 
+// |x| as an ordered integer: for non-negative floats the bit patterns order like the values, with
+// Inf above every finite value and NaN patterns above Inf, so an integer max is exact,
+// order-independent and lets a NaN win.
+__device__ __forceinline__ uint32_t abs_bits(float x) { return __float_as_uint(x) & 0x7FFFFFFFu; }
+
+// Per-segment maxima of |p'| taken inside the update.  An atomic on one word costs ~11 ns and is
+// serialised in its memory channel, so the waves of a launch spread over kAmaxSubSlots words that lie
+// kAmaxStrideWords apart (different channels), and a wave sends an atomic only when it beats what its
+// word held when the wave started: the word only grows, so that early read (device-coherent: an
+// ordinary cached read returns stale values and half of the waves would still send) filters out all
+// but the record holders.  It is issued with the wave's first loads, so its latency is hidden.
+constexpr int kAmaxSubSlots = 64;
+constexpr int kAmaxStrideWords = 64;   // 256 bytes
+constexpr size_t kAmaxWordsPerSegment = (size_t)kAmaxSubSlots * kAmaxStrideWords;
+
+__device__ __forceinline__ uint32_t *amax_word(uint32_t *segment_words) {
+    return segment_words + (blockIdx.x & (kAmaxSubSlots - 1)) * kAmaxStrideWords;
+}
+__device__ __forceinline__ uint32_t amax_seen(uint32_t *segment_words) {
+    return segment_words == nullptr
+               ? 0u
+               : __hip_atomic_load(amax_word(segment_words), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void wave_amax_into(uint32_t m, uint32_t seen, uint32_t *segment_words) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) m = max(m, (uint32_t)__shfl_down((int)m, off, 64));
+    if ((threadIdx.x & 63) == 0 && m > seen) atomicMax(amax_word(segment_words), m);
+}
+
+// d_amax[i] = the largest of segment i's words, as a float.
+__global__ void __launch_bounds__(kAmaxSubSlots) amax_fold_kernel(const uint32_t *__restrict__ words,
+                                                                 uint32_t *__restrict__ d_amax) {
+    uint32_t m = words[(size_t)blockIdx.x * kAmaxWordsPerSegment + threadIdx.x * kAmaxStrideWords];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) m = max(m, (uint32_t)__shfl_down((int)m, off, 64));
+    if (threadIdx.x == 0) d_amax[blockIdx.x] = m;
+}
+
 template <int K, bool WRITE_BF16>
 __global__ void __launch_bounds__(kThreads) adamw_kernel(PartialPtrs pp, int k, const float *__restrict__ gf32,
                                                          float *__restrict__ master, float *__restrict__ exp_avg,
                                                          float *__restrict__ exp_avg_sq, uint16_t *__restrict__ out,
-                                                         AdamConsts c, Span s) {
+                                                         uint32_t *__restrict__ amax, AdamConsts c, Span s) {
     constexpr int VEC = kVecRW;
     const double sqnorm = load_sqnorm(c);
+    const uint32_t seen = amax_seen(amax);
+    uint32_t biggest = 0;   // of |p'| over this lane's elements, when amax != nullptr
     if (s.vectorised) {
         const uint64_t vi = vector_index();
         if (vi < s.nvec) {
@@ -468,29 +508,38 @@ __global__ void __launch_bounds__(kThreads) adamw_kernel(PartialPtrs pp, int k, 
             st_f32<VEC>(exp_avg, e, m);
             st_f32<VEC>(exp_avg_sq, e, v);
             if constexpr (WRITE_BF16) st_bf16<VEC>(out, e, p);
+            if (amax != nullptr) {
+#pragma unroll
+                for (int q = 0; q < VEC; ++q) biggest = max(biggest, abs_bits(p[q]));
+            }
         }
-        if (blockIdx.x != 0) return;
-        const float scale = clip_scale(c, sqnorm);
-        for (uint32_t t = threadIdx.x; t < s.head + s.tail; t += kRwThreads) {
-            const uint64_t i = edge_elem<VEC>(s, t);
+        if (blockIdx.x == 0) {
+            const float scale = clip_scale(c, sqnorm);
+            for (uint32_t t = threadIdx.x; t < s.head + s.tail; t += kRwThreads) {
+                const uint64_t i = edge_elem<VEC>(s, t);
+                float p = master[i], m = exp_avg[i], v = exp_avg_sq[i];
+                adamw1(c, scale, grad1<K>(pp, k, gf32, i), p, m, v);
+                master[i] = p;
+                exp_avg[i] = m;
+                exp_avg_sq[i] = v;
+                if constexpr (WRITE_BF16) out[i] = (uint16_t)f32_to_bf16(p);
+                biggest = max(biggest, abs_bits(p));
+            }
+        }
+    } else {
+        const uint64_t i = element_index();
+        if (i < s.n) {
             float p = master[i], m = exp_avg[i], v = exp_avg_sq[i];
-            adamw1(c, scale, grad1<K>(pp, k, gf32, i), p, m, v);
+            const float g = grad1<K>(pp, k, gf32, i);
+            adamw1(c, clip_scale(c, sqnorm), g, p, m, v);
             master[i] = p;
             exp_avg[i] = m;
             exp_avg_sq[i] = v;
             if constexpr (WRITE_BF16) out[i] = (uint16_t)f32_to_bf16(p);
+            biggest = max(biggest, abs_bits(p));
         }
-    } else {
-        const uint64_t i = element_index();
-        if (i >= s.n) return;
-        float p = master[i], m = exp_avg[i], v = exp_avg_sq[i];
-        const float g = grad1<K>(pp, k, gf32, i);
-        adamw1(c, clip_scale(c, sqnorm), g, p, m, v);
-        master[i] = p;
-        exp_avg[i] = m;
-        exp_avg_sq[i] = v;
-        if constexpr (WRITE_BF16) out[i] = (uint16_t)f32_to_bf16(p);
     }
+    if (amax != nullptr) wave_amax_into(biggest, seen, amax);   // uniform branch: every lane of the wave arrives
 }
 
 // ---------------------------------------------------------------- FP8 (E4M3) payload
@@ -513,11 +562,6 @@ __device__ __forceinline__ uint32_t f32_to_e4m3(float x) {
     }
     return sign | code;
 }
-
-// |x| as an ordered integer: for non-negative floats the bit patterns order like the values, with
-// Inf above every finite value and NaN patterns above Inf, so an integer max is exact,
-// order-independent and lets a NaN win.
-__device__ __forceinline__ uint32_t abs_bits(float x) { return __float_as_uint(x) & 0x7FFFFFFFu; }
 
 __global__ void __launch_bounds__(kThreads) fill_u32_kernel(uint32_t *p, uint32_t count, uint32_t value) {
     for (uint32_t i = blockIdx.x * kThreads + threadIdx.x; i < count; i += gridDim.x * kThreads) p[i] = value;
@@ -1017,9 +1061,11 @@ int amsp_grad_sqnorm(const uint16_t *const *partials, uint32_t k, const float *g
     return batch.flush();
 }
 
-int amsp_adamw_step_shard(const uint16_t *const *partials, uint32_t k, const float *grad_f32, uint64_t n,
-                          uint64_t bucket_elems, float *master, float *exp_avg, float *exp_avg_sq,
-                          uint16_t *param_bf16_out, const amsp_adamw_hparams *hp, void *stream) {
+// amax_slot: the range's kAmaxWordsPerSegment device words that collect the largest |p'| bit pattern, or NULL.
+static int adamw_step_range(const uint16_t *const *partials, uint32_t k, const float *grad_f32, uint64_t n,
+                            uint64_t bucket_elems, float *master, float *exp_avg, float *exp_avg_sq,
+                            uint16_t *param_bf16_out, uint32_t *amax_slot, const amsp_adamw_hparams *hp,
+                            void *stream) {
     if (hp == nullptr) return AMSP_ENULL;
     PartialPtrs pp{};
     if (k > 0) {
@@ -1072,9 +1118,9 @@ int amsp_adamw_step_shard(const uint16_t *const *partials, uint32_t k, const flo
         clear_stale_error();
 #define AMSP_LAUNCH_ADAMW(KV)                                                                              \
         if (out) hipLaunchKernelGGL((adamw_kernel<KV, true>), grid, block, lds, hs, q, (int)k, gf, master + off, \
-                                    exp_avg + off, exp_avg_sq + off, out, c, s);                            \
+                                    exp_avg + off, exp_avg_sq + off, out, amax_slot, c, s);                 \
         else hipLaunchKernelGGL((adamw_kernel<KV, false>), grid, block, lds, hs, q, (int)k, gf, master + off, \
-                                exp_avg + off, exp_avg_sq + off, out, c, s)
+                                exp_avg + off, exp_avg_sq + off, out, amax_slot, c, s)
         if (k == 0) {
             AMSP_LAUNCH_ADAMW(0);
         } else {
@@ -1083,6 +1129,13 @@ int amsp_adamw_step_shard(const uint16_t *const *partials, uint32_t k, const flo
 #undef AMSP_LAUNCH_ADAMW
         return launched();
     });
+}
+
+int amsp_adamw_step_shard(const uint16_t *const *partials, uint32_t k, const float *grad_f32, uint64_t n,
+                          uint64_t bucket_elems, float *master, float *exp_avg, float *exp_avg_sq,
+                          uint16_t *param_bf16_out, const amsp_adamw_hparams *hp, void *stream) {
+    return adamw_step_range(partials, k, grad_f32, n, bucket_elems, master, exp_avg, exp_avg_sq, param_bf16_out,
+                            nullptr, hp, stream);
 }
 
 // ---------------------------------------------------------------- inter-tensor shards
@@ -1167,25 +1220,57 @@ int amsp_grad_sqnorm_segments(const uint16_t *const *partials_flat, uint32_t k, 
     return batch.flush();
 }
 
+size_t amsp_amax_workspace_bytes(uint32_t num_segments) {
+    return (size_t)num_segments * kAmaxWordsPerSegment * sizeof(uint32_t);
+}
+
 int amsp_adamw_step_segments(const uint16_t *const *partials_flat, uint32_t k, uint64_t flat_elems,
                              const amsp_segment *segments, uint32_t num_segments, uint64_t local_elems,
                              float *master_local, float *exp_avg_local, float *exp_avg_sq_local,
-                             uint16_t *param_bf16_flat, const amsp_adamw_hparams *hp, void *stream) {
+                             uint16_t *param_bf16_flat, float *d_amax, void *amax_workspace,
+                             size_t amax_workspace_bytes, const amsp_adamw_hparams *hp, void *stream) {
     PartialPtrs pp;
     int rc = check_partials(partials_flat, k, pp);
     if (rc != AMSP_OK) return rc;
     rc = check_segments(segments, num_segments, flat_elems, local_elems);
     if (rc != AMSP_OK) return rc;
     if (hp == nullptr) return AMSP_ENULL;
+    uint32_t *words = nullptr;
+    if (d_amax != nullptr && num_segments > 0) {
+        if (amax_workspace == nullptr) return AMSP_ENULL;
+        if (misaligned(d_amax, 4) || misaligned(amax_workspace, 4)) return AMSP_EALIGN;
+        if (amax_workspace_bytes < amsp_amax_workspace_bytes(num_segments)) return AMSP_EWORKSPACE;
+        words = static_cast<uint32_t *>(amax_workspace);
+    }
+    for (uint32_t i = 0; i < num_segments; ++i)
+        if (segments[i].length != 0 &&
+            (master_local == nullptr || exp_avg_local == nullptr || exp_avg_sq_local == nullptr))
+            return AMSP_ENULL;
+    hipStream_t hs = (hipStream_t)stream;
+    if (words != nullptr) {   // the maxima start from +0, the smallest |x| pattern
+        const size_t count = (size_t)num_segments * kAmaxWordsPerSegment;
+        if (count > 0xFFFFFFFFull) return AMSP_EINVAL;
+        clear_stale_error();
+        const unsigned blocks = (unsigned)((count + kThreads - 1) / kThreads);
+        hipLaunchKernelGGL(fill_u32_kernel, dim3(blocks > 1024 ? 1024 : blocks), dim3(kThreads), 0, hs, words,
+                           (uint32_t)count, 0u);
+        if (launched() != AMSP_OK) return AMSP_EDEVICE;
+    }
     for (uint32_t i = 0; i < num_segments; ++i) {
         const amsp_segment &g = segments[i];
         if (g.length == 0) continue;
-        if (master_local == nullptr || exp_avg_local == nullptr || exp_avg_sq_local == nullptr) return AMSP_ENULL;
         PartialPtrs q = offset_partials(pp, k, g.flat_offset);
-        rc = amsp_adamw_step_shard(q.p, k, nullptr, g.length, 0, master_local + g.local_offset,
-                                   exp_avg_local + g.local_offset, exp_avg_sq_local + g.local_offset,
-                                   param_bf16_flat ? param_bf16_flat + g.flat_offset : nullptr, hp, stream);
+        rc = adamw_step_range(q.p, k, nullptr, g.length, 0, master_local + g.local_offset,
+                              exp_avg_local + g.local_offset, exp_avg_sq_local + g.local_offset,
+                              param_bf16_flat ? param_bf16_flat + g.flat_offset : nullptr,
+                              words ? words + (size_t)i * kAmaxWordsPerSegment : nullptr, hp, stream);
         if (rc != AMSP_OK) return rc;
+    }
+    if (words != nullptr) {
+        clear_stale_error();
+        hipLaunchKernelGGL(amax_fold_kernel, dim3(num_segments), dim3(kAmaxSubSlots), 0, hs, words,
+                           reinterpret_cast<uint32_t *>(d_amax));
+        return launched();
     }
     return AMSP_OK;
 }
@@ -1207,7 +1292,7 @@ int amsp_cast_param_fp8_shard(const float *master, uint64_t n, const float *d_sc
 
 int amsp_fp8_payload_segments(const float *master_local, uint64_t local_elems, const amsp_segment *segments,
                               uint32_t num_segments, uint64_t flat_elems, uint8_t *param_fp8_flat, float *d_amax,
-                              float *d_scale, void *stream) {
+                              int amax_ready, float *d_scale, void *stream) {
     int rc = check_segments(segments, num_segments, flat_elems, local_elems);
     if (rc != AMSP_OK) return rc;
     if (num_segments == 0) return AMSP_OK;
@@ -1216,15 +1301,17 @@ int amsp_fp8_payload_segments(const float *master_local, uint64_t local_elems, c
     hipStream_t hs = (hipStream_t)stream;
     uint32_t *slots = reinterpret_cast<uint32_t *>(d_amax);
     clear_stale_error();
-    hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(kThreads), 0, hs, slots, num_segments, 0u);
-    if (launched() != AMSP_OK) return AMSP_EDEVICE;
-    for (uint32_t i = 0; i < num_segments; ++i) {
-        if (segments[i].length == 0) continue;
-        const float *x = master_local + segments[i].local_offset;
-        Stream16 st[1] = {{x, 4}};
-        Span s = make_span(segments[i].length, st, 1, 4);
-        hipLaunchKernelGGL(absmax_kernel, dim3(norm_grid(s)), dim3(kNormThreads), 0, hs, x, s, slots + i);
+    if (!amax_ready) {
+        hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(kThreads), 0, hs, slots, num_segments, 0u);
         if (launched() != AMSP_OK) return AMSP_EDEVICE;
+        for (uint32_t i = 0; i < num_segments; ++i) {
+            if (segments[i].length == 0) continue;
+            const float *x = master_local + segments[i].local_offset;
+            Stream16 st[1] = {{x, 4}};
+            Span s = make_span(segments[i].length, st, 1, 4);
+            hipLaunchKernelGGL(absmax_kernel, dim3(norm_grid(s)), dim3(kNormThreads), 0, hs, x, s, slots + i);
+            if (launched() != AMSP_OK) return AMSP_EDEVICE;
+        }
     }
     hipLaunchKernelGGL(fp8_scale_kernel, dim3(1), dim3(kThreads), 0, hs, d_amax, d_scale, num_segments);
     if (launched() != AMSP_OK) return AMSP_EDEVICE;

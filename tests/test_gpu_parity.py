@@ -489,6 +489,28 @@ def test_fp8_payload_of_inter_tensor_shard(B, torch_mod):
         assert np.array_equal(oracle.select(got, segs), codes)                                # codes bit-exact
         elem_owner = np.repeat(np.array(owner), sizes)
         assert np.all(got[elem_owner != rank] == 0xA5)
+    # the same maxima taken inside the update (fused amax), also with a NaN and a huge value among the new parameters
+    rank = 1
+    segs, local = B.amsp_owned_segments(sizes, owner, rank)
+    inp = H.HostInputs([oracle.select(flat.partials[0], segs)], oracle.select(flat.p, segs).copy(),
+                       oracle.select(flat.m, segs), oracle.select(flat.v, segs))
+    inp.p[7] = np.nan                                         # first segment: NaN wins
+    inp.p[segs[1][1] + 3] = 3e38                              # second segment: a huge finite value
+    dp, dm, dv = H.to_dev_f32(inp.p), H.to_dev_f32(inp.m), H.to_dev_f32(inp.v)
+    d_amax = torch.full((len(segs),), -1.0, dtype=torch.float32, device="cuda")
+    amax_ws = torch.full((B.amsp_amax_workspace_bytes(len(segs)) // 4,), 0x7FFFFFFF, dtype=torch.int32, device="cuda")
+    B.amsp_adamw_step_segments([H.to_dev_bf16(flat.partials[0])], total, segs, local, dp, dm, dv, None,
+                               B.AdamWHparams(**H.hparams_of(w, max_norm=0.0, weight_decay=0.0)), d_amax=d_amax,
+                               amax_workspace=amax_ws)
+    with pytest.raises(B.AmspError) as ei:                  # too small a workspace: refused, nothing enqueued
+        B.amsp_adamw_step_segments([H.to_dev_bf16(flat.partials[0])], total, segs, local, dp, dm, dv, None,
+                                   B.AdamWHparams(**H.hparams_of(w)), d_amax=d_amax, amax_workspace=amax_ws[:-1])
+    assert ei.value.status == B.AMSP_EWORKSPACE
+    p_new = dp.cpu().numpy()
+    _, _, amaxes = oracle.fp8_payload_segments(p_new, segs)
+    got = d_amax.cpu().numpy()
+    assert np.isnan(got[0]) and np.isnan(np.float32(amaxes[0])) and got[1] == np.float32(3e38)
+    assert got[1:].tolist() == [float(np.float32(a)) for a in amaxes[1:]]
     # a NaN and an all-zero tensor: scale 1 on both sides
     t = np.zeros(5000, dtype=np.float32)
     t[2500:] = synth.fill_f32(9, 0, 2500, 1.0)

@@ -145,8 +145,12 @@ def test_random_inter_tensor_models(B, torch_mod):
             out = torch.full((total,), 0x5A5A, dtype=torch.int16, device="cuda")
             d_s = torch.full((1,), -3.0, dtype=torch.float64, device="cuda")
             B.amsp_grad_sqnorm_segments(dparts, total, segs, d_s, ws)
+            d_amax_fused = torch.full((max(len(segs), 1),), -1.0, dtype=torch.float32, device="cuda")
+            amax_ws = torch.full((max(B.amsp_amax_workspace_bytes(len(segs)) // 4, 1),), 0x7FFFFFFF, dtype=torch.int32,
+                                 device="cuda")                 # poisoned: the library clears what it uses
             B.amsp_adamw_step_segments(dparts, total, segs, local, dp, dm, dv, out,
-                                       B.AdamWHparams(d_total_sqnorm=d_s, **hp))
+                                       B.AdamWHparams(d_total_sqnorm=d_s, **hp), d_amax=d_amax_fused,
+                                       amax_workspace=amax_ws)
             torch.cuda.synchronize()
             out_bits = H.dev_bits(out)
             assert np.all(out_bits[elem_owner != rank] == 0x5A5A)
@@ -171,3 +175,9 @@ def test_random_inter_tensor_models(B, torch_mod):
             got = fp8.cpu().numpy()
             assert np.array_equal(oracle.select(got, segs), codes)
             assert np.all(got[elem_owner != rank] == 0xA5)
+            # the maxima taken inside the update are the same bits, and the payload built on them the same codes
+            assert d_amax_fused.cpu().numpy()[:len(segs)].tolist() == [float(np.float32(a)) for a in amaxes]
+            fp8b = torch.full((total,), 0xA5, dtype=torch.uint8, device="cuda")
+            d_scale_b = torch.zeros(len(segs), dtype=torch.float32, device="cuda")
+            B.amsp_fp8_payload_segments(dp, local, segs, total, fp8b, d_amax_fused, d_scale_b, amax_ready=True)
+            assert torch.equal(fp8b, fp8) and torch.equal(d_scale_b, d_scale)
