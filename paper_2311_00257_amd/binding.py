@@ -260,14 +260,14 @@ def amsp_grad_sqnorm_segments(partials_flat, flat_elems: int, segments, d_sqnorm
 
 def amsp_adamw_step_segments(partials_flat, flat_elems: int, segments, local_elems: int, master_local,
                              exp_avg_local, exp_avg_sq_local, param_bf16_flat, hp: AdamWHparams, stream=None,
-                             d_amax=None, amax_workspace=None) -> None:
+                             d_amax=None, amax_workspace=None, amax_workspace_bytes: Optional[int] = None) -> None:
     arr, k = _partials(partials_flat)
     segs, ns = _segments(segments)
     c = _hp_struct(hp) if hp is not None else None
     _check(load().amsp_adamw_step_segments(arr, k, flat_elems, segs, ns, local_elems, _ptr(master_local),
                                            _ptr(exp_avg_local), _ptr(exp_avg_sq_local), _ptr(param_bf16_flat),
                                            _ptr(d_amax), _ptr(amax_workspace),
-                                           _nbytes(amax_workspace, None),
+                                           _nbytes(amax_workspace, amax_workspace_bytes),
                                            ctypes.byref(c) if c is not None else None, _stream(stream)),
            "amsp_adamw_step_segments")
 

@@ -158,6 +158,16 @@ def test_segment_validation_without_device():
         B.amsp_adamw_step_segments([A], 100, [(0, 0, 10)], 100, 0, A, A, A, hp, stream=0)
     assert ei.value.status == B.AMSP_ENULL
     B.amsp_adamw_step_segments([A], 100, [], 0, 0, 0, 0, 0, hp, stream=0)          # owns nothing: fine
+    # per-segment maxima asked for: the workspace is checked before anything is enqueued
+    need = B.amsp_amax_workspace_bytes(3)
+    assert need == 3 * B.amsp_amax_workspace_bytes(1) > 0 and B.amsp_amax_workspace_bytes(0) == 0
+    three = [(0, 0, 10), (20, 10, 10), (40, 20, 10)]
+    for kw, status in ((dict(amax_workspace=None), B.AMSP_ENULL),
+                       (dict(amax_workspace=A + 2, amax_workspace_bytes=need), B.AMSP_EALIGN),
+                       (dict(amax_workspace=A, amax_workspace_bytes=need - 4), B.AMSP_EWORKSPACE)):
+        with pytest.raises(B.AmspError) as ei:
+            B.amsp_adamw_step_segments([A], 100, three, 100, A, A, A, A, hp, stream=0, d_amax=A, **kw)
+        assert ei.value.status == status
     with pytest.raises(B.AmspError) as ei:
         B.amsp_fp8_payload_segments(A, 100, [(95, 0, 10)], 100, A, A, A, stream=0)
     assert ei.value.status == B.AMSP_EINVAL
