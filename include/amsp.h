@@ -35,7 +35,8 @@
  *     enqueued and the call returns without waiting; amsp_shard_range alone is synchronous.
  *   - `bucket_elems` (Section IV-C.2: gradients are synchronised in buckets of size U; here
  *     counted in elements): 0 processes [0,n) in one launch; U > 0 processes the buckets
- *     [bU, min((b+1)U, n)) in order, one launch each, as they would arrive.
+ *     [bU, min((b+1)U, n)) in order, one launch each, as they would arrive (the read-only
+ *     amsp_grad_sqnorm takes up to 32 buckets per launch, each with its own head and tail).
  *   - One launch covers at most (2^31 - 1) * 64 elements (about 5.5e11, more than fits the device);
  *     a longer range, or a longer bucket, is AMSP_EINVAL.
  *   - n == 0 is valid: AMSP_OK, nothing launched (amsp_grad_sqnorm still writes 0 when
@@ -112,7 +113,9 @@ int amsp_reduce_grad_shard(const uint16_t *const *partials, uint32_t k, uint64_t
  *   k >= 1      g is recomputed from `partials` exactly as in step 1 (grad_f32 ignored)
  *   k == 0      g is read from grad_f32, device fp32[n] (partials ignored)
  *   d_sqnorm    device double, written when the enqueued work completes
- *   accumulate  0: overwrite; 1: add to the value already there (in bucket order)
+ *   accumulate  0: overwrite; 1: add to the value already there
+ *   The order of the additions is fixed by (n, bucket_elems, the pointers' alignment, the number of
+ *   compute units): the same call gives the same bits every time.
  *   workspace   device, >= amsp_workspace_bytes(), 8-byte aligned; contents need no
  *               initialisation and are clobbered; calls sharing a workspace must be ordered
  *               on one stream
@@ -203,8 +206,9 @@ int amsp_owned_segments(const uint64_t *tensor_elems, const uint32_t *owner, uin
                         uint32_t *num_segments, uint64_t *local_elems);
 
 /*
- * Steps 2 and 1+3+4 over a segment list: as amsp_grad_sqnorm / amsp_adamw_step_shard, one launch
- * per segment in list order ("select": only owned elements are read; "drop": nothing else is touched).
+ * Steps 2 and 1+3+4 over a segment list: as amsp_grad_sqnorm / amsp_adamw_step_shard, the update one
+ * launch per segment in list order, the norm up to 32 segments per launch ("select": only owned
+ * elements are read; "drop": nothing else is touched).
  *   partials_flat    host array of k device pointers, each bf16[flat_elems] (flat whole-model
  *                    gradient buffers: one all-reduced buffer, k = 1, or k partial ones)
  *   segments         host array [num_segments]; each must lie inside [0, flat_elems) and

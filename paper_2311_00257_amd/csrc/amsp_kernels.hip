@@ -321,12 +321,24 @@ __global__ void __launch_bounds__(kThreads) reduce_kernel(PartialPtrs pp, int k,
 // shuffle tree, waves through LDS, and each block stores one double.  A second one-block
 // kernel adds the block sums in index order.  No atomics, so the result depends only on
 // (n, alignment, grid size), never on timing.
+// One launch covers up to kMaxNormSegs ranges (buckets of a flat range, or the segments of an
+// inter-tensor shard), each with its own head and tail: a read-only pass gains nothing from a launch per
+// range, and short launches lose 10-30 % to their start and end.
+constexpr int kMaxNormSegs = 32;
+struct NormSeg {
+    uint64_t base;   // first element of the range, relative to the stream pointers
+    Span s;
+};
+struct NormSegTable {
+    int count;
+    NormSeg seg[kMaxNormSegs];
+};
+
+// acc += sum of g^2 over one range: this lane's share of the vectors, a grid stride apart.
 template <int K, int VEC>
-__global__ void __launch_bounds__(kNormThreads) sqnorm_kernel(PartialPtrs pp, int k, const float *__restrict__ gf32,
-                                                              double *__restrict__ block_sums, Span s) {
-    const uint64_t first = (uint64_t)blockIdx.x * kNormThreads + threadIdx.x;
-    const uint64_t stride = (uint64_t)gridDim.x * kNormThreads;
-    double acc = 0.0;
+__device__ __forceinline__ double sqnorm_span(const PartialPtrs &pp, int k, const float *__restrict__ gf32,
+                                              const uint64_t base, const Span &s, const uint64_t first,
+                                              const uint64_t stride, double acc) {
     if (s.vectorised) {
         uint64_t v = first;
         // With one or two streams a single vector per lane leaves too little in flight: take U vectors,
@@ -340,7 +352,7 @@ __global__ void __launch_bounds__(kNormThreads) sqnorm_kernel(PartialPtrs pp, in
                 W w[U][KS];
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
-                    const uint64_t e = s.head + (v + u * stride) * VEC;
+                    const uint64_t e = base + s.head + (v + u * stride) * VEC;
                     if constexpr (K == 0) {
                         a[u] = ld_stream(reinterpret_cast<const f32x4 *>(gf32 + e));
                     } else {
@@ -366,23 +378,33 @@ __global__ void __launch_bounds__(kNormThreads) sqnorm_kernel(PartialPtrs pp, in
         }
         for (; v < s.nvec; v += stride) {
             float g[VEC];
-            grad_vec<K, VEC>(pp, k, gf32, s.head + v * VEC, g);
+            grad_vec<K, VEC>(pp, k, gf32, base + s.head + v * VEC, g);
 #pragma unroll
             for (int c = 0; c < VEC; ++c) acc = fma((double)g[c], (double)g[c], acc);
         }
         if (blockIdx.x == 0)
             for (uint32_t t = threadIdx.x; t < s.head + s.tail; t += kNormThreads) {
-                const double g = (double)grad1<K>(pp, k, gf32, edge_elem<VEC>(s, t));
+                const double g = (double)grad1<K>(pp, k, gf32, base + edge_elem<VEC>(s, t));
                 acc = fma(g, g, acc);
             }
     } else {
         for (uint64_t i = first; i < s.n; i += stride) {
-            double g = (double)grad1<K>(pp, k, gf32, i);
+            double g = (double)grad1<K>(pp, k, gf32, base + i);
             acc = fma(g, g, acc);
         }
     }
-    const double t = block_sum<kNormThreads>(acc);
-    if (threadIdx.x == 0) block_sums[blockIdx.x] = t;
+    return acc;
+}
+
+template <int K, int VEC>
+__global__ void __launch_bounds__(kNormThreads) sqnorm_kernel(PartialPtrs pp, int k, const float *__restrict__ gf32,
+                                                              double *__restrict__ block_sums, NormSegTable t) {
+    const uint64_t first = (uint64_t)blockIdx.x * kNormThreads + threadIdx.x;
+    const uint64_t stride = (uint64_t)gridDim.x * kNormThreads;
+    double acc = 0.0;
+    for (int i = 0; i < t.count; ++i) acc = sqnorm_span<K, VEC>(pp, k, gf32, t.seg[i].base, t.seg[i].s, first, stride, acc);
+    const double total = block_sum<kNormThreads>(acc);
+    if (threadIdx.x == 0) block_sums[blockIdx.x] = total;
 }
 
 // Adds nblocks block sums in a fixed order (lane-strided, then a tree) and stores or adds the total.
@@ -776,15 +798,16 @@ int cu_count() {
     return n;
 }
 
-// The norm pass: two 1024-thread blocks per CU (what a CU holds), at most kNormBlocks.
-int norm_grid(const Span &s) {
-    uint64_t work = s.vectorised ? s.nvec : s.n;
+// The norm pass: two 1024-thread blocks per CU (what a CU holds), at most kNormBlocks; `work` = lanes' worth
+// of vectors (or elements on the element-wise path).
+int norm_grid(uint64_t work) {
     uint64_t blocks = (work + kNormThreads - 1) / kNormThreads;
     uint64_t cap = 2 * (uint64_t)cu_count();
     if (cap > kNormBlocks) cap = kNormBlocks;
     if (blocks > cap) blocks = cap;
     return blocks == 0 ? 1 : (int)blocks;
 }
+int norm_grid(const Span &s) { return norm_grid(s.vectorised ? s.nvec : s.n); }
 
 // One launch covers at most this many elements (one wave per 256 of them in a grid of < 2^31 blocks):
 // about 5.5e11, beyond any buffer that fits the device.
@@ -913,21 +936,30 @@ int finish_sums(hipStream_t hs, double *sums, uint64_t count, double *stage, dou
     return launched();
 }
 
-// One norm launch over `len` elements starting at the given pointers, its block sums appended to the batch.
-int norm_launch(NormBatch &batch, const PartialPtrs &q, uint32_t k, const float *gf, uint64_t len) {
-    Stream16 st[AMSP_MAX_K + 1];
-    int ns = add_partial_streams(st, 0, q, k);
-    if (k == 0) st[ns++] = Stream16{gf, 4};
+// One norm launch over up to kMaxNormSegs ranges [base[i], base[i] + len[i]) of the streams, its block sums
+// appended to the batch.  The streams are the k partials (k >= 1) or the fp32 gradient (k == 0).
+int norm_launch(NormBatch &batch, const PartialPtrs &pp, uint32_t k, const float *gf, const uint64_t *base,
+                const uint64_t *len, int count) {
     // 16-byte accesses in every case: 8 bf16 elements per lane, or 4 of the fp32 gradient
     const int vec = k == 0 ? 4 : kVecNorm;
-    Span s = make_span(len, st, ns, vec);
-    const int grid = norm_grid(s);
+    NormSegTable t;
+    t.count = count;
+    uint64_t work = 0;
+    for (int i = 0; i < count; ++i) {
+        Stream16 st[AMSP_MAX_K + 1];
+        int ns = add_partial_streams(st, 0, offset_partials(pp, k, base[i]), k);
+        if (k == 0) st[ns++] = Stream16{gf + base[i], 4};
+        t.seg[i].base = base[i];
+        t.seg[i].s = make_span(len[i], st, ns, vec);
+        work += t.seg[i].s.vectorised ? t.seg[i].s.nvec : t.seg[i].s.n;
+    }
+    const int grid = norm_grid(work);
     double *block_sums = nullptr;
     int rc = batch.reserve(grid, &block_sums);
     if (rc != AMSP_OK) return rc;
     hipStream_t hs = batch.hs;
 #define AMSP_LAUNCH_SQNORM(KV, V)                                                                     \
-    hipLaunchKernelGGL((sqnorm_kernel<KV, V>), dim3(grid), dim3(kNormThreads), 0, hs, q, (int)k, gf, block_sums, s)
+    hipLaunchKernelGGL((sqnorm_kernel<KV, V>), dim3(grid), dim3(kNormThreads), 0, hs, pp, (int)k, gf, block_sums, t)
     if (k == 0) {
         AMSP_LAUNCH_SQNORM(0, 4);
     } else {
@@ -936,6 +968,28 @@ int norm_launch(NormBatch &batch, const PartialPtrs &q, uint32_t k, const float 
 #undef AMSP_LAUNCH_SQNORM
     return launched();
 }
+
+// Norm launches over a list of ranges, kMaxNormSegs per launch, in list order.
+struct NormRanges {
+    NormBatch &batch;
+    const PartialPtrs &pp;
+    uint32_t k;
+    const float *gf;
+    uint64_t base[kMaxNormSegs], len[kMaxNormSegs];
+    int count = 0;
+
+    int flush() {
+        if (count == 0) return AMSP_OK;
+        const int rc = norm_launch(batch, pp, k, gf, base, len, count);
+        count = 0;
+        return rc;
+    }
+    int add(uint64_t b, uint64_t l) {
+        base[count] = b;
+        len[count] = l;
+        return ++count == kMaxNormSegs ? flush() : AMSP_OK;
+    }
+};
 
 }  // namespace
 
@@ -1054,9 +1108,9 @@ int amsp_grad_sqnorm(const uint16_t *const *partials, uint32_t k, const float *g
         if (!accumulate) return finish_sums(batch.hs, batch.sums, 0, batch.sums + kNormSlots, d_sqnorm, 0);
         return AMSP_OK;
     }
-    int rc = for_buckets(n, bucket_elems, [&](uint64_t off, uint64_t len) {
-        return norm_launch(batch, offset_partials(pp, k, off), k, k == 0 ? grad_f32 + off : nullptr, len);
-    });
+    NormRanges ranges{batch, pp, k, grad_f32};
+    int rc = for_buckets(n, bucket_elems, [&](uint64_t off, uint64_t len) { return ranges.add(off, len); });
+    if (rc == AMSP_OK) rc = ranges.flush();
     if (rc != AMSP_OK) return rc;
     return batch.flush();
 }
@@ -1207,12 +1261,15 @@ int amsp_grad_sqnorm_segments(const uint16_t *const *partials_flat, uint32_t k, 
     NormBatch batch{(hipStream_t)stream, static_cast<double *>(workspace), d_sqnorm, 0, accumulate != 0};
     clear_stale_error();
     bool any = false;
+    NormRanges ranges{batch, pp, k, nullptr};
     for (uint32_t i = 0; i < num_segments; ++i) {
         if (segments[i].length == 0) continue;
-        rc = norm_launch(batch, offset_partials(pp, k, segments[i].flat_offset), k, nullptr, segments[i].length);
+        rc = ranges.add(segments[i].flat_offset, segments[i].length);
         if (rc != AMSP_OK) return rc;
         any = true;
     }
+    rc = ranges.flush();
+    if (rc != AMSP_OK) return rc;
     if (!any) {   // nothing owned: same contract as n == 0
         if (!accumulate) return finish_sums(batch.hs, batch.sums, 0, batch.sums + kNormSlots, d_sqnorm, 0);
         return AMSP_OK;
