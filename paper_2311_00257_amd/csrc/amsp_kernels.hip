@@ -694,6 +694,58 @@ Span make_span(uint64_t n, const Stream16 *st, int ns, int vec) {
     return s;
 }
 
+// Occupancy cap of the read+write kernels.  With one-wave workgroups and only as many waves resident
+// per CU as it takes to keep a target amount of loads in flight, the same kernels move 5-12 % more
+// bytes per second than at full occupancy (32 waves): fewer waves in flight keep the window of
+// addresses being read and written at any moment small, and reads and writes disturb each other
+// less.  The cap is imposed by giving every workgroup an unused slice of the CU's 160 KiB of LDS.
+// `load_bytes_per_lane` is what one lane has in flight before it waits.
+struct RwKnobs {
+    int inflight_kib, min_waves, reduce_inflight_kib, reduce_min_waves;
+};
+RwKnobs read_rw_knobs() {   // developer knobs for sweeps; read once (thread-safe static below)
+    auto knob = [](const char *name, int lo, int hi, int dflt) {
+        const char *v = getenv(name);
+        const int x = v ? atoi(v) : 0;
+        return (x >= lo && x <= hi) ? x : dflt;
+    };
+    return RwKnobs{knob("AMSP_INFLIGHT_KIB", 8, 1024, 40), knob("AMSP_MIN_WAVES", 4, 32, 8),
+                   knob("AMSP_REDUCE_INFLIGHT_KIB", 8, 1024, 64), knob("AMSP_REDUCE_MIN_WAVES", 4, 32, 12)};
+}
+const RwKnobs &rw_knobs() {
+    static const RwKnobs knobs = read_rw_knobs();
+    return knobs;
+}
+
+// What a kernel family wants in flight per CU, and the fewest waves it is given.
+struct RwTarget {
+    int inflight_kib, min_waves;
+};
+// AdamW kernels: 40 KiB, at least 8 waves (10 waves for an fp32 gradient, 12 for k = 1, 8 from k = 4 on),
+// 7 once a wave loads more than 8 KiB (fused step from k = 9 on: k = 16 reads 6,330 GB/s at 7 waves
+// against 6,010-6,270 at 8, while k = 8 is best at 8).
+RwTarget adamw_target(unsigned load_bytes_per_lane) {
+    const int floor = 64u * load_bytes_per_lane > 8192u ? rw_knobs().min_waves - 1 : rw_knobs().min_waves;
+    return RwTarget{rw_knobs().inflight_kib, floor};
+}
+// Reduction (its writes are a small share of the traffic): 64 KiB, at least 12 waves (k = 8: 16 waves,
+// 13 with accumulate; k = 16: 12; no cap below k = 8).
+RwTarget reduce_target() { return RwTarget{rw_knobs().reduce_inflight_kib, rw_knobs().reduce_min_waves}; }
+
+int rw_waves_per_cu(unsigned load_bytes_per_lane, RwTarget t) {
+    const unsigned per_wave = 64u * load_bytes_per_lane;
+    int waves = (int)(((unsigned)t.inflight_kib * 1024u + per_wave - 1) / per_wave);
+    if (waves < t.min_waves) waves = t.min_waves;
+    return waves > 32 ? 32 : waves;
+}
+
+// Bytes of dynamic LDS per one-wave workgroup so that at most that many of them fit a CU.
+unsigned occupancy_lds(unsigned load_bytes_per_lane, RwTarget t) {
+    const int waves = rw_waves_per_cu(load_bytes_per_lane, t);
+    if (waves >= 32) return 0;
+    return (unsigned)((160 * 1024 / waves) & ~255);
+}
+
 // One lane per vector in one-wave workgroups under the occupancy cap, or, on the element-wise path,
 // one lane per element in 256-thread workgroups; the whole range in one grid either way.
 struct RwLaunch {
@@ -701,19 +753,13 @@ struct RwLaunch {
     unsigned lds;
 };
 
-unsigned occupancy_lds(unsigned load_bytes_per_lane, int inflight_kib);
-struct RwKnobs;
-const RwKnobs &rw_knobs();
-int adamw_inflight_kib();
-int reduce_inflight_kib();
-
-RwLaunch rw_launch(const Span &s, unsigned load_bytes_per_lane, int inflight_kib) {
+RwLaunch rw_launch(const Span &s, unsigned load_bytes_per_lane, RwTarget t) {
     const uint64_t work = s.vectorised ? s.nvec : s.n;
     const unsigned threads = s.vectorised ? kRwThreads : kThreads;
     uint64_t blocks = (work + threads - 1) / threads;   // <= kMaxGrid: the entry points refuse larger launches
     if (blocks == 0) blocks = 1;
     return RwLaunch{dim3((unsigned)blocks), dim3(threads),
-                    s.vectorised ? occupancy_lds(load_bytes_per_lane, inflight_kib) : 0u};
+                    s.vectorised ? occupancy_lds(load_bytes_per_lane, t) : 0u};
 }
 
 // Reduce with the norm fused in: every block leaves one double.  One-wave blocks of one vector per
@@ -740,51 +786,6 @@ uint64_t reduce_norm_slots(uint64_t n, uint64_t bucket_elems) {
     const uint64_t full = n / bucket_elems, rest = n % bucket_elems;
     return full * reduce_norm_blocks_max(bucket_elems) + (rest ? reduce_norm_blocks_max(rest) : 0);
 }
-
-// Occupancy cap of the read+write kernels.  With one-wave workgroups and only as many waves resident
-// per CU as it takes to keep a target amount of loads in flight, the same kernels move 5-12 % more
-// bytes per second than at full occupancy (32 waves): fewer waves in flight keep the window of
-// addresses being read and written at any moment small, and reads and writes disturb each other
-// less.  Measured targets: ~40 KiB per CU for the AdamW kernels but never fewer than 8 waves (10 waves
-// for an fp32 gradient, 12 for k = 1, 8 from k = 4 on), ~96 KiB for the reduction (24 waves at k = 8,
-// 12 at k = 16), whose writes are a small share.  The
-// cap is imposed by giving every workgroup an unused slice of the CU's 160 KiB of LDS.
-// `load_bytes_per_lane` is what one lane has in flight before it waits.
-struct RwKnobs {
-    int inflight_kib, min_waves, reduce_inflight_kib;
-};
-RwKnobs read_rw_knobs() {   // developer knobs for sweeps; read once (thread-safe static below)
-    auto knob = [](const char *name, int lo, int hi, int dflt) {
-        const char *v = getenv(name);
-        const int x = v ? atoi(v) : 0;
-        return (x >= lo && x <= hi) ? x : dflt;
-    };
-    return RwKnobs{knob("AMSP_INFLIGHT_KIB", 8, 1024, 40), knob("AMSP_MIN_WAVES", 4, 32, 8),
-                   knob("AMSP_REDUCE_INFLIGHT_KIB", 8, 1024, 96)};
-}
-const RwKnobs &rw_knobs() {
-    static const RwKnobs knobs = read_rw_knobs();
-    return knobs;
-}
-int rw_waves_per_cu(unsigned load_bytes_per_lane, int inflight_kib) {
-    const unsigned per_wave = 64u * load_bytes_per_lane;
-    int waves = (int)(((unsigned)inflight_kib * 1024u + per_wave - 1) / per_wave);
-    // the floor: 8 waves, 7 once a wave loads more than 8 KiB (fused step from k = 9 on; k = 16 reads
-    // 6,330 GB/s at 7 waves against 6,010-6,270 at 8, while k = 8 is best at 8)
-    const int floor = per_wave > 8192u ? rw_knobs().min_waves - 1 : rw_knobs().min_waves;
-    if (waves < floor) waves = floor;
-    return waves > 32 ? 32 : waves;
-}
-
-// Bytes of dynamic LDS per one-wave workgroup so that at most that many of them fit a CU.
-unsigned occupancy_lds(unsigned load_bytes_per_lane, int inflight_kib) {
-    const int waves = rw_waves_per_cu(load_bytes_per_lane, inflight_kib);
-    if (waves >= 32) return 0;
-    return (unsigned)((160 * 1024 / waves) & ~255);
-}
-
-int adamw_inflight_kib() { return rw_knobs().inflight_kib; }
-int reduce_inflight_kib() { return rw_knobs().reduce_inflight_kib; }
 
 int cu_count() {
     static std::atomic<int> cached[64];   // per device; zero until first asked (any thread may fill it: same value)
@@ -1029,7 +1030,7 @@ int amsp_cast_param_shard(const float *master, uint16_t *param_bf16_out, uint64_
     Stream16 st[2] = {{master, 4}, {param_bf16_out, 2}};
     Span s = make_span(n, st, 2, kVecRW);
     clear_stale_error();
-    const RwLaunch L = rw_launch(s, 16, adamw_inflight_kib());
+    const RwLaunch L = rw_launch(s, 16, adamw_target(16));
     hipLaunchKernelGGL(cast_kernel, L.grid, L.block, L.lds, (hipStream_t)stream, master, param_bf16_out, s);
     return launched();
 }
@@ -1071,7 +1072,7 @@ int amsp_reduce_grad_shard(const uint16_t *const *partials, uint32_t k, uint64_t
         st[ns++] = Stream16{grad_out + off, 4};
         Span s = make_span(len, st, ns, kVecRW);
         clear_stale_error();
-        const RwLaunch L = rw_launch(s, 8 * k + (accumulate ? 16 : 0), reduce_inflight_kib());
+        const RwLaunch L = rw_launch(s, 8 * k + (accumulate ? 16 : 0), reduce_target());
         if (!norm) {
             AMSP_DISPATCH_K(k, hipLaunchKernelGGL((reduce_kernel<KK, false>), L.grid, L.block, L.lds, hs, q, (int)k,
                                                   grad_out + off, accumulate, block_sums, s));
@@ -1166,7 +1167,8 @@ static int adamw_step_range(const uint16_t *const *partials, uint32_t k, const f
         uint16_t *out = param_bf16_out ? param_bf16_out + off : nullptr;
         if (out) st[ns++] = Stream16{out, 2};
         Span s = make_span(len, st, ns, kVecRW);
-        const RwLaunch L = rw_launch(s, (k != 0 ? 8 * k : 16) + 48, adamw_inflight_kib());
+        const unsigned lane_bytes = (k != 0 ? 8 * k : 16) + 48;
+        const RwLaunch L = rw_launch(s, lane_bytes, adamw_target(lane_bytes));
         const dim3 grid = L.grid, block = L.block;
         const unsigned lds = L.lds;
         clear_stale_error();
@@ -1342,7 +1344,7 @@ int amsp_cast_param_fp8_shard(const float *master, uint64_t n, const float *d_sc
     Stream16 st[2] = {{master, 4}, {param_fp8_out, 1}};
     Span s = make_span(n, st, 2, 4);
     clear_stale_error();
-    const RwLaunch L = rw_launch(s, 16, adamw_inflight_kib());
+    const RwLaunch L = rw_launch(s, 16, adamw_target(16));
     hipLaunchKernelGGL(cast_fp8_kernel, L.grid, L.block, L.lds, (hipStream_t)stream, master, d_scale, param_fp8_out, s);
     return launched();
 }
