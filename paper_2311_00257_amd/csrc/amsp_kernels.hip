@@ -189,8 +189,8 @@ __device__ __forceinline__ float grad1(const PartialPtrs &pp, int k, const float
 }
 
 // A launch covers n elements: `head` leading ones up to the element at which every stream is
-// aligned (to a 128-byte line when the streams allow it, so that every wave's piece of every stream
-// is whole lines; else to its vector access), nvec groups of VEC taken with vector accesses, and
+// aligned (to a wave's piece when the streams allow it, else to a 128-byte line, else to its vector
+// access), nvec groups of VEC taken with vector accesses, and
 // `tail` < VEC trailing ones.  Head and tail are the "edge", done element-wise by block 0.  When the
 // streams have no common phase the host sets vectorised = 0 and every element goes through the
 // element-wise loop.
@@ -206,6 +206,46 @@ struct Span {
 template <int VEC>
 __device__ __forceinline__ uint64_t edge_elem(const Span &s, uint32_t t) {
     return t < s.head ? (uint64_t)t : (uint64_t)s.head + s.nvec * VEC + (t - s.head);
+}
+
+// Several buckets in one launch (a launch per 25 M-element bucket loses ~4 % to its start and end, the
+// reduction ~10 %).  Bucket b covers [b * bucket_elems, min((b + 1) * bucket_elems, n)) and is given
+// blocks_per_bucket consecutive one-wave blocks; its own head, vector count and tail follow from h0, the
+// head of element 0, because alignment repeats every mask + 1 elements.  bucket_elems == 0: the launch
+// is the single range described by the Span argument.
+struct Buckets {
+    uint64_t bucket_elems;
+    uint64_t n;
+    uint32_t h0;
+    uint32_t mask;
+    uint32_t blocks_per_bucket;
+};
+
+// The range this block works on: its Span (relative to `off`), the range's first element `off`, and the
+// block's index within the range.
+template <int VEC>
+__device__ __forceinline__ void block_range(const Buckets &bk, Span &s, uint64_t &off, uint32_t &local_block) {
+    off = 0;
+    local_block = blockIdx.x;
+    if (bk.bucket_elems != 0) {
+        const uint32_t b = blockIdx.x / bk.blocks_per_bucket;
+        local_block = blockIdx.x - b * bk.blocks_per_bucket;
+        off = (uint64_t)b * bk.bucket_elems;
+        const uint64_t left = bk.n - off;
+        const uint64_t len = left < bk.bucket_elems ? left : bk.bucket_elems;
+        uint32_t head = (bk.h0 - (uint32_t)off) & bk.mask;
+        s.n = len;
+        s.vectorised = 1;
+        if (len < (uint64_t)head + VEC) {   // too short for one aligned vector: all of it is edge
+            s.head = (uint32_t)len;
+            s.nvec = 0;
+            s.tail = 0;
+        } else {
+            s.head = head;
+            s.nvec = (len - head) / VEC;
+            s.tail = (uint32_t)(len - head - s.nvec * VEC);
+        }
+    }
 }
 
 // The read+write kernels are straight-line code: the grid covers the range exactly once, with
@@ -267,13 +307,17 @@ __device__ __forceinline__ double block_sum(double acc) {
 // vector path (a one-wave block), a capped number on the element-wise path.
 template <int K, bool NORM>
 __global__ void __launch_bounds__(kThreads) reduce_kernel(PartialPtrs pp, int k, float *__restrict__ out,
-                                                          int accumulate, double *__restrict__ block_sums, Span s) {
+                                                          int accumulate, double *__restrict__ block_sums, Span s,
+                                                          Buckets bk) {
     constexpr int VEC = kVecRW;
     double acc = 0.0;
     if (s.vectorised) {
-        const uint64_t v = vector_index();
+        uint64_t off;
+        uint32_t lb;
+        block_range<VEC>(bk, s, off, lb);
+        const uint64_t v = (uint64_t)lb * kRwThreads + threadIdx.x;
         if (v < s.nvec) {
-            const uint64_t e = s.head + v * VEC;
+            const uint64_t e = off + s.head + v * VEC;
             float g[VEC], o[VEC];
             if (accumulate) ld_f32<VEC>(out, e, o);   // issued ahead of the partial loads
             grad_vec<K, VEC>(pp, k, nullptr, e, g);
@@ -287,9 +331,9 @@ __global__ void __launch_bounds__(kThreads) reduce_kernel(PartialPtrs pp, int k,
                 for (int c = 0; c < VEC; ++c) acc = fma((double)g[c], (double)g[c], acc);
             }
         }
-        if (blockIdx.x == 0)
+        if (lb == 0)
             for (uint32_t t = threadIdx.x; t < s.head + s.tail; t += kRwThreads) {
-                const uint64_t i = edge_elem<VEC>(s, t);
+                const uint64_t i = off + edge_elem<VEC>(s, t);
                 float g1 = grad1<K>(pp, k, nullptr, i);
                 if (accumulate) g1 = out[i] + g1;
                 out[i] = g1;
@@ -508,15 +552,19 @@ template <int K, bool WRITE_BF16>
 __global__ void __launch_bounds__(kThreads) adamw_kernel(PartialPtrs pp, int k, const float *__restrict__ gf32,
                                                          float *__restrict__ master, float *__restrict__ exp_avg,
                                                          float *__restrict__ exp_avg_sq, uint16_t *__restrict__ out,
-                                                         uint32_t *__restrict__ amax, AdamConsts c, Span s) {
+                                                         uint32_t *__restrict__ amax, AdamConsts c, Span s,
+                                                         Buckets bk) {
     constexpr int VEC = kVecRW;
     const double sqnorm = load_sqnorm(c);
     const uint32_t seen = amax_seen(amax);
     uint32_t biggest = 0;   // of |p'| over this lane's elements, when amax != nullptr
     if (s.vectorised) {
-        const uint64_t vi = vector_index();
+        uint64_t off;
+        uint32_t lb;
+        block_range<VEC>(bk, s, off, lb);
+        const uint64_t vi = (uint64_t)lb * kRwThreads + threadIdx.x;
         if (vi < s.nvec) {
-            const uint64_t e = s.head + vi * VEC;
+            const uint64_t e = off + s.head + vi * VEC;
             float g[VEC], p[VEC], m[VEC], v[VEC];
             // every load of the vector is in flight before anything waits: one memory round trip
             ld_f32<VEC>(master, e, p);
@@ -535,10 +583,10 @@ __global__ void __launch_bounds__(kThreads) adamw_kernel(PartialPtrs pp, int k, 
                 for (int q = 0; q < VEC; ++q) biggest = max(biggest, abs_bits(p[q]));
             }
         }
-        if (blockIdx.x == 0) {
+        if (lb == 0) {
             const float scale = clip_scale(c, sqnorm);
             for (uint32_t t = threadIdx.x; t < s.head + s.tail; t += kRwThreads) {
-                const uint64_t i = edge_elem<VEC>(s, t);
+                const uint64_t i = off + edge_elem<VEC>(s, t);
                 float p = master[i], m = exp_avg[i], v = exp_avg_sq[i];
                 adamw1(c, scale, grad1<K>(pp, k, gf32, i), p, m, v);
                 master[i] = p;
@@ -663,14 +711,33 @@ struct Stream16 {
     uint32_t elem;   // bytes per element: 2 or 4
 };
 
-// Smallest head below `limit` at which every stream sits on a multiple of min(align, vec * elem)
-// bytes (align = 16: its vector access; align = 128: a whole line), or -1.
-int common_head(const Stream16 *st, int ns, int vec, uintptr_t align, int limit) {
-    for (int h = 0; h < limit; ++h) {
+// Three alignments a launch may start its vector accesses at, best first:
+//   kAlignWave   every stream on a multiple of what one wave takes from it per access (64 lanes x
+//                vec elements: 512 B of bf16, 1 KiB of fp32 at vec = 4), so that a wave's piece is
+//                aligned to its own size; pieces shifted by 128-384 B cost the fused step 4-5 %
+//   kAlignLine   every stream on a 128-byte line (each piece is whole lines)
+//   kAlignVector every stream aligned for its vector access only
+// Alignment repeats every `period` elements; the head is the smallest element offset that reaches it.
+enum AlignLevel { kAlignWave = 0, kAlignLine = 1, kAlignVector = 2 };
+
+int align_period(AlignLevel level, const Stream16 *st, int ns, int vec) {
+    if (level == kAlignWave) return 64 * vec;
+    if (level == kAlignVector) return vec;
+    uint32_t smallest = 4;
+    for (int i = 0; i < ns; ++i)
+        if (st[i].elem < smallest) smallest = st[i].elem;
+    return (int)(128 / smallest);
+}
+
+// Smallest head at which every stream meets `level`, or -1.
+int common_head(const Stream16 *st, int ns, int vec, AlignLevel level) {
+    const int period = align_period(level, st, ns, vec);
+    for (int h = 0; h < period; ++h) {
         bool ok = true;
         for (int i = 0; i < ns && ok; ++i) {
-            uintptr_t need = align;
-            if (align <= 16 && (uintptr_t)vec * st[i].elem < need) need = (uintptr_t)vec * st[i].elem;
+            uintptr_t need = 128;
+            if (level == kAlignWave) need = (uintptr_t)64 * vec * st[i].elem;
+            if (level == kAlignVector) need = (uintptr_t)vec * st[i].elem < 16 ? (uintptr_t)vec * st[i].elem : 16;
             ok = ((reinterpret_cast<uintptr_t>(st[i].ptr) + (uintptr_t)h * st[i].elem) & (need - 1)) == 0;
         }
         if (ok) return h;
@@ -680,18 +747,46 @@ int common_head(const Stream16 *st, int ns, int vec, uintptr_t align, int limit)
 
 Span make_span(uint64_t n, const Stream16 *st, int ns, int vec) {
     Span s{n, 0, 0, 0, 0};
-    uint32_t smallest = 4;
-    for (int i = 0; i < ns; ++i)
-        if (st[i].elem < smallest) smallest = st[i].elem;
-    int h = common_head(st, ns, vec, 128, (int)(128 / smallest));   // line-aligned pieces when the streams allow it
-    if (h < 0 || n < (uint64_t)h + vec) h = common_head(st, ns, vec, 16, vec);
-    if (h >= 0 && n >= (uint64_t)h + vec) {
+    for (int level = kAlignWave; level <= kAlignVector; ++level) {
+        const int h = common_head(st, ns, vec, (AlignLevel)level);
+        if (h < 0 || n < (uint64_t)h + vec) continue;
         s.head = (uint32_t)h;
         s.nvec = (n - (uint64_t)h) / vec;
         s.tail = (uint32_t)(n - (uint64_t)h - s.nvec * vec);
         s.vectorised = 1;
+        break;
     }
     return s;
+}
+
+// Geometry of one launch over the buckets of [0, n) whose streams start at `st`; false when the streams
+// have no common phase (then every bucket goes through the element-wise path, a launch each).
+bool make_buckets(uint64_t n, uint64_t bucket_elems, const Stream16 *st, int ns, int vec, Buckets &bk) {
+    for (int level = kAlignWave; level <= kAlignVector; ++level) {
+        const int h = common_head(st, ns, vec, (AlignLevel)level);
+        if (h < 0) continue;
+        bk = Buckets{bucket_elems, n, (uint32_t)h, (uint32_t)align_period((AlignLevel)level, st, ns, vec) - 1u,
+                     (uint32_t)(bucket_elems / ((uint64_t)kRwThreads * vec) + 1)};
+        return true;
+    }
+    return false;
+}
+
+// Calls f(off, len, U).  U == 0: one launch over the single range [off, off + len).  U > 0: one launch
+// over the buckets of U elements of [off, off + len): as many buckets as the grid limit allows.
+template <typename F>
+int for_bucket_launches(uint64_t n, uint64_t bucket_elems, F f) {
+    if (bucket_elems == 0 || bucket_elems >= n) return f((uint64_t)0, n, (uint64_t)0);
+    const uint64_t blocks_per_bucket = bucket_elems / ((uint64_t)kRwThreads * kVecRW) + 1;
+    uint64_t per_launch = kMaxGrid / blocks_per_bucket;
+    if (per_launch == 0) per_launch = 1;
+    const uint64_t step = per_launch > (~0ull) / bucket_elems ? n : per_launch * bucket_elems;
+    for (uint64_t off = 0; off < n; off += step) {
+        const uint64_t len = n - off < step ? n - off : step;
+        const int rc = f(off, len, bucket_elems);
+        if (rc != AMSP_OK) return rc;
+    }
+    return AMSP_OK;
 }
 
 // Occupancy cap of the read+write kernels.  With one-wave workgroups and only as many waves resident
@@ -783,8 +878,8 @@ uint64_t reduce_norm_blocks_max(uint64_t len) { return len / ((uint64_t)kRwThrea
 // Block sums of every bucket of a call lie side by side and are added once, after the last bucket.
 uint64_t reduce_norm_slots(uint64_t n, uint64_t bucket_elems) {
     if (bucket_elems == 0 || bucket_elems >= n) return reduce_norm_blocks_max(n);
-    const uint64_t full = n / bucket_elems, rest = n % bucket_elems;
-    return full * reduce_norm_blocks_max(bucket_elems) + (rest ? reduce_norm_blocks_max(rest) : 0);
+    const uint64_t buckets = (n + bucket_elems - 1) / bucket_elems;   // a short last bucket gets a full one's blocks
+    return buckets * reduce_norm_blocks_max(bucket_elems);
 }
 
 int cu_count() {
@@ -1065,23 +1160,48 @@ int amsp_reduce_grad_shard(const uint16_t *const *partials, uint32_t k, uint64_t
     if (grad_out == nullptr) return AMSP_ENULL;
     if (misaligned(grad_out, 4)) return AMSP_EALIGN;
     uint64_t used = 0;   // block sums written so far, bucket after bucket
-    rc = for_buckets(n, bucket_elems, [&](uint64_t off, uint64_t len) {
+    const unsigned lane_bytes = 8 * k + (accumulate ? 16 : 0);
+    auto single = [&](uint64_t off, uint64_t len) -> int {
         PartialPtrs q = offset_partials(pp, k, off);
         Stream16 st[AMSP_MAX_K + 1];
         int ns = add_partial_streams(st, 0, q, k);
         st[ns++] = Stream16{grad_out + off, 4};
         Span s = make_span(len, st, ns, kVecRW);
+        const Buckets none{};
         clear_stale_error();
-        const RwLaunch L = rw_launch(s, 8 * k + (accumulate ? 16 : 0), reduce_target());
+        const RwLaunch L = rw_launch(s, lane_bytes, reduce_target());
         if (!norm) {
             AMSP_DISPATCH_K(k, hipLaunchKernelGGL((reduce_kernel<KK, false>), L.grid, L.block, L.lds, hs, q, (int)k,
-                                                  grad_out + off, accumulate, block_sums, s));
+                                                  grad_out + off, accumulate, block_sums, s, none));
             return launched();
         }
         const uint64_t blocks = reduce_norm_grid(s);   // == L.grid.x on the vector path, capped on the other
         AMSP_DISPATCH_K(k, hipLaunchKernelGGL((reduce_kernel<KK, true>), dim3((unsigned)blocks), L.block, L.lds, hs, q,
-                                              (int)k, grad_out + off, accumulate, block_sums + used, s));
+                                              (int)k, grad_out + off, accumulate, block_sums + used, s, none));
         used += blocks;
+        return launched();
+    };
+    rc = for_bucket_launches(n, bucket_elems, [&](uint64_t off, uint64_t len, uint64_t U) -> int {
+        if (U == 0) return single(off, len);
+        PartialPtrs q = offset_partials(pp, k, off);
+        Stream16 st[AMSP_MAX_K + 1];
+        int ns = add_partial_streams(st, 0, q, k);
+        st[ns++] = Stream16{grad_out + off, 4};
+        Buckets bk;
+        if (!make_buckets(len, U, st, ns, kVecRW, bk))
+            return for_buckets(len, U, [&](uint64_t o, uint64_t l) { return single(off + o, l); });
+        const dim3 grid((unsigned)(((len + U - 1) / U) * bk.blocks_per_bucket)), block(kRwThreads);
+        const unsigned lds = occupancy_lds(lane_bytes, reduce_target());
+        const Span s{len, 0, 0, 0, 1};
+        clear_stale_error();
+        if (!norm) {
+            AMSP_DISPATCH_K(k, hipLaunchKernelGGL((reduce_kernel<KK, false>), grid, block, lds, hs, q, (int)k,
+                                                  grad_out + off, accumulate, block_sums, s, bk));
+            return launched();
+        }
+        AMSP_DISPATCH_K(k, hipLaunchKernelGGL((reduce_kernel<KK, true>), grid, block, lds, hs, q, (int)k,
+                                              grad_out + off, accumulate, block_sums + used, s, bk));
+        used += grid.x;
         return launched();
     });
     if (rc != AMSP_OK || !norm) return rc;
@@ -1152,7 +1272,9 @@ static int adamw_step_range(const uint16_t *const *partials, uint32_t k, const f
     c.d_total_sqnorm = hp->d_total_sqnorm;
     hipStream_t hs = (hipStream_t)stream;
 
-    return for_buckets(n, bucket_elems, [&](uint64_t off, uint64_t len) {
+    const unsigned lane_bytes = (k != 0 ? 8 * k : 16) + 48;
+    // one launch: a single range (U == 0, its Span worked out here) or the buckets of U elements of a range
+    auto launch = [&](uint64_t off, uint64_t len, uint64_t U) -> int {
         PartialPtrs q = offset_partials(pp, k, off);
         Stream16 st[AMSP_MAX_K + 5];
         int ns = add_partial_streams(st, 0, q, k);
@@ -1166,17 +1288,24 @@ static int adamw_step_range(const uint16_t *const *partials, uint32_t k, const f
         st[ns++] = Stream16{exp_avg_sq + off, 4};
         uint16_t *out = param_bf16_out ? param_bf16_out + off : nullptr;
         if (out) st[ns++] = Stream16{out, 2};
-        Span s = make_span(len, st, ns, kVecRW);
-        const unsigned lane_bytes = (k != 0 ? 8 * k : 16) + 48;
-        const RwLaunch L = rw_launch(s, lane_bytes, adamw_target(lane_bytes));
-        const dim3 grid = L.grid, block = L.block;
-        const unsigned lds = L.lds;
+        Span s{len, 0, 0, 0, 1};
+        Buckets bk{};
+        dim3 grid, block(kRwThreads);
+        unsigned lds = occupancy_lds(lane_bytes, adamw_target(lane_bytes));
+        if (U == 0) {
+            s = make_span(len, st, ns, kVecRW);
+            const RwLaunch L = rw_launch(s, lane_bytes, adamw_target(lane_bytes));
+            grid = L.grid; block = L.block; lds = L.lds;
+        } else {
+            if (!make_buckets(len, U, st, ns, kVecRW, bk)) return (int)AMSP_EALIGN;   // the caller falls back
+            grid = dim3((unsigned)(((len + U - 1) / U) * bk.blocks_per_bucket));
+        }
         clear_stale_error();
 #define AMSP_LAUNCH_ADAMW(KV)                                                                              \
         if (out) hipLaunchKernelGGL((adamw_kernel<KV, true>), grid, block, lds, hs, q, (int)k, gf, master + off, \
-                                    exp_avg + off, exp_avg_sq + off, out, amax_slot, c, s);                 \
+                                    exp_avg + off, exp_avg_sq + off, out, amax_slot, c, s, bk);             \
         else hipLaunchKernelGGL((adamw_kernel<KV, false>), grid, block, lds, hs, q, (int)k, gf, master + off, \
-                                exp_avg + off, exp_avg_sq + off, out, amax_slot, c, s)
+                                exp_avg + off, exp_avg_sq + off, out, amax_slot, c, s, bk)
         if (k == 0) {
             AMSP_LAUNCH_ADAMW(0);
         } else {
@@ -1184,6 +1313,13 @@ static int adamw_step_range(const uint16_t *const *partials, uint32_t k, const f
         }
 #undef AMSP_LAUNCH_ADAMW
         return launched();
+    };
+    return for_bucket_launches(n, bucket_elems, [&](uint64_t off, uint64_t len, uint64_t U) -> int {
+        if (U == 0) return launch(off, len, 0);
+        const int rc = launch(off, len, U);
+        if (rc != AMSP_EALIGN) return rc;
+        // streams without a common phase: a launch per bucket through the element-wise path
+        return for_buckets(len, U, [&](uint64_t o, uint64_t l) { return launch(off + o, l, 0); });
     });
 }
 
