@@ -35,8 +35,8 @@
  *     enqueued and the call returns without waiting; amsp_shard_range alone is synchronous.
  *   - `bucket_elems` (Section IV-C.2: gradients are synchronised in buckets of size U; here
  *     counted in elements): 0 processes [0,n) in one launch; U > 0 processes the buckets
- *     [bU, min((b+1)U, n)) in order, one launch each, as they would arrive (the read-only
- *     amsp_grad_sqnorm takes up to 32 buckets per launch, each with its own head and tail).
+ *     [bU, min((b+1)U, n)) in order, each bucket a range of its own with its own ragged head
+ *     and tail; buckets of one call may share a launch.
  *   - One launch covers at most (2^31 - 1) * 64 elements (about 5.5e11, more than fits the device);
  *     a longer range, or a longer bucket, is AMSP_EINVAL.
  *   - n == 0 is valid: AMSP_OK, nothing launched (amsp_grad_sqnorm still writes 0 when
