@@ -158,7 +158,8 @@ def main():
     if not w.inter_tensor:
         begin, end = B.amsp_shard_range(w.total_elems, w.shard_factor, w.rank)
         n = end - begin - w.drop_tail
-        launches = 1 if not w.bucket_elems else -(-n // w.bucket_elems)
+        launches = 1                       # the buckets of one call share a launch (until the grid limit)
+        buckets = 1 if not w.bucket_elems else -(-n // w.bucket_elems)
         parts = []
         for j in range(k):
             t = torch.empty(n, dtype=torch.int16, device="cuda")
@@ -183,7 +184,7 @@ def main():
         sizes, total = w.tensor_sizes, w.total_elems
         owner = B.amsp_partition_tensors(sizes, w.shard_factor)
         segs, n = B.amsp_owned_segments(sizes, owner, w.rank)
-        begin, launches = 0, len(segs)
+        begin, launches, buckets = 0, len(segs), 1
         parts = []
         for j in range(k):
             t = torch.empty(total, dtype=torch.int16, device="cuda")
@@ -262,7 +263,7 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": w.name, "elements": n, "k": k, "shard_factor": w.shard_factor, "rank": w.rank,
-                   "bucket_elems": w.bucket_elems, "launches_per_pass": launches},
+                   "bucket_elems": w.bucket_elems, "buckets": buckets, "launches_per_pass": launches},
         "roofline": {"bound": "hbm", "kernel": "adamw_kernel<k=%d,bf16 out> (amsp_adamw_step_shard)" % k,
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
