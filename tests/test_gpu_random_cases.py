@@ -40,11 +40,12 @@ EDGE_LENGTHS = (1, 2, 3, 4, 5, 63, 64, 65, 127, 128, 129, 255, 256, 257, 1023, 1
 def _case(rng: np.random.Generator, idx: int) -> dict:
     n = int(rng.choice(EDGE_LENGTHS)) if rng.random() < 0.4 else int(rng.integers(1, 40_000))
     k = int(rng.choice([1, 2, 3, 4, 5, 6, 7, 8, 9, 12, 15, 16, 17, 24, 31, 32]))
-    common = int(rng.integers(0, 70))
+    common = int(rng.integers(0, 600))                       # beyond one alignment period (256 elements)
     mixed = rng.random() < 0.2
     return dict(idx=idx, n=n, k=k,
                 shifts=[int(rng.integers(0, 9)) if mixed else common for _ in range(k + 4)],
-                bucket=int(rng.choice([0, 0, 1 if n <= 3000 else 251, 7 if n <= 20_000 else 999, 250, 1025, 4099]))
+                bucket=int(rng.choice([0, 0, 1 if n <= 3000 else 251, 7 if n <= 20_000 else 999, 250, 255, 256, 257, 513,
+                                       1025, 4099]))
                 if n > 1 else 0,
                 with_bf16=bool(rng.random() < 0.8),
                 max_norm=float(rng.choice([0.0, 1e-3, 0.05, 1e9])),
