@@ -1,0 +1,147 @@
+// Range geometry of the model-state kernels: how a launch over n elements of several streams splits
+// into an element-wise head, aligned vector accesses and an element-wise tail, for a single range and
+// for the buckets of one launch.  Plain integer arithmetic shared by the host code that sizes the
+// launches and the kernels that walk them; it compiles as ordinary C++ too, so that the indexing can be
+// checked exhaustively on a CPU.
+#pragma once
+#include <stdint.h>
+
+#if defined(__HIPCC__)
+#define AMSP_HOST_DEVICE __host__ __device__
+#else
+#define AMSP_HOST_DEVICE
+#endif
+
+namespace amsp_geom {
+
+constexpr int kWaveLanes = 64;   // one-wave workgroups: lanes per block on the vector path
+
+// A launch covers n elements: `head` leading ones up to the element at which every stream is
+// aligned (to a wave's piece when the streams allow it, else to a 128-byte line, else to its vector
+// access), nvec groups of VEC taken with vector accesses, and `tail` < VEC trailing ones.  Head and
+// tail are the "edge", done element-wise by the range's first block.  When the streams have no common
+// phase the host sets vectorised = 0 and every element goes through the element-wise loop.
+struct Span {
+    uint64_t n;
+    uint64_t nvec;
+    uint32_t head;
+    uint32_t tail;
+    uint32_t vectorised;
+};
+
+// Element index of the t-th edge element, t < head + tail.
+AMSP_HOST_DEVICE inline uint64_t edge_elem(const Span &s, uint32_t t, int vec) {
+    return t < s.head ? (uint64_t)t : (uint64_t)s.head + s.nvec * (uint64_t)vec + (t - s.head);
+}
+
+// Several buckets in one launch.  Bucket b covers [b * bucket_elems, min((b + 1) * bucket_elems, n)) and
+// is given blocks_per_bucket consecutive one-wave blocks; its own head, vector count and tail follow
+// from h0, the head of element 0, because alignment repeats every mask + 1 elements.
+// bucket_elems == 0: the launch is a single range described by a Span.
+struct Buckets {
+    uint64_t bucket_elems;
+    uint64_t n;
+    uint32_t h0;
+    uint32_t mask;
+    uint32_t blocks_per_bucket;
+};
+
+// The range block `block` works on: its Span (relative to `off`), the range's first element `off`, and
+// the block's index within the range.  With bucket_elems == 0, `s` is left as passed in.
+AMSP_HOST_DEVICE inline void block_range(const Buckets &bk, uint32_t block, int vec, Span &s, uint64_t &off,
+                                         uint32_t &local_block) {
+    off = 0;
+    local_block = block;
+    if (bk.bucket_elems != 0) {
+        const uint32_t b = block / bk.blocks_per_bucket;
+        local_block = block - b * bk.blocks_per_bucket;
+        off = (uint64_t)b * bk.bucket_elems;
+        const uint64_t left = bk.n - off;
+        const uint64_t len = left < bk.bucket_elems ? left : bk.bucket_elems;
+        const uint32_t head = (bk.h0 - (uint32_t)off) & bk.mask;
+        s.n = len;
+        s.vectorised = 1;
+        if (len < (uint64_t)head + (uint64_t)vec) {   // too short for one aligned vector: all of it is edge
+            s.head = (uint32_t)len;
+            s.nvec = 0;
+            s.tail = 0;
+        } else {
+            s.head = head;
+            s.nvec = (len - head) / (uint64_t)vec;
+            s.tail = (uint32_t)(len - head - s.nvec * (uint64_t)vec);
+        }
+    }
+}
+
+// ---------------------------------------------------------------- host side
+struct Stream {
+    const void *ptr;
+    uint32_t elem;   // bytes per element: 1, 2 or 4
+};
+
+// Three alignments a launch may start its vector accesses at, best first:
+//   kAlignWave   every stream on a multiple of what one wave takes from it per access (64 lanes x
+//                vec elements: 512 B of bf16, 1 KiB of fp32 at vec = 4), so that a wave's piece is
+//                aligned to its own size; pieces shifted by 128-384 B cost the fused step 4-5 %
+//   kAlignLine   every stream on a 128-byte line (each piece is whole lines)
+//   kAlignVector every stream aligned for its vector access only
+// Alignment repeats every `period` elements; the head is the smallest element offset that reaches it.
+enum AlignLevel { kAlignWave = 0, kAlignLine = 1, kAlignVector = 2 };
+
+inline uintptr_t align_need(AlignLevel level, uint32_t elem, int vec) {
+    if (level == kAlignWave) return (uintptr_t)kWaveLanes * vec * elem;
+    if (level == kAlignLine) return 128;
+    return (uintptr_t)vec * elem < 16 ? (uintptr_t)vec * elem : 16;
+}
+
+inline int align_period(AlignLevel level, const Stream *st, int ns, int vec) {
+    if (level == kAlignWave) return kWaveLanes * vec;
+    if (level == kAlignVector) return vec;
+    uint32_t smallest = 4;
+    for (int i = 0; i < ns; ++i)
+        if (st[i].elem < smallest) smallest = st[i].elem;
+    return (int)(128 / smallest);
+}
+
+// Smallest head at which every stream meets `level`, or -1.
+inline int common_head(const Stream *st, int ns, int vec, AlignLevel level) {
+    const int period = align_period(level, st, ns, vec);
+    for (int h = 0; h < period; ++h) {
+        bool ok = true;
+        for (int i = 0; i < ns && ok; ++i) {
+            const uintptr_t need = align_need(level, st[i].elem, vec);
+            ok = (((uintptr_t)st[i].ptr + (uintptr_t)h * st[i].elem) & (need - 1)) == 0;
+        }
+        if (ok) return h;
+    }
+    return -1;
+}
+
+inline Span make_span(uint64_t n, const Stream *st, int ns, int vec) {
+    Span s{n, 0, 0, 0, 0};
+    for (int level = kAlignWave; level <= kAlignVector; ++level) {
+        const int h = common_head(st, ns, vec, (AlignLevel)level);
+        if (h < 0 || n < (uint64_t)h + (uint64_t)vec) continue;
+        s.head = (uint32_t)h;
+        s.nvec = (n - (uint64_t)h) / (uint64_t)vec;
+        s.tail = (uint32_t)(n - (uint64_t)h - s.nvec * (uint64_t)vec);
+        s.vectorised = 1;
+        break;
+    }
+    return s;
+}
+
+// Geometry of one launch over the buckets of [0, n) whose streams start at `st`; false when the streams
+// have no common phase (then every bucket goes through the element-wise path, a launch each).
+inline bool make_buckets(uint64_t n, uint64_t bucket_elems, const Stream *st, int ns, int vec, Buckets &bk) {
+    for (int level = kAlignWave; level <= kAlignVector; ++level) {
+        const int h = common_head(st, ns, vec, (AlignLevel)level);
+        if (h < 0) continue;
+        bk = Buckets{bucket_elems, n, (uint32_t)h, (uint32_t)align_period((AlignLevel)level, st, ns, vec) - 1u,
+                     (uint32_t)(bucket_elems / ((uint64_t)kWaveLanes * vec) + 1)};
+        return true;
+    }
+    return false;
+}
+
+}  // namespace amsp_geom

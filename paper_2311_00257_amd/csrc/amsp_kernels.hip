@@ -36,6 +36,7 @@
 #include <atomic>
 
 #include "amsp.h"
+#include "amsp_geometry.h"
 
 #ifndef AMSP_NT_LOAD
 #define AMSP_NT_LOAD 1   // non-temporal hint on loads
@@ -188,64 +189,21 @@ __device__ __forceinline__ float grad1(const PartialPtrs &pp, int k, const float
     }
 }
 
-// A launch covers n elements: `head` leading ones up to the element at which every stream is
-// aligned (to a wave's piece when the streams allow it, else to a 128-byte line, else to its vector
-// access), nvec groups of VEC taken with vector accesses, and
-// `tail` < VEC trailing ones.  Head and tail are the "edge", done element-wise by block 0.  When the
-// streams have no common phase the host sets vectorised = 0 and every element goes through the
-// element-wise loop.
-struct Span {
-    uint64_t n;
-    uint64_t nvec;
-    uint32_t head;
-    uint32_t tail;
-    uint32_t vectorised;
-};
+using amsp_geom::Span;
+using amsp_geom::Buckets;
+static_assert(kRwThreads == amsp_geom::kWaveLanes, "the geometry assumes one-wave workgroups on the vector path");
 
 // Element index of the t-th edge element, t < head + tail.
 template <int VEC>
 __device__ __forceinline__ uint64_t edge_elem(const Span &s, uint32_t t) {
-    return t < s.head ? (uint64_t)t : (uint64_t)s.head + s.nvec * VEC + (t - s.head);
+    return amsp_geom::edge_elem(s, t, VEC);
 }
 
-// Several buckets in one launch (a launch per 25 M-element bucket loses ~4 % to its start and end, the
-// reduction ~10 %).  Bucket b covers [b * bucket_elems, min((b + 1) * bucket_elems, n)) and is given
-// blocks_per_bucket consecutive one-wave blocks; its own head, vector count and tail follow from h0, the
-// head of element 0, because alignment repeats every mask + 1 elements.  bucket_elems == 0: the launch
-// is the single range described by the Span argument.
-struct Buckets {
-    uint64_t bucket_elems;
-    uint64_t n;
-    uint32_t h0;
-    uint32_t mask;
-    uint32_t blocks_per_bucket;
-};
-
-// The range this block works on: its Span (relative to `off`), the range's first element `off`, and the
-// block's index within the range.
+// The range this block works on (a launch per 25 M-element bucket would also do, but buckets of one
+// call share launches; see the geometry header).
 template <int VEC>
 __device__ __forceinline__ void block_range(const Buckets &bk, Span &s, uint64_t &off, uint32_t &local_block) {
-    off = 0;
-    local_block = blockIdx.x;
-    if (bk.bucket_elems != 0) {
-        const uint32_t b = blockIdx.x / bk.blocks_per_bucket;
-        local_block = blockIdx.x - b * bk.blocks_per_bucket;
-        off = (uint64_t)b * bk.bucket_elems;
-        const uint64_t left = bk.n - off;
-        const uint64_t len = left < bk.bucket_elems ? left : bk.bucket_elems;
-        uint32_t head = (bk.h0 - (uint32_t)off) & bk.mask;
-        s.n = len;
-        s.vectorised = 1;
-        if (len < (uint64_t)head + VEC) {   // too short for one aligned vector: all of it is edge
-            s.head = (uint32_t)len;
-            s.nvec = 0;
-            s.tail = 0;
-        } else {
-            s.head = head;
-            s.nvec = (len - head) / VEC;
-            s.tail = (uint32_t)(len - head - s.nvec * VEC);
-        }
-    }
+    amsp_geom::block_range(bk, blockIdx.x, VEC, s, off, local_block);
 }
 
 // The read+write kernels are straight-line code: the grid covers the range exactly once, with
@@ -706,71 +664,9 @@ __global__ void __launch_bounds__(kThreads) cast_fp8_kernel(const float *__restr
 }
 
 // ---------------------------------------------------------------- host side
-struct Stream16 {
-    const void *ptr;
-    uint32_t elem;   // bytes per element: 2 or 4
-};
-
-// Three alignments a launch may start its vector accesses at, best first:
-//   kAlignWave   every stream on a multiple of what one wave takes from it per access (64 lanes x
-//                vec elements: 512 B of bf16, 1 KiB of fp32 at vec = 4), so that a wave's piece is
-//                aligned to its own size; pieces shifted by 128-384 B cost the fused step 4-5 %
-//   kAlignLine   every stream on a 128-byte line (each piece is whole lines)
-//   kAlignVector every stream aligned for its vector access only
-// Alignment repeats every `period` elements; the head is the smallest element offset that reaches it.
-enum AlignLevel { kAlignWave = 0, kAlignLine = 1, kAlignVector = 2 };
-
-int align_period(AlignLevel level, const Stream16 *st, int ns, int vec) {
-    if (level == kAlignWave) return 64 * vec;
-    if (level == kAlignVector) return vec;
-    uint32_t smallest = 4;
-    for (int i = 0; i < ns; ++i)
-        if (st[i].elem < smallest) smallest = st[i].elem;
-    return (int)(128 / smallest);
-}
-
-// Smallest head at which every stream meets `level`, or -1.
-int common_head(const Stream16 *st, int ns, int vec, AlignLevel level) {
-    const int period = align_period(level, st, ns, vec);
-    for (int h = 0; h < period; ++h) {
-        bool ok = true;
-        for (int i = 0; i < ns && ok; ++i) {
-            uintptr_t need = 128;
-            if (level == kAlignWave) need = (uintptr_t)64 * vec * st[i].elem;
-            if (level == kAlignVector) need = (uintptr_t)vec * st[i].elem < 16 ? (uintptr_t)vec * st[i].elem : 16;
-            ok = ((reinterpret_cast<uintptr_t>(st[i].ptr) + (uintptr_t)h * st[i].elem) & (need - 1)) == 0;
-        }
-        if (ok) return h;
-    }
-    return -1;
-}
-
-Span make_span(uint64_t n, const Stream16 *st, int ns, int vec) {
-    Span s{n, 0, 0, 0, 0};
-    for (int level = kAlignWave; level <= kAlignVector; ++level) {
-        const int h = common_head(st, ns, vec, (AlignLevel)level);
-        if (h < 0 || n < (uint64_t)h + vec) continue;
-        s.head = (uint32_t)h;
-        s.nvec = (n - (uint64_t)h) / vec;
-        s.tail = (uint32_t)(n - (uint64_t)h - s.nvec * vec);
-        s.vectorised = 1;
-        break;
-    }
-    return s;
-}
-
-// Geometry of one launch over the buckets of [0, n) whose streams start at `st`; false when the streams
-// have no common phase (then every bucket goes through the element-wise path, a launch each).
-bool make_buckets(uint64_t n, uint64_t bucket_elems, const Stream16 *st, int ns, int vec, Buckets &bk) {
-    for (int level = kAlignWave; level <= kAlignVector; ++level) {
-        const int h = common_head(st, ns, vec, (AlignLevel)level);
-        if (h < 0) continue;
-        bk = Buckets{bucket_elems, n, (uint32_t)h, (uint32_t)align_period((AlignLevel)level, st, ns, vec) - 1u,
-                     (uint32_t)(bucket_elems / ((uint64_t)kRwThreads * vec) + 1)};
-        return true;
-    }
-    return false;
-}
+typedef amsp_geom::Stream Stream16;
+using amsp_geom::make_span;
+using amsp_geom::make_buckets;
 
 // Calls f(off, len, U).  U == 0: one launch over the single range [off, off + len).  U > 0: one launch
 // over the buckets of U elements of [off, off + len): as many buckets as the grid limit allows.
