@@ -445,7 +445,9 @@ struct AdamConsts {
 };
 
 // The squared norm is fetched first (a scalar load that overlaps everything after it); the scale is
-// worked out from it later, in double, once the wave's vector loads are in flight.
+// worked out from it later, in double, once the wave's vector loads are in flight.  (Fetched through
+// the vector path with a device-coherent load instead, it costs 1-3 %: it misses the caches, and the
+// in-order return of vector loads puts its latency in front of the first partial.)
 __device__ __forceinline__ double load_sqnorm(const AdamConsts &c) {
     return (c.d_total_sqnorm != nullptr && c.max_norm > 0.0f) ? *c.d_total_sqnorm : -1.0;
 }
@@ -487,9 +489,7 @@ __device__ __forceinline__ uint32_t *amax_word(uint32_t *segment_words) {
     return segment_words + (blockIdx.x & (kAmaxSubSlots - 1)) * kAmaxStrideWords;
 }
 __device__ __forceinline__ uint32_t amax_seen(uint32_t *segment_words) {
-    return segment_words == nullptr
-               ? 0u
-               : __hip_atomic_load(amax_word(segment_words), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return __hip_atomic_load(amax_word(segment_words), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ void wave_amax_into(uint32_t m, uint32_t seen, uint32_t *segment_words) {
 #pragma unroll
@@ -506,7 +506,7 @@ __global__ void __launch_bounds__(kAmaxSubSlots) amax_fold_kernel(const uint32_t
     if (threadIdx.x == 0) d_amax[blockIdx.x] = m;
 }
 
-template <int K, bool WRITE_BF16>
+template <int K, bool WRITE_BF16, bool AMAX>
 __global__ void __launch_bounds__(kThreads) adamw_kernel(PartialPtrs pp, int k, const float *__restrict__ gf32,
                                                          float *__restrict__ master, float *__restrict__ exp_avg,
                                                          float *__restrict__ exp_avg_sq, uint16_t *__restrict__ out,
@@ -514,8 +514,9 @@ __global__ void __launch_bounds__(kThreads) adamw_kernel(PartialPtrs pp, int k, 
                                                          Buckets bk) {
     constexpr int VEC = kVecRW;
     const double sqnorm = load_sqnorm(c);
-    const uint32_t seen = amax_seen(amax);
-    uint32_t biggest = 0;   // of |p'| over this lane's elements, when amax != nullptr
+    uint32_t seen = 0;
+    if constexpr (AMAX) seen = amax_seen(amax);
+    uint32_t biggest = 0;   // of |p'| over this lane's elements, with AMAX
     if (s.vectorised) {
         uint64_t off;
         uint32_t lb;
@@ -536,7 +537,7 @@ __global__ void __launch_bounds__(kThreads) adamw_kernel(PartialPtrs pp, int k, 
             st_f32<VEC>(exp_avg, e, m);
             st_f32<VEC>(exp_avg_sq, e, v);
             if constexpr (WRITE_BF16) st_bf16<VEC>(out, e, p);
-            if (amax != nullptr) {
+            if constexpr (AMAX) {
 #pragma unroll
                 for (int q = 0; q < VEC; ++q) biggest = max(biggest, abs_bits(p[q]));
             }
@@ -567,7 +568,7 @@ __global__ void __launch_bounds__(kThreads) adamw_kernel(PartialPtrs pp, int k, 
             biggest = max(biggest, abs_bits(p));
         }
     }
-    if (amax != nullptr) wave_amax_into(biggest, seen, amax);   // uniform branch: every lane of the wave arrives
+    if constexpr (AMAX) wave_amax_into(biggest, seen, amax);
 }
 
 // ---------------------------------------------------------------- FP8 (E4M3) payload
@@ -1197,17 +1198,22 @@ static int adamw_step_range(const uint16_t *const *partials, uint32_t k, const f
             grid = dim3((unsigned)(((len + U - 1) / U) * bk.blocks_per_bucket));
         }
         clear_stale_error();
+#define AMSP_LAUNCH_ADAMW_ONE(KV, B16, AM)                                                                  \
+        hipLaunchKernelGGL((adamw_kernel<KV, B16, AM>), grid, block, lds, hs, q, (int)k, gf, master + off,       \
+                           exp_avg + off, exp_avg_sq + off, out, amax_slot, c, s, bk)
+#define AMSP_LAUNCH_ADAMW_AS(KV, b16, am)                                                                   \
+        if (b16) { if (am) AMSP_LAUNCH_ADAMW_ONE(KV, true, true); else AMSP_LAUNCH_ADAMW_ONE(KV, true, false); } \
+        else { if (am) AMSP_LAUNCH_ADAMW_ONE(KV, false, true); else AMSP_LAUNCH_ADAMW_ONE(KV, false, false); }
 #define AMSP_LAUNCH_ADAMW(KV)                                                                              \
-        if (out) hipLaunchKernelGGL((adamw_kernel<KV, true>), grid, block, lds, hs, q, (int)k, gf, master + off, \
-                                    exp_avg + off, exp_avg_sq + off, out, amax_slot, c, s, bk);             \
-        else hipLaunchKernelGGL((adamw_kernel<KV, false>), grid, block, lds, hs, q, (int)k, gf, master + off, \
-                                exp_avg + off, exp_avg_sq + off, out, amax_slot, c, s, bk)
+        AMSP_LAUNCH_ADAMW_AS(KV, (out != nullptr), (amax_slot != nullptr))
         if (k == 0) {
             AMSP_LAUNCH_ADAMW(0);
         } else {
             AMSP_DISPATCH_K(k, AMSP_LAUNCH_ADAMW(KK));
         }
 #undef AMSP_LAUNCH_ADAMW
+#undef AMSP_LAUNCH_ADAMW_AS
+#undef AMSP_LAUNCH_ADAMW_ONE
         return launched();
     };
     return for_bucket_launches(n, bucket_elems, [&](uint64_t off, uint64_t len, uint64_t U) -> int {
