@@ -524,3 +524,47 @@ def test_fp8_payload_of_inter_tensor_shard(B, torch_mod):
     assert a[0] == 0.0 and np.isnan(a[1]) and d_scale.cpu().numpy().tolist() == [1.0, 1.0]
     codes, _, _ = oracle.fp8_payload_segments(t, segs)
     assert np.array_equal(out.cpu().numpy(), codes)
+
+
+# ------------------------------------------------------------------ non-finite gradients propagate
+@pytest.mark.parametrize("poison", ["inf", "nan", "overflow"])
+def test_non_finite_gradients_propagate_like_the_oracle(B, torch_mod, poison):
+    """No skip-step logic: an Inf or NaN among the partial gradients goes where IEEE arithmetic takes
+    it, on both sides alike.  Inf makes the norm Inf and the scale 0 (0 * Inf = NaN at that element,
+    a pure decay step everywhere else); NaN makes the norm NaN, which switches clipping off (scale 1);
+    two finite partials whose fp32 sum overflows make that element's gradient Inf."""
+    w = workloads.get(0)
+    n, k = 10_007, 3
+    inp = H.host_inputs(w, 12345, n, k=k)
+    at = 4321
+    if poison == "inf":
+        inp.partials[1][at] = 0x7F80                         # +Inf in bf16
+    elif poison == "nan":
+        inp.partials[2][at] = 0x7FC1
+    else:
+        inp.partials[0][at] = 0x7F7F                         # largest finite bf16, twice: the sum overflows fp32
+        inp.partials[1][at] = 0x7F7F
+    hp = H.hparams_of(w, max_norm=0.05)
+    with np.errstate(all="ignore"):
+        ref = _oracle_step(inp, hp)
+    p, m, v, bits, S = _run_step(B, torch_mod, w, inp, n, hp)
+    if poison == "nan":
+        assert np.isnan(S) and np.isnan(ref["sqnorm"]) and ref["scale"] == 1.0
+    elif poison == "inf":
+        assert np.isinf(S) and np.isinf(ref["sqnorm"]) and ref["scale"] == 0.0
+    else:
+        # the oracle's exact double sum stays finite where the library's fp32 sum is +Inf: the one place the two
+        # differ by construction; the library's value is the fp32 one the step is defined on
+        assert np.isinf(S) and np.isfinite(ref["sqnorm"])
+        inp2 = H.HostInputs([q.copy() for q in inp.partials], inp.p, inp.m, inp.v)
+        inp2.partials[1][at] = 0x7F80                        # same fp32 gradient, now Inf on both sides
+        with np.errstate(all="ignore"):
+            ref = _oracle_step(inp2, hp)
+    good = np.ones(n, dtype=bool)
+    good[at] = False
+    assert np.isnan(p[at]) and np.isnan(m[at]) and np.isnan(v[at]) and np.isnan(ref["p"][at])
+    assert (bits[at] & 0x7FFF) > 0x7F80                      # the shipped bf16 is a NaN too
+    assert np.all(np.isfinite(p[good])) and np.all(np.isfinite(m[good])) and np.all(np.isfinite(v[good]))
+    sub = {key: (val[good] if isinstance(val, np.ndarray) else val) for key, val in ref.items()}
+    H.check_state(p[good], m[good], v[good], sub, inp.p[good], inp.m[good], hp)
+    H.check_bf16(bits[good], sub, inp.p[good])
