@@ -185,6 +185,7 @@ def main():
         owner = B.amsp_partition_tensors(sizes, w.shard_factor)
         segs, n = B.amsp_owned_segments(sizes, owner, w.rank)
         begin, launches, buckets = 0, len(segs), 1
+        seg_tuples, segs = segs, B.marshal_segments(segs)      # the C array, built once
         parts = []
         for j in range(k):
             t = torch.empty(total, dtype=torch.int16, device="cuda")
@@ -193,7 +194,7 @@ def main():
         master = torch.empty(n, dtype=torch.float32, device="cuda")
         exp_avg = torch.empty(n, dtype=torch.float32, device="cuda")
         exp_avg_sq = torch.empty(n, dtype=torch.float32, device="cuda")
-        for f, l, m in segs:
+        for f, l, m in seg_tuples:
             synth_device.fill_f32(master[l:l + m], w.key(synth.TENSOR_MASTER), f, w.sigma_param)
             synth_device.fill_f32(exp_avg[l:l + m], w.key(synth.TENSOR_EXP_AVG), f, w.sigma_m)
             synth_device.fill_f32(exp_avg_sq[l:l + m], w.key(synth.TENSOR_EXP_AVG_SQ), f, w.scale_v, absolute=True)

@@ -206,9 +206,10 @@ int amsp_owned_segments(const uint64_t *tensor_elems, const uint32_t *owner, uin
                         uint32_t *num_segments, uint64_t *local_elems);
 
 /*
- * Steps 2 and 1+3+4 over a segment list: as amsp_grad_sqnorm / amsp_adamw_step_shard, the update one
- * launch per segment in list order, the norm up to 32 segments per launch ("select": only owned
- * elements are read; "drop": nothing else is touched).
+ * Steps 2 and 1+3+4 over a segment list: as amsp_grad_sqnorm / amsp_adamw_step_shard ("select":
+ * only owned elements are read; "drop": nothing else is touched).  Long segments get a launch of
+ * their own; segments shorter than 2^20 elements share launches, 32 to a launch, and so do the
+ * segments of the norm pass: a shard of thousands of small tensors is not bound by launches.
  *   partials_flat    host array of k device pointers, each bf16[flat_elems] (flat whole-model
  *                    gradient buffers: one all-reduced buffer, k = 1, or k partial ones)
  *   segments         host array [num_segments]; each must lie inside [0, flat_elems) and

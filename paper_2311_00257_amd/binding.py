@@ -221,9 +221,26 @@ def _hp_struct(hp: AdamWHparams):
                     _ptr(hp.d_total_sqnorm), hp.grad_scale)
 
 
+class SegmentArray:
+    """A segment list already laid out as the C array the entry points take: build it once with
+    ``marshal_segments`` and pass it wherever a list of (flat_offset, local_offset, length) goes, so
+    that a long list is not converted again on every call."""
+
+    def __init__(self, segments):
+        self.n = len(segments)
+        self.arr = (_Segment * max(self.n, 1))(*[_Segment(*map(int, s)) for s in segments])
+
+    def __len__(self):
+        return self.n
+
+
+def marshal_segments(segments) -> SegmentArray:
+    return segments if isinstance(segments, SegmentArray) else SegmentArray(segments)
+
+
 def _segments(segments):
-    arr = (_Segment * max(len(segments), 1))(*[_Segment(*map(int, s)) for s in segments])
-    return arr, len(segments)
+    a = marshal_segments(segments)
+    return a.arr, a.n
 
 
 def amsp_partition_tensors(tensor_elems: Sequence[int], shard_factor: int):

@@ -103,18 +103,27 @@ inline int align_period(AlignLevel level, const Stream *st, int ns, int vec) {
     return (int)(128 / smallest);
 }
 
-// Smallest head at which every stream meets `level`, or -1.
+// Smallest head at which every stream meets `level`, or -1.  Every stream's alignment repeats with a
+// power-of-two period (in elements) that divides the longest one, so the only candidate below the
+// longest period is the head of the stream that has it; the others either agree with it or no head exists.
 inline int common_head(const Stream *st, int ns, int vec, AlignLevel level) {
-    const int period = align_period(level, st, ns, vec);
-    for (int h = 0; h < period; ++h) {
-        bool ok = true;
-        for (int i = 0; i < ns && ok; ++i) {
-            const uintptr_t need = align_need(level, st[i].elem, vec);
-            ok = (((uintptr_t)st[i].ptr + (uintptr_t)h * st[i].elem) & (need - 1)) == 0;
+    if (ns <= 0) return 0;
+    int widest = 0;
+    uintptr_t widest_period = 0;
+    for (int i = 0; i < ns; ++i) {
+        const uintptr_t period = align_need(level, st[i].elem, vec) / st[i].elem;
+        if (period > widest_period) {
+            widest_period = period;
+            widest = i;
         }
-        if (ok) return h;
     }
-    return -1;
+    const uintptr_t need = align_need(level, st[widest].elem, vec);
+    const uintptr_t past = (uintptr_t)st[widest].ptr & (need - 1);   // bytes past the last aligned address
+    if (past % st[widest].elem != 0) return -1;                      // not even element-aligned
+    const uintptr_t h = ((need - past) & (need - 1)) / st[widest].elem;
+    for (int i = 0; i < ns; ++i)
+        if ((((uintptr_t)st[i].ptr + h * st[i].elem) & (align_need(level, st[i].elem, vec) - 1)) != 0) return -1;
+    return (int)h;
 }
 
 inline Span make_span(uint64_t n, const Stream *st, int ns, int vec) {

@@ -409,6 +409,54 @@ __global__ void __launch_bounds__(kNormThreads) sqnorm_kernel(PartialPtrs pp, in
     if (threadIdx.x == 0) block_sums[blockIdx.x] = total;
 }
 
+// Short ranges (norm gains, biases, small buckets): in the kernel above every block walks every
+// range, so a range shorter than the grid leaves most blocks idle while the few that have work go
+// through the ranges one memory round trip after the other.  Here each range gets blocks of its own,
+// one vector per lane (a grid-stride loop on the element-wise path), and a block finds its range with
+// 31 scalar compares against the table in the kernel arguments.  Run-time k: short ranges hold a
+// sliver of the bytes.
+struct ShortNormTable {
+    uint32_t first_block[kMaxNormSegs];   // unused entries: 0xFFFFFFFF
+    uint32_t blocks[kMaxNormSegs];
+    NormSeg seg[kMaxNormSegs];
+};
+
+template <int K, int VEC>
+__global__ void __launch_bounds__(kNormThreads) sqnorm_short_kernel(PartialPtrs pp, int k,
+                                                                    const float *__restrict__ gf32,
+                                                                    double *__restrict__ block_sums,
+                                                                    ShortNormTable t) {
+    uint32_t r = 0;
+#pragma unroll
+    for (int i = 1; i < kMaxNormSegs; ++i) r += blockIdx.x >= t.first_block[i] ? 1u : 0u;
+    const uint32_t lb = blockIdx.x - t.first_block[r];
+    const Span s = t.seg[r].s;
+    const uint64_t base = t.seg[r].base;
+    double acc = 0.0;
+    if (s.vectorised) {
+        const uint64_t v = (uint64_t)lb * kNormThreads + threadIdx.x;
+        if (v < s.nvec) {
+            float g[VEC];
+            grad_vec<K, VEC>(pp, k, gf32, base + s.head + v * VEC, g);
+#pragma unroll
+            for (int c = 0; c < VEC; ++c) acc = fma((double)g[c], (double)g[c], acc);
+        }
+        if (lb == 0)
+            for (uint32_t e = threadIdx.x; e < s.head + s.tail; e += kNormThreads) {
+                const double g = (double)grad1<K>(pp, k, gf32, base + edge_elem<VEC>(s, e));
+                acc = fma(g, g, acc);
+            }
+    } else {
+        const uint64_t stride = (uint64_t)t.blocks[r] * kNormThreads;
+        for (uint64_t i = (uint64_t)lb * kNormThreads + threadIdx.x; i < s.n; i += stride) {
+            const double g = (double)grad1<K>(pp, k, gf32, base + i);
+            acc = fma(g, g, acc);
+        }
+    }
+    const double total = block_sum<kNormThreads>(acc);
+    if (threadIdx.x == 0) block_sums[blockIdx.x] = total;
+}
+
 // Adds nblocks block sums in a fixed order (lane-strided, then a tree) and stores or adds the total.
 __global__ void __launch_bounds__(kThreads) sqnorm_finish_kernel(const double *__restrict__ block_sums, int nblocks,
                                                                  double *__restrict__ out, int accumulate) {
@@ -569,6 +617,83 @@ __global__ void __launch_bounds__(kThreads) adamw_kernel(PartialPtrs pp, int k, 
         }
     }
     if constexpr (AMAX) wave_amax_into(biggest, seen, amax);
+}
+
+// Many short ranges in one launch: the segments of an inter-tensor shard that are too short to be
+// worth a launch each (norm gains, biases).  Range r owns the blocks [first_block[r], first_block[r+1])
+// and has its own head; its gradient and bf16 output sit at flat_off[r] of the flat buffers, its
+// optimizer states at local_off[r] of the compact ones.  The table travels in the kernel arguments, so a
+// block finds its range with 31 scalar compares and no memory access of its own.  Run-time k only:
+// these ranges hold a sliver of the model's bytes.
+constexpr int kMaxTableRanges = 32;
+constexpr uint64_t kShortSegment = 1ull << 20;   // elements: ~5 us of traffic, about what a launch costs
+struct RangeTable {
+    uint32_t first_block[kMaxTableRanges];   // unused entries: 0xFFFFFFFF
+    uint32_t head[kMaxTableRanges];          // elements before the first aligned vector; == len: no vector at all
+    uint32_t segment[kMaxTableRanges];       // index in the caller's segment list (for the maxima words)
+    uint64_t flat_off[kMaxTableRanges];
+    uint64_t local_off[kMaxTableRanges];
+    uint64_t len[kMaxTableRanges];
+};
+
+template <bool WRITE_BF16, bool AMAX>
+__global__ void __launch_bounds__(kRwThreads) adamw_table_kernel(PartialPtrs pp, int k, float *__restrict__ master,
+                                                                 float *__restrict__ exp_avg,
+                                                                 float *__restrict__ exp_avg_sq,
+                                                                 uint16_t *__restrict__ out,
+                                                                 uint32_t *__restrict__ amax_words, AdamConsts c,
+                                                                 RangeTable t) {
+    constexpr int VEC = kVecRW;
+    const double sqnorm = load_sqnorm(c);
+    uint32_t r = 0;
+#pragma unroll
+    for (int i = 1; i < kMaxTableRanges; ++i) r += blockIdx.x >= t.first_block[i] ? 1u : 0u;
+    const uint32_t lb = blockIdx.x - t.first_block[r];
+    const uint64_t len = t.len[r], flat = t.flat_off[r], local = t.local_off[r];
+    const uint32_t head = t.head[r];
+    uint32_t *words = nullptr;
+    uint32_t seen = 0;
+    if constexpr (AMAX) {
+        words = amax_words + (size_t)t.segment[r] * kAmaxWordsPerSegment;
+        seen = amax_seen(words);
+    }
+    const uint64_t nvec = (len - head) / VEC;
+    const uint32_t tail = (uint32_t)(len - head - nvec * VEC);
+    uint32_t biggest = 0;
+    const uint64_t vi = (uint64_t)lb * kRwThreads + threadIdx.x;
+    if (vi < nvec) {
+        const uint64_t i = head + vi * VEC;
+        float g[VEC], p[VEC], m[VEC], v[VEC];
+        ld_f32<VEC>(master, local + i, p);
+        ld_f32<VEC>(exp_avg, local + i, m);
+        ld_f32<VEC>(exp_avg_sq, local + i, v);
+        grad_vec<-1, VEC>(pp, k, nullptr, flat + i, g);
+        const float scale = clip_scale(c, sqnorm);
+#pragma unroll
+        for (int q = 0; q < VEC; ++q) adamw1(c, scale, g[q], p[q], m[q], v[q]);
+        st_f32<VEC>(master, local + i, p);
+        st_f32<VEC>(exp_avg, local + i, m);
+        st_f32<VEC>(exp_avg_sq, local + i, v);
+        if constexpr (WRITE_BF16) st_bf16<VEC>(out, flat + i, p);
+        if constexpr (AMAX) {
+#pragma unroll
+            for (int q = 0; q < VEC; ++q) biggest = max(biggest, abs_bits(p[q]));
+        }
+    }
+    if (lb == 0) {
+        const float scale = clip_scale(c, sqnorm);
+        for (uint32_t e = threadIdx.x; e < head + tail; e += kRwThreads) {
+            const uint64_t i = e < head ? (uint64_t)e : (uint64_t)head + nvec * VEC + (e - head);
+            float p = master[local + i], m = exp_avg[local + i], v = exp_avg_sq[local + i];
+            adamw1(c, scale, grad1<-1>(pp, k, nullptr, flat + i), p, m, v);
+            master[local + i] = p;
+            exp_avg[local + i] = m;
+            exp_avg_sq[local + i] = v;
+            if constexpr (WRITE_BF16) out[flat + i] = (uint16_t)f32_to_bf16(p);
+            biggest = max(biggest, abs_bits(p));
+        }
+    }
+    if constexpr (AMAX) wave_amax_into(biggest, seen, words);
 }
 
 // ---------------------------------------------------------------- FP8 (E4M3) payload
@@ -962,25 +1087,83 @@ int norm_launch(NormBatch &batch, const PartialPtrs &pp, uint32_t k, const float
     return launched();
 }
 
-// Norm launches over a list of ranges, kMaxNormSegs per launch, in list order.
+// One launch of the short-range kernel over up to kMaxNormSegs ranges.
+int norm_launch_short(NormBatch &batch, const PartialPtrs &pp, uint32_t k, const float *gf, const uint64_t *base,
+                      const uint64_t *len, int count) {
+    const int vec = k == 0 ? 4 : kVecNorm;
+    ShortNormTable t;
+    uint32_t blocks_total = 0;
+    for (int i = 0; i < kMaxNormSegs; ++i) {
+        if (i >= count) {
+            t.first_block[i] = 0xFFFFFFFFu;
+            t.blocks[i] = 0;
+            t.seg[i] = NormSeg{0, Span{0, 0, 0, 0, 0}};
+            continue;
+        }
+        Stream16 st[AMSP_MAX_K + 1];
+        int ns = add_partial_streams(st, 0, offset_partials(pp, k, base[i]), k);
+        if (k == 0) st[ns++] = Stream16{gf + base[i], 4};
+        t.seg[i].base = base[i];
+        t.seg[i].s = make_span(len[i], st, ns, vec);
+        uint64_t blocks = t.seg[i].s.vectorised ? (t.seg[i].s.nvec + kNormThreads - 1) / kNormThreads
+                                                : (len[i] + kNormThreads - 1) / kNormThreads;
+        if (!t.seg[i].s.vectorised && blocks > 64) blocks = 64;
+        if (blocks == 0) blocks = 1;
+        t.first_block[i] = blocks_total;
+        t.blocks[i] = (uint32_t)blocks;
+        blocks_total += (uint32_t)blocks;
+    }
+    double *block_sums = nullptr;
+    int rc = batch.reserve((int)blocks_total, &block_sums);
+    if (rc != AMSP_OK) return rc;
+    hipStream_t hs = batch.hs;
+    if (k == 0)
+        hipLaunchKernelGGL((sqnorm_short_kernel<0, 4>), dim3(blocks_total), dim3(kNormThreads), 0, hs, pp, (int)k, gf,
+                           block_sums, t);
+    else
+        hipLaunchKernelGGL((sqnorm_short_kernel<-1, kVecNorm>), dim3(blocks_total), dim3(kNormThreads), 0, hs, pp,
+                           (int)k, gf, block_sums, t);
+    return launched();
+}
+
+// Norm launches over a list of ranges, kMaxNormSegs per launch: ranges long enough to keep the whole
+// persistent grid busy (a few vectors per lane) go to the grid-stride kernel, the others to the
+// short-range kernel.
+constexpr uint64_t kShortNormRange = 4ull << 20;   // elements; 4 Mi elements = one 16-byte vector per resident lane
 struct NormRanges {
     NormBatch &batch;
     const PartialPtrs &pp;
     uint32_t k;
     const float *gf;
     uint64_t base[kMaxNormSegs], len[kMaxNormSegs];
-    int count = 0;
+    uint64_t short_base[kMaxNormSegs], short_len[kMaxNormSegs];
+    int count = 0, short_count = 0;
 
-    int flush() {
+    int flush_long() {
         if (count == 0) return AMSP_OK;
         const int rc = norm_launch(batch, pp, k, gf, base, len, count);
         count = 0;
         return rc;
     }
+    int flush_short() {
+        if (short_count == 0) return AMSP_OK;
+        const int rc = norm_launch_short(batch, pp, k, gf, short_base, short_len, short_count);
+        short_count = 0;
+        return rc;
+    }
+    int flush() {
+        const int rc = flush_long();
+        return rc != AMSP_OK ? rc : flush_short();
+    }
     int add(uint64_t b, uint64_t l) {
+        if (l < kShortNormRange) {
+            short_base[short_count] = b;
+            short_len[short_count] = l;
+            return ++short_count == kMaxNormSegs ? flush_short() : AMSP_OK;
+        }
         base[count] = b;
         len[count] = l;
-        return ++count == kMaxNormSegs ? flush() : AMSP_OK;
+        return ++count == kMaxNormSegs ? flush_long() : AMSP_OK;
     }
 };
 
@@ -1133,6 +1316,26 @@ int amsp_grad_sqnorm(const uint16_t *const *partials, uint32_t k, const float *g
     return batch.flush();
 }
 
+// Hyper-parameters checked and turned into the constants the kernels use (bias corrections in double).
+static int adam_consts(const amsp_adamw_hparams *hp, AdamConsts &c) {
+    if (hp == nullptr) return AMSP_ENULL;
+    const bool finite = isfinite(hp->lr) && isfinite(hp->beta1) && isfinite(hp->beta2) && isfinite(hp->eps) &&
+                        isfinite(hp->weight_decay) && isfinite(hp->grad_scale) && isfinite(hp->clip_eps) &&
+                        !isnan(hp->max_norm);
+    if (!finite || hp->step == 0 || !(hp->beta1 >= 0.0f && hp->beta1 < 1.0f) ||
+        !(hp->beta2 >= 0.0f && hp->beta2 < 1.0f) || hp->eps < 0.0f)
+        return AMSP_EINVAL;
+    if (hp->d_total_sqnorm && misaligned(hp->d_total_sqnorm, 8)) return AMSP_EALIGN;
+    c.lr = hp->lr; c.beta1 = hp->beta1; c.beta2 = hp->beta2; c.eps = hp->eps; c.wd = hp->weight_decay;
+    c.one_minus_beta1 = (float)(1.0 - (double)hp->beta1);
+    c.one_minus_beta2 = (float)(1.0 - (double)hp->beta2);
+    c.rbc1 = (float)(1.0 / (1.0 - pow((double)hp->beta1, (double)hp->step)));
+    c.rbc2 = (float)(1.0 / (1.0 - pow((double)hp->beta2, (double)hp->step)));
+    c.max_norm = hp->max_norm; c.clip_eps = hp->clip_eps; c.grad_scale = hp->grad_scale;
+    c.d_total_sqnorm = hp->d_total_sqnorm;
+    return AMSP_OK;
+}
+
 // amax_slot: the range's kAmaxWordsPerSegment device words that collect the largest |p'| bit pattern, or NULL.
 static int adamw_step_range(const uint16_t *const *partials, uint32_t k, const float *grad_f32, uint64_t n,
                             uint64_t bucket_elems, float *master, float *exp_avg, float *exp_avg_sq,
@@ -1144,12 +1347,11 @@ static int adamw_step_range(const uint16_t *const *partials, uint32_t k, const f
         int rc = check_partials(partials, k, pp);
         if (rc != AMSP_OK) return rc;
     }
-    const bool finite = isfinite(hp->lr) && isfinite(hp->beta1) && isfinite(hp->beta2) && isfinite(hp->eps) &&
-                        isfinite(hp->weight_decay) && isfinite(hp->grad_scale) && isfinite(hp->clip_eps) &&
-                        !isnan(hp->max_norm);
-    if (!finite || hp->step == 0 || !(hp->beta1 >= 0.0f && hp->beta1 < 1.0f) ||
-        !(hp->beta2 >= 0.0f && hp->beta2 < 1.0f) || hp->eps < 0.0f)
-        return AMSP_EINVAL;
+    AdamConsts c;
+    {
+        const int rc = adam_consts(hp, c);
+        if (rc != AMSP_OK) return rc;
+    }
     if (n == 0) return AMSP_OK;
     if (too_long(n, bucket_elems)) return AMSP_EINVAL;
     if (master == nullptr || exp_avg == nullptr || exp_avg_sq == nullptr) return AMSP_ENULL;
@@ -1159,14 +1361,6 @@ static int adamw_step_range(const uint16_t *const *partials, uint32_t k, const f
         (hp->d_total_sqnorm && misaligned(hp->d_total_sqnorm, 8)))
         return AMSP_EALIGN;
 
-    AdamConsts c;
-    c.lr = hp->lr; c.beta1 = hp->beta1; c.beta2 = hp->beta2; c.eps = hp->eps; c.wd = hp->weight_decay;
-    c.one_minus_beta1 = (float)(1.0 - (double)hp->beta1);
-    c.one_minus_beta2 = (float)(1.0 - (double)hp->beta2);
-    c.rbc1 = (float)(1.0 / (1.0 - pow((double)hp->beta1, (double)hp->step)));
-    c.rbc2 = (float)(1.0 / (1.0 - pow((double)hp->beta2, (double)hp->step)));
-    c.max_norm = hp->max_norm; c.clip_eps = hp->clip_eps; c.grad_scale = hp->grad_scale;
-    c.d_total_sqnorm = hp->d_total_sqnorm;
     hipStream_t hs = (hipStream_t)stream;
 
     const unsigned lane_bytes = (k != 0 ? 8 * k : 16) + 48;
@@ -1353,16 +1547,73 @@ int amsp_adamw_step_segments(const uint16_t *const *partials_flat, uint32_t k, u
                            (uint32_t)count, 0u);
         if (launched() != AMSP_OK) return AMSP_EDEVICE;
     }
+    // Segments shorter than kShortSegment share launches, up to kMaxTableRanges each (a launch costs more
+    // than such a segment's traffic); the others get a launch of their own with every k loaded at once.
+    AdamConsts c;
+    rc = adam_consts(hp, c);
+    if (rc != AMSP_OK) return rc;
+    if (misaligned(master_local, 4) || misaligned(exp_avg_local, 4) || misaligned(exp_avg_sq_local, 4) ||
+        (param_bf16_flat && misaligned(param_bf16_flat, 2)))
+        return AMSP_EALIGN;
+    RangeTable table;
+    uint32_t in_table = 0, table_blocks = 0;
+    auto flush_table = [&]() -> int {
+        if (in_table == 0) return AMSP_OK;
+        for (uint32_t j = in_table; j < (uint32_t)kMaxTableRanges; ++j) {
+            table.first_block[j] = 0xFFFFFFFFu;
+            table.head[j] = 0; table.segment[j] = 0; table.flat_off[j] = 0; table.local_off[j] = 0; table.len[j] = 0;
+        }
+        const unsigned lane_bytes = 8 * k + 48;
+        const unsigned lds = occupancy_lds(lane_bytes, adamw_target(lane_bytes));
+        const dim3 grid(table_blocks), block(kRwThreads);
+        clear_stale_error();
+#define AMSP_LAUNCH_TABLE(B16, AM)                                                                              \
+        hipLaunchKernelGGL((adamw_table_kernel<B16, AM>), grid, block, lds, hs, pp, (int)k, master_local,      \
+                           exp_avg_local, exp_avg_sq_local, param_bf16_flat, words, c, table)
+        if (param_bf16_flat) { if (words) AMSP_LAUNCH_TABLE(true, true); else AMSP_LAUNCH_TABLE(true, false); }
+        else { if (words) AMSP_LAUNCH_TABLE(false, true); else AMSP_LAUNCH_TABLE(false, false); }
+#undef AMSP_LAUNCH_TABLE
+        in_table = 0;
+        table_blocks = 0;
+        return launched();
+    };
     for (uint32_t i = 0; i < num_segments; ++i) {
         const amsp_segment &g = segments[i];
         if (g.length == 0) continue;
         PartialPtrs q = offset_partials(pp, k, g.flat_offset);
+        if (g.length < kShortSegment) {
+            Stream16 st[AMSP_MAX_K + 4];
+            int ns = add_partial_streams(st, 0, q, k);
+            st[ns++] = Stream16{master_local + g.local_offset, 4};
+            st[ns++] = Stream16{exp_avg_local + g.local_offset, 4};
+            st[ns++] = Stream16{exp_avg_sq_local + g.local_offset, 4};
+            if (param_bf16_flat) st[ns++] = Stream16{param_bf16_flat + g.flat_offset, 2};
+            const Span sp = make_span(g.length, st, ns, kVecRW);
+            // no common phase: still fine for the table when the edge loop of one wave can take it all
+            if (sp.vectorised || g.length <= 16 * kRwThreads) {
+                table.first_block[in_table] = table_blocks;
+                table.head[in_table] = sp.vectorised ? sp.head : (uint32_t)g.length;
+                table.segment[in_table] = i;
+                table.flat_off[in_table] = g.flat_offset;
+                table.local_off[in_table] = g.local_offset;
+                table.len[in_table] = g.length;
+                const uint64_t blocks = sp.vectorised ? (sp.nvec + kRwThreads - 1) / kRwThreads : 0;
+                table_blocks += (uint32_t)(blocks ? blocks : 1);
+                if (++in_table == (uint32_t)kMaxTableRanges) {
+                    rc = flush_table();
+                    if (rc != AMSP_OK) return rc;
+                }
+                continue;
+            }
+        }
         rc = adamw_step_range(q.p, k, nullptr, g.length, 0, master_local + g.local_offset,
                               exp_avg_local + g.local_offset, exp_avg_sq_local + g.local_offset,
                               param_bf16_flat ? param_bf16_flat + g.flat_offset : nullptr,
                               words ? words + (size_t)i * kAmaxWordsPerSegment : nullptr, hp, stream);
         if (rc != AMSP_OK) return rc;
     }
+    rc = flush_table();
+    if (rc != AMSP_OK) return rc;
     if (words != nullptr) {
         clear_stale_error();
         hipLaunchKernelGGL(amax_fold_kernel, dim3(num_segments), dim3(kAmaxSubSlots), 0, hs, words,

@@ -144,11 +144,12 @@ int main() {
         c.n = below(3) == 0 ? lengths[below(sizeof lengths / sizeof *lengths)] : 1 + below(6000);
         c.bucket = c.vec == 8 ? 0 : buckets[below(sizeof buckets / sizeof *buckets)];
         const int ns = 1 + (int)below(6);
-        const bool mixed = below(5) == 0;
+        const int mode = (int)below(5);   // 0: unrelated small shifts; 1: a common shift plus whole lines; else: a common shift
         const uint64_t common = below(700);
         for (int i = 0; i < ns; ++i) {
             const uint32_t elem = c.vec == 8 ? 2u : (below(8) == 0 ? 1u : (below(2) ? 2u : 4u));
-            const uint64_t shift = mixed ? below(9) : common;
+            // mode 1 leaves the streams line-aligned together but (mostly) not aligned to a wave's piece together
+            const uint64_t shift = mode == 0 ? below(9) : (mode == 1 ? common + below(4) * (128 / elem) : common);
             const uintptr_t base = (uintptr_t)((1 + below(1000)) << 21);   // 2 MiB-aligned allocations
             c.st.push_back(Stream{(const void *)(base + shift * elem), elem});
         }
