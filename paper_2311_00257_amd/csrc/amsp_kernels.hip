@@ -789,6 +789,60 @@ __global__ void __launch_bounds__(kThreads) cast_fp8_kernel(const float *__restr
     }
 }
 
+// The FP8 payload of short segments, 32 to a launch like the update above.  CAST = false: the largest
+// |x| of each range into slots[segment] (integer atomic max, sent only when it beats the word's current
+// value); CAST = true: codes = e4m3(x * d_scale[segment]) at the range's flat position.
+template <bool CAST>
+__global__ void __launch_bounds__(kRwThreads) fp8_table_kernel(const float *__restrict__ master,
+                                                               const float *__restrict__ d_scale,
+                                                               uint8_t *__restrict__ out, uint32_t *__restrict__ slots,
+                                                               RangeTable t) {
+    constexpr int VEC = 4;
+    uint32_t r = 0;
+#pragma unroll
+    for (int i = 1; i < kMaxTableRanges; ++i) r += blockIdx.x >= t.first_block[i] ? 1u : 0u;
+    const uint32_t lb = blockIdx.x - t.first_block[r];
+    const uint64_t len = t.len[r], flat = t.flat_off[r], local = t.local_off[r];
+    const uint32_t head = t.head[r], seg = t.segment[r];
+    const uint64_t nvec = (len - head) / VEC;
+    const uint32_t tail = (uint32_t)(len - head - nvec * VEC);
+    const uint64_t vi = (uint64_t)lb * kRwThreads + threadIdx.x;
+    if constexpr (CAST) {
+        const float scale = d_scale[seg];
+        if (vi < nvec) {
+            const uint64_t i = head + vi * VEC;
+            float x[VEC];
+            ld_f32<VEC>(master, local + i, x);
+            uint32_t w = 0;
+#pragma unroll
+            for (int c = 0; c < VEC; ++c) w |= f32_to_e4m3(x[c] * scale) << (8 * c);
+            st_stream(reinterpret_cast<uint32_t *>(out + flat + i), w);
+        }
+        if (lb == 0)
+            for (uint32_t e = threadIdx.x; e < head + tail; e += kRwThreads) {
+                const uint64_t i = e < head ? (uint64_t)e : (uint64_t)head + nvec * VEC + (e - head);
+                out[flat + i] = (uint8_t)f32_to_e4m3(master[local + i] * scale);
+            }
+    } else {
+        uint32_t m = 0;
+        if (vi < nvec) {
+            float x[VEC];
+            ld_f32<VEC>(master, local + head + vi * VEC, x);
+#pragma unroll
+            for (int c = 0; c < VEC; ++c) m = max(m, abs_bits(x[c]));
+        }
+        if (lb == 0)
+            for (uint32_t e = threadIdx.x; e < head + tail; e += kRwThreads) {
+                const uint64_t i = e < head ? (uint64_t)e : (uint64_t)head + nvec * VEC + (e - head);
+                m = max(m, abs_bits(master[local + i]));
+            }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) m = max(m, (uint32_t)__shfl_down((int)m, off, 64));
+        if (threadIdx.x == 0 && m > __hip_atomic_load(slots + seg, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
+            atomicMax(slots + seg, m);
+    }
+}
+
 // ---------------------------------------------------------------- host side
 typedef amsp_geom::Stream Stream16;
 using amsp_geom::make_span;
@@ -1649,27 +1703,74 @@ int amsp_fp8_payload_segments(const float *master_local, uint64_t local_elems, c
     hipStream_t hs = (hipStream_t)stream;
     uint32_t *slots = reinterpret_cast<uint32_t *>(d_amax);
     clear_stale_error();
+    // short segments share launches (tables of kMaxTableRanges); `cast` selects the pass
+    RangeTable table;
+    uint32_t in_table = 0, table_blocks = 0;
+    auto flush_table = [&](bool cast) -> int {
+        if (in_table == 0) return AMSP_OK;
+        for (uint32_t j = in_table; j < (uint32_t)kMaxTableRanges; ++j) {
+            table.first_block[j] = 0xFFFFFFFFu;
+            table.head[j] = 0; table.segment[j] = 0; table.flat_off[j] = 0; table.local_off[j] = 0; table.len[j] = 0;
+        }
+        if (cast)
+            hipLaunchKernelGGL((fp8_table_kernel<true>), dim3(table_blocks), dim3(kRwThreads), 0, hs, master_local,
+                               d_scale, param_fp8_flat, slots, table);
+        else
+            hipLaunchKernelGGL((fp8_table_kernel<false>), dim3(table_blocks), dim3(kRwThreads), 0, hs, master_local,
+                               d_scale, param_fp8_flat, slots, table);
+        in_table = 0;
+        table_blocks = 0;
+        return launched();
+    };
+    // true when segment i went into the table (short, and vectorisable or tiny)
+    auto tabled = [&](uint32_t i, bool cast, int *rc_out) -> bool {
+        const amsp_segment &g = segments[i];
+        if (g.length >= kShortSegment) return false;
+        Stream16 st[2] = {{master_local + g.local_offset, 4}, {param_fp8_flat + g.flat_offset, 1}};
+        const Span sp = make_span(g.length, st, cast ? 2 : 1, 4);
+        if (!sp.vectorised && g.length > 16 * kRwThreads) return false;
+        table.first_block[in_table] = table_blocks;
+        table.head[in_table] = sp.vectorised ? sp.head : (uint32_t)g.length;
+        table.segment[in_table] = i;
+        table.flat_off[in_table] = g.flat_offset;
+        table.local_off[in_table] = g.local_offset;
+        table.len[in_table] = g.length;
+        const uint64_t blocks = sp.vectorised ? (sp.nvec + kRwThreads - 1) / kRwThreads : 0;
+        table_blocks += (uint32_t)(blocks ? blocks : 1);
+        *rc_out = ++in_table == (uint32_t)kMaxTableRanges ? flush_table(cast) : (int)AMSP_OK;
+        return true;
+    };
     if (!amax_ready) {
         hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(kThreads), 0, hs, slots, num_segments, 0u);
         if (launched() != AMSP_OK) return AMSP_EDEVICE;
         for (uint32_t i = 0; i < num_segments; ++i) {
             if (segments[i].length == 0) continue;
+            if (tabled(i, false, &rc)) {
+                if (rc != AMSP_OK) return rc;
+                continue;
+            }
             const float *x = master_local + segments[i].local_offset;
             Stream16 st[1] = {{x, 4}};
             Span s = make_span(segments[i].length, st, 1, 4);
             hipLaunchKernelGGL(absmax_kernel, dim3(norm_grid(s)), dim3(kNormThreads), 0, hs, x, s, slots + i);
             if (launched() != AMSP_OK) return AMSP_EDEVICE;
         }
+        rc = flush_table(false);
+        if (rc != AMSP_OK) return rc;
     }
     hipLaunchKernelGGL(fp8_scale_kernel, dim3(1), dim3(kThreads), 0, hs, d_amax, d_scale, num_segments);
     if (launched() != AMSP_OK) return AMSP_EDEVICE;
     for (uint32_t i = 0; i < num_segments; ++i) {
         if (segments[i].length == 0) continue;
+        if (tabled(i, true, &rc)) {
+            if (rc != AMSP_OK) return rc;
+            continue;
+        }
         rc = amsp_cast_param_fp8_shard(master_local + segments[i].local_offset, segments[i].length, d_scale + i,
                                        param_fp8_flat + segments[i].flat_offset, stream);
         if (rc != AMSP_OK) return rc;
     }
-    return AMSP_OK;
+    return flush_table(true);
 }
 
 }  // extern "C"
