@@ -561,6 +561,10 @@ __global__ void __launch_bounds__(kThreads) adamw_kernel(PartialPtrs pp, int k, 
                                                          uint32_t *__restrict__ amax, AdamConsts c, Span s,
                                                          Buckets bk) {
     constexpr int VEC = kVecRW;
+    // Every kernel argument the common path needs is fetched before the squared norm is: scalar loads
+    // return out of order, so a later wait for an argument would also wait for that value.
+    const uint64_t bucket_elems = bk.bucket_elems;
+    asm volatile("" ::"s"(bucket_elems), "s"(s.nvec), "s"(s.head));
     const double sqnorm = load_sqnorm(c);
     uint32_t seen = 0;
     if constexpr (AMAX) seen = amax_seen(amax);
