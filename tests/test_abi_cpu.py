@@ -187,3 +187,36 @@ def test_product_package_never_imports_the_oracle():
             if f.endswith((".py", ".hip", ".c", ".h")):
                 text = open(os.path.join(dirpath, f)).read()
                 assert "import oracle" not in text and "from oracle" not in text and "amsp_oracle" not in text, f
+
+
+def test_header_is_plain_c_and_links_against_the_library(tmp_path):
+    """include/amsp.h compiles as C99 with gcc (no C++ in the boundary), and a C program that only
+    calls the host-side entry points links against libamsp.so and gets the documented answers."""
+    import subprocess
+
+    src = tmp_path / "abi_check.c"
+    src.write_text(r'''
+#include <stdio.h>
+#include "amsp.h"
+int main(void) {
+    uint64_t b = 0, e = 0;
+    if (amsp_shard_range(10, 3, 1, &b, &e) != AMSP_OK || b != 4 || e != 7) return 1;
+    if (amsp_shard_range(10, 0, 0, &b, &e) != AMSP_EINVAL) return 2;
+    if (amsp_workspace_bytes() == 0 || amsp_reduce_workspace_bytes(1u << 20, 0) == 0) return 3;
+    uint64_t sizes[4] = {5, 3, 3, 1};
+    uint32_t owner[4];
+    if (amsp_partition_tensors(sizes, 4, 2, owner) != AMSP_OK) return 4;
+    if (owner[0] != 0 || owner[1] != 1 || owner[2] != 1 || owner[3] != 0) return 5;
+    amsp_adamw_hparams hp;
+    if (sizeof hp != 48) return 6;
+    printf("%s\n", amsp_status_string(AMSP_EWORKSPACE));
+    return 0;
+}
+''')
+    exe = tmp_path / "abi_check"
+    lib_dir = os.path.dirname(build.LIB_AMSP)
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                    str(src), "-o", str(exe), "-L", lib_dir, "-lamsp", "-Wl,-rpath," + lib_dir], check=True)
+    out = subprocess.run([str(exe)], capture_output=True, text=True, timeout=60)
+    assert out.returncode == 0, (out.returncode, out.stderr[-500:])
+    assert "workspace" in out.stdout
