@@ -13,17 +13,21 @@
 //     instead of ~5.8 TB/s on the k = 8 fused step.
 //   - Those kernels run one-wave (64-thread) workgroups under an occupancy cap: only as many
 //     waves per CU as keep ~40 KiB of loads in flight, at least 8 (8 for k = 8, where the hardware
-//     would take 32).  That brings the k = 8 fused step from ~5.8 to 6.4-6.5 TB/s.  The cap is an unused slice
-//     of LDS per workgroup.  With so few waves, nothing may stand between a wave's start and its
-//     loads: no blockDim/gridDim (a dispatch-packet fetch), the clip scale worked out after the
-//     loads are in flight, and a scheduling barrier that keeps all k + 3 loads ahead of the first
-//     wait.
-//   - The head peeled off a misaligned range brings every stream to a 128-byte line, so that each
-//     wave's piece of each stream is whole lines.
+//     would take 32); the reduction 64 KiB and at least 12.  That brings the k = 8 fused step from
+//     ~5.8 to 6.4-6.5 TB/s.  The cap is an unused slice of LDS per workgroup.  With so few waves,
+//     nothing may stand between a wave's start and its loads: no blockDim/gridDim (a
+//     dispatch-packet fetch), the clip scale worked out after the loads are in flight, and a
+//     scheduling barrier that keeps all k + 3 loads ahead of the first wait.
+//   - The head peeled off a misaligned range brings every stream to a multiple of what a wave
+//     takes from it per access (512 B of bf16, 1 KiB of fp32): a wave's piece aligned to its own
+//     size.  Pieces that are only line-aligned cost 4-5 %, pieces that straddle lines ~20 %.
 //   - The read-only norm pass is the opposite case: a persistent grid of exactly the resident
 //     size (two 1024-thread blocks per CU) with a grid-stride loop and 16-byte loads reads at
 //     6.6-6.9 TB/s, more than any full-grid or 256-thread variant, and its per-block sums fit a
 //     small fixed workspace, summed in a fixed order.
+//   - Launches are shared: the buckets of a call, and the short segments of an inter-tensor shard
+//     (32 to a launch, the table in the kernel arguments), so that neither many buckets nor many
+//     small tensors make the step launch-bound.
 //   - Non-temporal hints on all loads and stores: nothing is reused.
 // Nothing is staged through LDS except the block-level sum of the norm.  No matrix cores:
 // there is no contraction on this path.
