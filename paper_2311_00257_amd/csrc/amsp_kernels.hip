@@ -496,9 +496,9 @@ struct AdamConsts {
     const double *d_total_sqnorm;
 };
 
-// The squared norm is fetched first (a scalar load that overlaps everything after it); the scale is
-// worked out from it later, in double, once the wave's vector loads are in flight.  (Fetched through
-// the vector path with a device-coherent load instead, it costs 1-3 %: it misses the caches, and the
+// The squared norm is fetched first (an ordinary cached load of one address, which overlaps everything
+// after it); the scale is worked out from it later, in double, once the wave's vector loads are in
+// flight.  (Fetched with a device-coherent load instead, it costs 1-3 %: it misses the caches, and the
 // in-order return of vector loads puts its latency in front of the first partial.)
 __device__ __forceinline__ double load_sqnorm(const AdamConsts &c) {
     return (c.d_total_sqnorm != nullptr && c.max_norm > 0.0f) ? *c.d_total_sqnorm : -1.0;
