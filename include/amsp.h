@@ -212,6 +212,9 @@ int amsp_owned_segments(const uint64_t *tensor_elems, const uint32_t *owner, uin
  * segments of the norm pass: a shard of thousands of small tensors is not bound by launches.
  *   partials_flat    host array of k device pointers, each bf16[flat_elems] (flat whole-model
  *                    gradient buffers: one all-reduced buffer, k = 1, or k partial ones)
+ *   k, grad_f32_local  k >= 1: the gradient is summed from partials_flat (grad_f32_local ignored).
+ *                    k == 0 (amsp_adamw_step_segments only): it is read from grad_f32_local, device
+ *                    fp32[local_elems], laid out like the optimizer states (partials_flat ignored)
  *   segments         host array [num_segments]; each must lie inside [0, flat_elems) and
  *                    [0, local_elems), else AMSP_EINVAL and nothing is enqueued
  *   master_local ... device fp32[local_elems], updated in place
@@ -225,11 +228,24 @@ int amsp_owned_segments(const uint64_t *tensor_elems, const uint32_t *owner, uin
  *                    when d_amax != NULL (else may be NULL); no initialisation needed, clobbered
  * The squared norm is accumulated in segment order (accumulate = 0 overwrites first).
  */
+/*
+ * Step 1 over a segment list ("select" into the rank's compact gradient buffer): for every owned
+ * segment, grad_f32_local[local_offset + i] (=|+=) sum_j partials_flat[j][flat_offset + i], as
+ * amsp_reduce_grad_shard does for a flat range.  With accumulate = 1 over the micro-batches of a step
+ * (Section IV-C.3) the buffer ends up holding the step's gradient of the rank's tensors; its squared
+ * norm is then amsp_grad_sqnorm(k = 0) over the compact buffer, and the update the k = 0 form of
+ * amsp_adamw_step_segments.
+ */
+int amsp_reduce_grad_segments(const uint16_t *const *partials_flat, uint32_t k, uint64_t flat_elems,
+                              const amsp_segment *segments, uint32_t num_segments,
+                              uint64_t local_elems, float *grad_f32_local, int accumulate, void *stream);
+
 int amsp_grad_sqnorm_segments(const uint16_t *const *partials_flat, uint32_t k, uint64_t flat_elems,
                               const amsp_segment *segments, uint32_t num_segments,
                               double *d_sqnorm, int accumulate,
                               void *workspace, size_t workspace_bytes, void *stream);
-int amsp_adamw_step_segments(const uint16_t *const *partials_flat, uint32_t k, uint64_t flat_elems,
+int amsp_adamw_step_segments(const uint16_t *const *partials_flat, uint32_t k,
+                             const float *grad_f32_local, uint64_t flat_elems,
                              const amsp_segment *segments, uint32_t num_segments, uint64_t local_elems,
                              float *master_local, float *exp_avg_local, float *exp_avg_sq_local,
                              uint16_t *param_bf16_flat, float *d_amax, void *amax_workspace,

@@ -21,7 +21,7 @@ AMSP_MAX_K = 32
 
 EXPORTS = ("amsp_status_string", "amsp_workspace_bytes", "amsp_reduce_workspace_bytes",
            "amsp_amax_workspace_bytes", "amsp_shard_range", "amsp_reduce_grad_shard", "amsp_grad_sqnorm", "amsp_adamw_step_shard", "amsp_cast_param_shard",
-           "amsp_partition_tensors", "amsp_owned_segments", "amsp_grad_sqnorm_segments",
+           "amsp_partition_tensors", "amsp_owned_segments", "amsp_reduce_grad_segments", "amsp_grad_sqnorm_segments",
            "amsp_adamw_step_segments", "amsp_cast_param_fp8_shard", "amsp_fp8_payload_segments",
            "amsp_plan_sharding")
 
@@ -109,8 +109,9 @@ def load() -> ctypes.CDLL:
         lib.amsp_owned_segments.argtypes = [pu64, pu32, u32, u32, ctypes.POINTER(_Segment), u32, pu32, pu64]
         lib.amsp_grad_sqnorm_segments.argtypes = [vp, u32, u64, ctypes.POINTER(_Segment), u32, vp, ci, vp,
                                                   ctypes.c_size_t, vp]
-        lib.amsp_adamw_step_segments.argtypes = [vp, u32, u64, ctypes.POINTER(_Segment), u32, u64, vp, vp, vp, vp,
-                                                 vp, vp, ctypes.c_size_t, ctypes.POINTER(_Hparams), vp]
+        lib.amsp_adamw_step_segments.argtypes = [vp, u32, vp, u64, ctypes.POINTER(_Segment), u32, u64, vp, vp, vp,
+                                                 vp, vp, vp, ctypes.c_size_t, ctypes.POINTER(_Hparams), vp]
+        lib.amsp_reduce_grad_segments.argtypes = [vp, u32, u64, ctypes.POINTER(_Segment), u32, u64, vp, ci, vp]
         lib.amsp_amax_workspace_bytes.argtypes = [u32]
         lib.amsp_amax_workspace_bytes.restype = ctypes.c_size_t
         lib.amsp_cast_param_fp8_shard.argtypes = [vp, u64, vp, vp, vp]
@@ -277,16 +278,29 @@ def amsp_grad_sqnorm_segments(partials_flat, flat_elems: int, segments, d_sqnorm
 
 def amsp_adamw_step_segments(partials_flat, flat_elems: int, segments, local_elems: int, master_local,
                              exp_avg_local, exp_avg_sq_local, param_bf16_flat, hp: AdamWHparams, stream=None,
-                             d_amax=None, amax_workspace=None, amax_workspace_bytes: Optional[int] = None) -> None:
-    arr, k = _partials(partials_flat)
+                             d_amax=None, amax_workspace=None, amax_workspace_bytes: Optional[int] = None,
+                             grad_f32_local=None) -> None:
+    """partials_flat: list of k flat bf16 buffers, or None with grad_f32_local (the k = 0 form)."""
+    if partials_flat is None:
+        arr, k = None, 0
+    else:
+        arr, k = _partials(partials_flat)
     segs, ns = _segments(segments)
     c = _hp_struct(hp) if hp is not None else None
-    _check(load().amsp_adamw_step_segments(arr, k, flat_elems, segs, ns, local_elems, _ptr(master_local),
-                                           _ptr(exp_avg_local), _ptr(exp_avg_sq_local), _ptr(param_bf16_flat),
-                                           _ptr(d_amax), _ptr(amax_workspace),
+    _check(load().amsp_adamw_step_segments(arr, k, _ptr(grad_f32_local), flat_elems, segs, ns, local_elems,
+                                           _ptr(master_local), _ptr(exp_avg_local), _ptr(exp_avg_sq_local),
+                                           _ptr(param_bf16_flat), _ptr(d_amax), _ptr(amax_workspace),
                                            _nbytes(amax_workspace, amax_workspace_bytes),
                                            ctypes.byref(c) if c is not None else None, _stream(stream)),
            "amsp_adamw_step_segments")
+
+
+def amsp_reduce_grad_segments(partials_flat, flat_elems: int, segments, local_elems: int, grad_f32_local,
+                              accumulate: bool = False, stream=None) -> None:
+    arr, k = _partials(partials_flat)
+    segs, ns = _segments(segments)
+    _check(load().amsp_reduce_grad_segments(arr, k, flat_elems, segs, ns, local_elems, _ptr(grad_f32_local),
+                                            int(accumulate), _stream(stream)), "amsp_reduce_grad_segments")
 
 
 def amsp_amax_workspace_bytes(num_segments: int) -> int:

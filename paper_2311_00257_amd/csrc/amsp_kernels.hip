@@ -644,8 +644,10 @@ struct RangeTable {
     uint64_t len[kMaxTableRanges];
 };
 
-template <bool WRITE_BF16, bool AMAX>
-__global__ void __launch_bounds__(kRwThreads) adamw_table_kernel(PartialPtrs pp, int k, float *__restrict__ master,
+template <int K, bool WRITE_BF16, bool AMAX>
+__global__ void __launch_bounds__(kRwThreads) adamw_table_kernel(PartialPtrs pp, int k,
+                                                                 const float *__restrict__ gf32_local,
+                                                                 float *__restrict__ master,
                                                                  float *__restrict__ exp_avg,
                                                                  float *__restrict__ exp_avg_sq,
                                                                  uint16_t *__restrict__ out,
@@ -675,7 +677,8 @@ __global__ void __launch_bounds__(kRwThreads) adamw_table_kernel(PartialPtrs pp,
         ld_f32<VEC>(master, local + i, p);
         ld_f32<VEC>(exp_avg, local + i, m);
         ld_f32<VEC>(exp_avg_sq, local + i, v);
-        grad_vec<-1, VEC>(pp, k, nullptr, flat + i, g);
+        // K == 0: the gradient is the rank's compact fp32 buffer, indexed like its optimizer states
+        grad_vec<K, VEC>(pp, k, gf32_local, (K == 0 ? local : flat) + i, g);
         const float scale = clip_scale(c, sqnorm);
 #pragma unroll
         for (int q = 0; q < VEC; ++q) adamw1(c, scale, g[q], p[q], m[q], v[q]);
@@ -693,7 +696,7 @@ __global__ void __launch_bounds__(kRwThreads) adamw_table_kernel(PartialPtrs pp,
         for (uint32_t e = threadIdx.x; e < head + tail; e += kRwThreads) {
             const uint64_t i = e < head ? (uint64_t)e : (uint64_t)head + nvec * VEC + (e - head);
             float p = master[local + i], m = exp_avg[local + i], v = exp_avg_sq[local + i];
-            adamw1(c, scale, grad1<-1>(pp, k, nullptr, flat + i), p, m, v);
+            adamw1(c, scale, grad1<K>(pp, k, gf32_local, (K == 0 ? local : flat) + i), p, m, v);
             master[local + i] = p;
             exp_avg[local + i] = m;
             exp_avg_sq[local + i] = v;
@@ -1573,36 +1576,74 @@ int amsp_grad_sqnorm_segments(const uint16_t *const *partials_flat, uint32_t k, 
     return batch.flush();
 }
 
-size_t amsp_amax_workspace_bytes(uint32_t num_segments) {
-    return (size_t)num_segments * kAmaxWordsPerSegment * sizeof(uint32_t);
-}
-
-int amsp_adamw_step_segments(const uint16_t *const *partials_flat, uint32_t k, uint64_t flat_elems,
-                             const amsp_segment *segments, uint32_t num_segments, uint64_t local_elems,
-                             float *master_local, float *exp_avg_local, float *exp_avg_sq_local,
-                             uint16_t *param_bf16_flat, float *d_amax, void *amax_workspace,
-                             size_t amax_workspace_bytes, const amsp_adamw_hparams *hp, void *stream) {
+int amsp_reduce_grad_segments(const uint16_t *const *partials_flat, uint32_t k, uint64_t flat_elems,
+                              const amsp_segment *segments, uint32_t num_segments, uint64_t local_elems,
+                              float *grad_f32_local, int accumulate, void *stream) {
     PartialPtrs pp;
     int rc = check_partials(partials_flat, k, pp);
     if (rc != AMSP_OK) return rc;
     rc = check_segments(segments, num_segments, flat_elems, local_elems);
     if (rc != AMSP_OK) return rc;
-    if (hp == nullptr) return AMSP_ENULL;
+    for (uint32_t i = 0; i < num_segments; ++i) {
+        if (segments[i].length == 0) continue;
+        if (grad_f32_local == nullptr) return AMSP_ENULL;
+        if (too_long(segments[i].length, 0)) return AMSP_EINVAL;
+    }
+    if (misaligned(grad_f32_local, 4)) return AMSP_EALIGN;
+    for (uint32_t i = 0; i < num_segments; ++i) {
+        const amsp_segment &g = segments[i];
+        if (g.length == 0) continue;
+        PartialPtrs q = offset_partials(pp, k, g.flat_offset);
+        rc = amsp_reduce_grad_shard(q.p, k, g.length, 0, grad_f32_local + g.local_offset, accumulate, nullptr, 0,
+                                    nullptr, 0, stream);
+        if (rc != AMSP_OK) return rc;
+    }
+    return AMSP_OK;
+}
+
+size_t amsp_amax_workspace_bytes(uint32_t num_segments) {
+    return (size_t)num_segments * kAmaxWordsPerSegment * sizeof(uint32_t);
+}
+
+int amsp_adamw_step_segments(const uint16_t *const *partials_flat, uint32_t k, const float *grad_f32_local,
+                             uint64_t flat_elems, const amsp_segment *segments, uint32_t num_segments,
+                             uint64_t local_elems, float *master_local, float *exp_avg_local,
+                             float *exp_avg_sq_local, uint16_t *param_bf16_flat, float *d_amax,
+                             void *amax_workspace, size_t amax_workspace_bytes, const amsp_adamw_hparams *hp,
+                             void *stream) {
+    PartialPtrs pp{};
+    int rc = AMSP_OK;
+    if (k > 0) {
+        rc = check_partials(partials_flat, k, pp);
+        if (rc != AMSP_OK) return rc;
+    }
+    rc = check_segments(segments, num_segments, flat_elems, local_elems);
+    if (rc != AMSP_OK) return rc;
+    AdamConsts c;
+    rc = adam_consts(hp, c);
+    if (rc != AMSP_OK) return rc;
     uint32_t *words = nullptr;
     if (d_amax != nullptr && num_segments > 0) {
         if (amax_workspace == nullptr) return AMSP_ENULL;
         if (misaligned(d_amax, 4) || misaligned(amax_workspace, 4)) return AMSP_EALIGN;
         if (amax_workspace_bytes < amsp_amax_workspace_bytes(num_segments)) return AMSP_EWORKSPACE;
+        if ((size_t)num_segments * kAmaxWordsPerSegment > 0xFFFFFFFFull) return AMSP_EINVAL;
         words = static_cast<uint32_t *>(amax_workspace);
     }
-    for (uint32_t i = 0; i < num_segments; ++i)
-        if (segments[i].length != 0 &&
-            (master_local == nullptr || exp_avg_local == nullptr || exp_avg_sq_local == nullptr))
+    for (uint32_t i = 0; i < num_segments; ++i) {
+        if (segments[i].length == 0) continue;
+        if (master_local == nullptr || exp_avg_local == nullptr || exp_avg_sq_local == nullptr ||
+            (k == 0 && grad_f32_local == nullptr))
             return AMSP_ENULL;
+        if (too_long(segments[i].length, 0)) return AMSP_EINVAL;
+    }
+    if (misaligned(master_local, 4) || misaligned(exp_avg_local, 4) || misaligned(exp_avg_sq_local, 4) ||
+        (k == 0 && misaligned(grad_f32_local, 4)) || (param_bf16_flat && misaligned(param_bf16_flat, 2)))
+        return AMSP_EALIGN;
+    // everything checked: from here on work is enqueued
     hipStream_t hs = (hipStream_t)stream;
     if (words != nullptr) {   // the maxima start from +0, the smallest |x| pattern
         const size_t count = (size_t)num_segments * kAmaxWordsPerSegment;
-        if (count > 0xFFFFFFFFull) return AMSP_EINVAL;
         clear_stale_error();
         const unsigned blocks = (unsigned)((count + kThreads - 1) / kThreads);
         hipLaunchKernelGGL(fill_u32_kernel, dim3(blocks > 1024 ? 1024 : blocks), dim3(kThreads), 0, hs, words,
@@ -1611,12 +1652,6 @@ int amsp_adamw_step_segments(const uint16_t *const *partials_flat, uint32_t k, u
     }
     // Segments shorter than kShortSegment share launches, up to kMaxTableRanges each (a launch costs more
     // than such a segment's traffic); the others get a launch of their own with every k loaded at once.
-    AdamConsts c;
-    rc = adam_consts(hp, c);
-    if (rc != AMSP_OK) return rc;
-    if (misaligned(master_local, 4) || misaligned(exp_avg_local, 4) || misaligned(exp_avg_sq_local, 4) ||
-        (param_bf16_flat && misaligned(param_bf16_flat, 2)))
-        return AMSP_EALIGN;
     RangeTable table;
     uint32_t in_table = 0, table_blocks = 0;
     auto flush_table = [&]() -> int {
@@ -1625,15 +1660,18 @@ int amsp_adamw_step_segments(const uint16_t *const *partials_flat, uint32_t k, u
             table.first_block[j] = 0xFFFFFFFFu;
             table.head[j] = 0; table.segment[j] = 0; table.flat_off[j] = 0; table.local_off[j] = 0; table.len[j] = 0;
         }
-        const unsigned lane_bytes = 8 * k + 48;
+        const unsigned lane_bytes = (k != 0 ? 8 * k : 16) + 48;
         const unsigned lds = occupancy_lds(lane_bytes, adamw_target(lane_bytes));
         const dim3 grid(table_blocks), block(kRwThreads);
         clear_stale_error();
-#define AMSP_LAUNCH_TABLE(B16, AM)                                                                              \
-        hipLaunchKernelGGL((adamw_table_kernel<B16, AM>), grid, block, lds, hs, pp, (int)k, master_local,      \
-                           exp_avg_local, exp_avg_sq_local, param_bf16_flat, words, c, table)
-        if (param_bf16_flat) { if (words) AMSP_LAUNCH_TABLE(true, true); else AMSP_LAUNCH_TABLE(true, false); }
-        else { if (words) AMSP_LAUNCH_TABLE(false, true); else AMSP_LAUNCH_TABLE(false, false); }
+#define AMSP_LAUNCH_TABLE(KV, B16, AM)                                                                          \
+        hipLaunchKernelGGL((adamw_table_kernel<KV, B16, AM>), grid, block, lds, hs, pp, (int)k, grad_f32_local, \
+                           master_local, exp_avg_local, exp_avg_sq_local, param_bf16_flat, words, c, table)
+#define AMSP_LAUNCH_TABLE_K(KV)                                                                                  \
+        if (param_bf16_flat) { if (words) AMSP_LAUNCH_TABLE(KV, true, true); else AMSP_LAUNCH_TABLE(KV, true, false); } \
+        else { if (words) AMSP_LAUNCH_TABLE(KV, false, true); else AMSP_LAUNCH_TABLE(KV, false, false); }
+        if (k == 0) { AMSP_LAUNCH_TABLE_K(0) } else { AMSP_LAUNCH_TABLE_K(-1) }
+#undef AMSP_LAUNCH_TABLE_K
 #undef AMSP_LAUNCH_TABLE
         in_table = 0;
         table_blocks = 0;
@@ -1643,9 +1681,11 @@ int amsp_adamw_step_segments(const uint16_t *const *partials_flat, uint32_t k, u
         const amsp_segment &g = segments[i];
         if (g.length == 0) continue;
         PartialPtrs q = offset_partials(pp, k, g.flat_offset);
+        const float *gf = k == 0 ? grad_f32_local + g.local_offset : nullptr;
         if (g.length < kShortSegment) {
-            Stream16 st[AMSP_MAX_K + 4];
+            Stream16 st[AMSP_MAX_K + 5];
             int ns = add_partial_streams(st, 0, q, k);
+            if (k == 0) st[ns++] = Stream16{gf, 4};
             st[ns++] = Stream16{master_local + g.local_offset, 4};
             st[ns++] = Stream16{exp_avg_local + g.local_offset, 4};
             st[ns++] = Stream16{exp_avg_sq_local + g.local_offset, 4};
@@ -1668,7 +1708,7 @@ int amsp_adamw_step_segments(const uint16_t *const *partials_flat, uint32_t k, u
                 continue;
             }
         }
-        rc = adamw_step_range(q.p, k, nullptr, g.length, 0, master_local + g.local_offset,
+        rc = adamw_step_range(q.p, k, gf, g.length, 0, master_local + g.local_offset,
                               exp_avg_local + g.local_offset, exp_avg_sq_local + g.local_offset,
                               param_bf16_flat ? param_bf16_flat + g.flat_offset : nullptr,
                               words ? words + (size_t)i * kAmaxWordsPerSegment : nullptr, hp, stream);

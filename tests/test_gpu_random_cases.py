@@ -165,6 +165,27 @@ def test_random_inter_tensor_models(B, torch_mod):
             mine = oracle.select(out_bits, segs)
             assert np.array_equal(mine, oracle.cast(p))
             H.check_bf16(mine, ref, inp.p)
+            # the same step through the rank's compact fp32 gradient, accumulated over two "micro-batches"
+            g_local = torch.full((local,), 7.0, dtype=torch.float32, device="cuda")
+            half = max(1, k // 2)
+            B.amsp_reduce_grad_segments(dparts[:half], total, segs, local, g_local)
+            if half < k:
+                B.amsp_reduce_grad_segments(dparts[half:], total, segs, local, g_local, accumulate=True)
+            d_s2 = torch.full((1,), -3.0, dtype=torch.float64, device="cuda")
+            B.amsp_grad_sqnorm(None, g_local, local, d_s2, ws)
+            dp2, dm2, dv2 = H.to_dev_f32(inp.p), H.to_dev_f32(inp.m), H.to_dev_f32(inp.v)
+            out2 = torch.full((total,), 0x5A5A, dtype=torch.int16, device="cuda")
+            B.amsp_adamw_step_segments(None, total, segs, local, dp2, dm2, dv2, out2,
+                                       B.AdamWHparams(d_total_sqnorm=d_s2, **hp), grad_f32_local=g_local)
+            torch.cuda.synchronize()
+            assert abs(float(d_s2.item()) - ref["sqnorm"]) <= H.REL_TOL * ref["sqnorm"]
+            p2 = dp2.cpu().numpy()
+            H.check_state(p2, dm2.cpu().numpy(), dv2.cpu().numpy(), ref, inp.p, inp.m, hp)
+            bits2 = H.dev_bits(out2)
+            assert np.all(bits2[elem_owner != rank] == 0x5A5A)
+            assert np.array_equal(oracle.select(bits2, segs), oracle.cast(p2))
+            if k == 1:                                         # one partial: the same fp32 gradient, the same bits
+                assert np.array_equal(p2, p) and np.array_equal(bits2, out_bits)
             # FP8 payload of the updated shard
             fp8 = torch.full((total,), 0xA5, dtype=torch.uint8, device="cuda")
             d_amax = torch.full((len(segs),), -1.0, dtype=torch.float32, device="cuda")
