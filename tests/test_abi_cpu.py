@@ -158,6 +158,23 @@ def test_segment_validation_without_device():
         B.amsp_adamw_step_segments([A], 100, [(0, 0, 10)], 100, 0, A, A, A, hp, stream=0)
     assert ei.value.status == B.AMSP_ENULL
     B.amsp_adamw_step_segments([A], 100, [], 0, 0, 0, 0, 0, hp, stream=0)          # owns nothing: fine
+    # the forms through a compact fp32 gradient
+    with pytest.raises(B.AmspError) as ei:
+        B.amsp_reduce_grad_segments([A], 100, [(95, 0, 10)], 100, A, stream=0)
+    assert ei.value.status == B.AMSP_EINVAL
+    with pytest.raises(B.AmspError) as ei:
+        B.amsp_reduce_grad_segments([A], 100, [(0, 0, 10)], 100, 0, stream=0)
+    assert ei.value.status == B.AMSP_ENULL
+    with pytest.raises(B.AmspError) as ei:
+        B.amsp_reduce_grad_segments([A], 100, [(0, 0, 10)], 100, A + 2, stream=0)
+    assert ei.value.status == B.AMSP_EALIGN
+    B.amsp_reduce_grad_segments([A], 100, [], 0, 0, stream=0)
+    with pytest.raises(B.AmspError) as ei:                   # k = 0 without a gradient buffer
+        B.amsp_adamw_step_segments(None, 100, [(0, 0, 10)], 100, A, A, A, A, hp, stream=0)
+    assert ei.value.status == B.AMSP_ENULL
+    with pytest.raises(B.AmspError) as ei:
+        B.amsp_adamw_step_segments(None, 100, [(0, 0, 10)], 100, A, A, A, A, hp, stream=0, grad_f32_local=A + 2)
+    assert ei.value.status == B.AMSP_EALIGN
     # per-segment maxima asked for: the workspace is checked before anything is enqueued
     need = B.amsp_amax_workspace_bytes(3)
     assert need == 3 * B.amsp_amax_workspace_bytes(1) > 0 and B.amsp_amax_workspace_bytes(0) == 0
