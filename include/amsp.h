@@ -29,7 +29,10 @@
  *     streams of a call reach the alignment of their vector access (8 or 16 bytes) at the
  *     same element index, as they do when every buffer is offset by the same number of
  *     elements from a 16-byte boundary, the kernels use vector accesses; otherwise a slower
- *     element-wise path gives the same results.
+ *     element-wise path gives the same results.  Fastest is every buffer at the same element
+ *     offset from a 1 KiB boundary (as separately allocated buffers are): the leading elements
+ *     up to the first such boundary (at most 255) are then done one by one and every wave's
+ *     accesses are aligned to their own size.
  *   - bf16 values are passed as uint16_t bit patterns.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is
  *     enqueued and the call returns without waiting; amsp_shard_range alone is synchronous.
@@ -96,7 +99,7 @@ int amsp_shard_range(uint64_t total_elems, uint32_t shard_factor, uint32_t rank,
  *   d_sqnorm    device double or NULL.  Not NULL: *d_sqnorm (=|+=) sum_i grad_out[i]^2 of the
  *               values just written (after `accumulate`), in fp64 in a fixed order, added in
  *               bucket order; sqnorm_accumulate 0 overwrites, 1 adds to the value already there
- *   workspace   device, >= amsp_reduce_workspace_bytes(n, bucket_elems) (about n/1024 doubles: the
+ *   workspace   device, >= amsp_reduce_workspace_bytes(n, bucket_elems) (about n/256 doubles: the
  *               block sums of every bucket side by side, added once after the last bucket),
  *               8-byte aligned, used only when d_sqnorm != NULL (else may be NULL); no
  *               initialisation needed, clobbered
