@@ -209,6 +209,18 @@ int amsp_owned_segments(const uint64_t *tensor_elems, const uint32_t *owner, uin
                         uint32_t *num_segments, uint64_t *local_elems);
 
 /*
+ * Step 1 over a segment list ("select" into the rank's compact gradient buffer): for every owned
+ * segment, grad_f32_local[local_offset + i] (=|+=) sum_j partials_flat[j][flat_offset + i], as
+ * amsp_reduce_grad_shard does for a flat range.  With accumulate = 1 over the micro-batches of a step
+ * (Section IV-C.3) the buffer ends up holding the step's gradient of the rank's tensors; its squared
+ * norm is then amsp_grad_sqnorm(k = 0) over the compact buffer, and the update the k = 0 form of
+ * amsp_adamw_step_segments.
+ */
+int amsp_reduce_grad_segments(const uint16_t *const *partials_flat, uint32_t k, uint64_t flat_elems,
+                              const amsp_segment *segments, uint32_t num_segments,
+                              uint64_t local_elems, float *grad_f32_local, int accumulate, void *stream);
+
+/*
  * Steps 2 and 1+3+4 over a segment list: as amsp_grad_sqnorm / amsp_adamw_step_shard ("select":
  * only owned elements are read; "drop": nothing else is touched).  Long segments get a launch of
  * their own; segments shorter than 2^20 elements share launches, 32 to a launch, and so do the
@@ -231,18 +243,6 @@ int amsp_owned_segments(const uint64_t *tensor_elems, const uint32_t *owner, uin
  *                    when d_amax != NULL (else may be NULL); no initialisation needed, clobbered
  * The squared norm is accumulated in segment order (accumulate = 0 overwrites first).
  */
-/*
- * Step 1 over a segment list ("select" into the rank's compact gradient buffer): for every owned
- * segment, grad_f32_local[local_offset + i] (=|+=) sum_j partials_flat[j][flat_offset + i], as
- * amsp_reduce_grad_shard does for a flat range.  With accumulate = 1 over the micro-batches of a step
- * (Section IV-C.3) the buffer ends up holding the step's gradient of the rank's tensors; its squared
- * norm is then amsp_grad_sqnorm(k = 0) over the compact buffer, and the update the k = 0 form of
- * amsp_adamw_step_segments.
- */
-int amsp_reduce_grad_segments(const uint16_t *const *partials_flat, uint32_t k, uint64_t flat_elems,
-                              const amsp_segment *segments, uint32_t num_segments,
-                              uint64_t local_elems, float *grad_f32_local, int accumulate, void *stream);
-
 int amsp_grad_sqnorm_segments(const uint16_t *const *partials_flat, uint32_t k, uint64_t flat_elems,
                               const amsp_segment *segments, uint32_t num_segments,
                               double *d_sqnorm, int accumulate,
