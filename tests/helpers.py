@@ -74,13 +74,30 @@ def rel_err_scaled(got: np.ndarray, want: np.ndarray, floor: np.ndarray) -> np.n
     return np.abs(got.astype(np.float64) - want) / den
 
 
+def master_floor(ref: dict, inp_p, inp_m, hp: dict) -> np.ndarray:
+    """Denominator floor of the master's relative error: the largest operand of the final addition
+    (|p| and the applied step), plus what the first moment's own floor becomes on its way into the
+    step.  The first moment m' = beta1 m + (1 - beta1) g' is only known to `tol` of its larger operand;
+    where the two cancel, that uncertainty reaches p through lr * m_hat / (sqrt(v_hat) + eps) and is
+    not small against a p and a step that are themselves tiny."""
+    f32 = lambda x: float(np.float32(x))
+    b1, b2, lr, eps = f32(hp["beta1"]), f32(hp["beta2"]), f32(hp["lr"]), f32(hp["eps"])
+    t = int(hp["step"])
+    gs = np.abs(ref["scale"] * ref["G"])
+    floor_m = np.maximum(b1 * np.abs(inp_m.astype(np.float64)), (1 - b1) * gs)
+    denom = np.sqrt(ref["v"] / (1.0 - b2 ** t)) + eps
+    through_m = abs(lr) * (floor_m / (1.0 - b1 ** t)) / np.where(denom > 0, denom, 1.0)
+    return np.maximum(np.abs(inp_p.astype(np.float64)), np.abs(ref["p"] - inp_p)) + through_m
+
+
 def check_state(got_p, got_m, got_v, ref: dict, inp_p, inp_m, hp: dict, tol: float = REL_TOL):
     """fp32 master/m/v against the oracle's doubles.  The floor of each denominator is the
-    largest operand of the final addition: |p| and the applied step for the master,
-    beta1 |m| and (1-beta1)|g'| for the first moment; the second moment has no cancellation."""
+    largest operand of the final addition: |p| and the applied step for the master (plus the first
+    moment's floor carried into the step, see master_floor), beta1 |m| and (1-beta1)|g'| for the first
+    moment; the second moment has no cancellation."""
     b1 = float(np.float32(hp["beta1"]))
     gs = np.abs(ref["scale"] * ref["G"])
-    floor_p = np.maximum(np.abs(inp_p.astype(np.float64)), np.abs(ref["p"] - inp_p))
+    floor_p = master_floor(ref, inp_p, inp_m, hp)
     floor_m = np.maximum(b1 * np.abs(inp_m.astype(np.float64)), (1 - b1) * gs)
     ep = rel_err_scaled(got_p, ref["p"], floor_p)
     em = rel_err_scaled(got_m, ref["m"], floor_m)
@@ -100,10 +117,11 @@ def _bf16_neighbours(bits: np.ndarray):
     return f
 
 
-def check_bf16(got_bits: np.ndarray, ref: dict, inp_p: np.ndarray, tol: float = REL_TOL) -> int:
+def check_bf16(got_bits: np.ndarray, ref: dict, inp_p: np.ndarray, tol: float = REL_TOL, inp_m=None,
+               hp=None) -> int:
     """bf16 parameters: identical to bf16(fp32(p')) of the oracle, except where the fp32 tolerance
     lets p' round elsewhere: with delta = `tol` * max(|p'|, |p|, |p' - p|) (check_state's tolerance
-    for the master), the shipped value must be the rounding of some value in [p' - delta, p' + delta],
+    for the master; with inp_m and hp given, master_floor's), the shipped value must be the rounding of some value in [p' - delta, p' + delta],
     i.e. lie between bf16(p' - delta) and bf16(p' + delta).  Away from cancellation delta is 1/400
     of a bf16 step, so this is "exact, or the other neighbour when p' is within delta of the midpoint";
     where p and the step cancel (p' a million times smaller than its operands) it is as wide as the
@@ -117,7 +135,11 @@ def check_bf16(got_bits: np.ndarray, ref: dict, inp_p: np.ndarray, tol: float = 
         return 0
     pp = ref["p"][bad]
     p_in = inp_p[bad].astype(np.float64)
-    delta = tol * np.maximum(np.abs(pp), np.maximum(np.abs(p_in), np.abs(pp - p_in)))
+    if inp_m is not None and hp is not None:
+        floor = np.maximum(np.abs(ref["p"]), master_floor(ref, inp_p, inp_m, hp))[bad]
+    else:
+        floor = np.maximum(np.abs(pp), np.maximum(np.abs(p_in), np.abs(pp - p_in)))
+    delta = tol * floor
     lo = synth.bf16_bits_to_f32(oracle.cast(oracle.round_f32(pp - delta))).astype(np.float64)
     hi = synth.bf16_bits_to_f32(oracle.cast(oracle.round_f32(pp + delta))).astype(np.float64)
     g = synth.bf16_bits_to_f32(got_bits[bad]).astype(np.float64)

@@ -99,7 +99,7 @@ def _run_fullsize(cfg, windows=24, width=1 << 16):
         gp, gm, gv = dp[sl].cpu().numpy(), dm[sl].cpu().numpy(), dv[sl].cpu().numpy()
         st = H.check_state(gp, gm, gv, ref, inp.p, inp.m, hp)
         bits = H.dev_bits(out[sl])
-        worst["mismatches"] += H.check_bf16(bits, ref, inp.p)
+        worst["mismatches"] += H.check_bf16(bits, ref, inp.p, inp_m=inp.m, hp=hp)
         assert np.array_equal(bits, oracle.cast(gp))         # the cast of the GPU's own fp32 is bit-exact
         for key in ("max_p", "max_m", "max_v"):
             worst[key] = max(worst[key], st[key])
@@ -189,7 +189,7 @@ def test_workload5_llama7b_inter_tensor_full():
             gp = dp[sl].cpu().numpy()
             st = H.check_state(gp, dm[sl].cpu().numpy(), dv[sl].cpu().numpy(), ref, inp.p, inp.m, hp)
             bits = H.dev_bits(out[f + a:f + a + wd])
-            worst["mismatches"] += H.check_bf16(bits, ref, inp.p)
+            worst["mismatches"] += H.check_bf16(bits, ref, inp.p, inp_m=inp.m, hp=hp)
             assert np.array_equal(bits, oracle.cast(gp))
             for key in ("max_p", "max_m", "max_v"):
                 worst[key] = max(worst[key], st[key])

@@ -262,7 +262,7 @@ def _check_all(got, ref, inp, hp):
     assert abs(S - ref["sqnorm"]) <= H.REL_TOL * ref["sqnorm"]
     stats = H.check_state(p, m, v, ref, inp.p, inp.m, hp)
     if bits is not None:
-        stats["bf16_boundary_mismatches"] = H.check_bf16(bits, ref, inp.p)
+        stats["bf16_boundary_mismatches"] = H.check_bf16(bits, ref, inp.p, inp_m=inp.m, hp=hp)
         assert np.array_equal(bits, oracle.cast(p))        # the cast of the GPU's own fp32 is bit-exact
         assert stats["bf16_boundary_mismatches"] <= max(3, 1e-4 * p.size)
     return stats
@@ -567,4 +567,4 @@ def test_non_finite_gradients_propagate_like_the_oracle(B, torch_mod, poison):
     assert np.all(np.isfinite(p[good])) and np.all(np.isfinite(m[good])) and np.all(np.isfinite(v[good]))
     sub = {key: (val[good] if isinstance(val, np.ndarray) else val) for key, val in ref.items()}
     H.check_state(p[good], m[good], v[good], sub, inp.p[good], inp.m[good], hp)
-    H.check_bf16(bits[good], sub, inp.p[good])
+    H.check_bf16(bits[good], sub, inp.p[good], inp_m=inp.m[good], hp=hp)

@@ -110,7 +110,7 @@ def test_random_cases_against_oracle(B, torch_mod):
             worst[key] = max(worst[key], stats[key])
         if bits is not None:
             assert np.array_equal(bits, oracle.cast(p)), c
-            assert H.check_bf16(bits, ref, inp.p) <= max(3, 1e-4 * p.size), c
+            assert H.check_bf16(bits, ref, inp.p, inp_m=inp.m, hp=hp) <= max(3, 1e-4 * p.size), c
     print("worst scaled relative errors over the sweep:", worst)
 
 
@@ -166,7 +166,7 @@ def test_random_inter_tensor_models(B, torch_mod):
             H.check_state(p, dm.cpu().numpy(), dv.cpu().numpy(), ref, inp.p, inp.m, hp)
             mine = oracle.select(out_bits, segs)
             assert np.array_equal(mine, oracle.cast(p))
-            H.check_bf16(mine, ref, inp.p)
+            H.check_bf16(mine, ref, inp.p, inp_m=inp.m, hp=hp)
             # the same step through the rank's compact fp32 gradient, accumulated over two "micro-batches"
             g_local = torch.full((local,), 7.0, dtype=torch.float32, device="cuda")
             half = max(1, k // 2)
