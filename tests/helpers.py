@@ -74,34 +74,55 @@ def rel_err_scaled(got: np.ndarray, want: np.ndarray, floor: np.ndarray) -> np.n
     return np.abs(got.astype(np.float64) - want) / den
 
 
-def master_floor(ref: dict, inp_p, inp_m, hp: dict) -> np.ndarray:
-    """Denominator floor of the master's relative error: the largest operand of the final addition
-    (|p| and the applied step), plus what the first moment's own floor becomes on its way into the
-    step.  The first moment m' = beta1 m + (1 - beta1) g' is only known to `tol` of its larger operand;
-    where the two cancel, that uncertainty reaches p through lr * m_hat / (sqrt(v_hat) + eps) and is
-    not small against a p and a step that are themselves tiny."""
+def abs_partials(partials) -> np.ndarray:
+    """sum_j |g_j[i]| in double: the magnitude against which a k-term fp32 sum is known."""
+    total = np.zeros(partials[0].size, dtype=np.float64)
+    for q in partials:
+        total += np.abs(synth.bf16_bits_to_f32(q).astype(np.float64))
+    return total
+
+
+def floors(ref: dict, inp_p, inp_m, hp: dict, abs_g=None):
+    """Denominator floors (master, first moment, second moment) of the scaled relative errors:
+    'max relative error <= tol' read relative to the largest operand where a result is small by
+    cancellation, and carried forward to first order.
+      gradient      a k-term fp32 sum is known to tol of sum_j |g_j| (abs_g), not of |G|;
+      first moment  tau_m = max(beta1 |m|, (1 - beta1) scale abs_g);
+      second moment v' plus the part of (1 - beta2) g'^2 that is uncertain because g' is:
+                    2 (1 - beta2) |g'| (scale abs_g - |g'|);
+      master        max(|p|, |p' - p|), the operands of the final addition, plus what the excess of
+                    the two moments' floors over their values becomes on its way into the step
+                    lr * m_hat / (sqrt(v_hat) + eps).
+    Away from cancellation the excess terms vanish and these are |m'|-, v'- and max(|p|, step)-relative."""
     f32 = lambda x: float(np.float32(x))
     b1, b2, lr, eps = f32(hp["beta1"]), f32(hp["beta2"]), f32(hp["lr"]), f32(hp["eps"])
     t = int(hp["step"])
-    gs = np.abs(ref["scale"] * ref["G"])
-    floor_m = np.maximum(b1 * np.abs(inp_m.astype(np.float64)), (1 - b1) * gs)
-    denom = np.sqrt(ref["v"] / (1.0 - b2 ** t)) + eps
-    through_m = abs(lr) * (floor_m / (1.0 - b1 ** t)) / np.where(denom > 0, denom, 1.0)
-    return np.maximum(np.abs(inp_p.astype(np.float64)), np.abs(ref["p"] - inp_p)) + through_m
+    bc1, bc2 = 1.0 - b1 ** t, 1.0 - b2 ** t
+    gp = np.abs(ref["scale"] * ref["G"])
+    gfl = gp if abs_g is None else np.maximum(gp, np.abs(ref["scale"]) * abs_g)
+    floor_m = np.maximum(b1 * np.abs(inp_m.astype(np.float64)), (1 - b1) * gfl)
+    floor_v = ref["v"] + 2.0 * (1 - b2) * gp * (gfl - gp)
+    denom = np.sqrt(ref["v"] / bc2) + eps
+    denom = np.where(denom > 0, denom, 1.0)
+    through_m = abs(lr) * (np.maximum(floor_m - np.abs(ref["m"]), 0.0) / bc1) / denom
+    u = np.abs(ref["m"] / bc1) / denom
+    with np.errstate(divide="ignore", invalid="ignore"):
+        excess_v = np.where(ref["v"] > 0, (floor_v - ref["v"]) / ref["v"], 0.0)
+    through_v = abs(lr) * u * 0.5 * excess_v
+    floor_p = np.maximum(np.abs(inp_p.astype(np.float64)), np.abs(ref["p"] - inp_p)) + through_m + through_v
+    return floor_p, floor_m, floor_v
 
 
-def check_state(got_p, got_m, got_v, ref: dict, inp_p, inp_m, hp: dict, tol: float = REL_TOL):
-    """fp32 master/m/v against the oracle's doubles.  The floor of each denominator is the
-    largest operand of the final addition: |p| and the applied step for the master (plus the first
-    moment's floor carried into the step, see master_floor), beta1 |m| and (1-beta1)|g'| for the first
-    moment; the second moment has no cancellation."""
-    b1 = float(np.float32(hp["beta1"]))
-    gs = np.abs(ref["scale"] * ref["G"])
-    floor_p = master_floor(ref, inp_p, inp_m, hp)
-    floor_m = np.maximum(b1 * np.abs(inp_m.astype(np.float64)), (1 - b1) * gs)
+def master_floor(ref: dict, inp_p, inp_m, hp: dict, abs_g=None) -> np.ndarray:
+    return floors(ref, inp_p, inp_m, hp, abs_g)[0]
+
+
+def check_state(got_p, got_m, got_v, ref: dict, inp_p, inp_m, hp: dict, tol: float = REL_TOL, abs_g=None):
+    """fp32 master/m/v against the oracle's doubles, each relative to its floor (see floors)."""
+    floor_p, floor_m, floor_v = floors(ref, inp_p, inp_m, hp, abs_g)
     ep = rel_err_scaled(got_p, ref["p"], floor_p)
     em = rel_err_scaled(got_m, ref["m"], floor_m)
-    ev = rel_err_scaled(got_v, ref["v"], np.zeros(1))
+    ev = rel_err_scaled(got_v, ref["v"], floor_v)
     stats = dict(max_p=float(ep.max(initial=0)), max_m=float(em.max(initial=0)), max_v=float(ev.max(initial=0)))
     # the strict element-wise figure, reported for audit
     with np.errstate(divide="ignore", invalid="ignore"):
@@ -118,7 +139,7 @@ def _bf16_neighbours(bits: np.ndarray):
 
 
 def check_bf16(got_bits: np.ndarray, ref: dict, inp_p: np.ndarray, tol: float = REL_TOL, inp_m=None,
-               hp=None) -> int:
+               hp=None, abs_g=None) -> int:
     """bf16 parameters: identical to bf16(fp32(p')) of the oracle, except where the fp32 tolerance
     lets p' round elsewhere: with delta = `tol` * max(|p'|, |p|, |p' - p|) (check_state's tolerance
     for the master; with inp_m and hp given, master_floor's), the shipped value must be the rounding of some value in [p' - delta, p' + delta],
@@ -136,7 +157,7 @@ def check_bf16(got_bits: np.ndarray, ref: dict, inp_p: np.ndarray, tol: float = 
     pp = ref["p"][bad]
     p_in = inp_p[bad].astype(np.float64)
     if inp_m is not None and hp is not None:
-        floor = np.maximum(np.abs(ref["p"]), master_floor(ref, inp_p, inp_m, hp))[bad]
+        floor = np.maximum(np.abs(ref["p"]), master_floor(ref, inp_p, inp_m, hp, abs_g))[bad]
     else:
         floor = np.maximum(np.abs(pp), np.maximum(np.abs(p_in), np.abs(pp - p_in)))
     delta = tol * floor

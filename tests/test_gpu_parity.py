@@ -260,9 +260,10 @@ def _oracle_step(inp, hp):
 def _check_all(got, ref, inp, hp):
     p, m, v, bits, S = got
     assert abs(S - ref["sqnorm"]) <= H.REL_TOL * ref["sqnorm"]
-    stats = H.check_state(p, m, v, ref, inp.p, inp.m, hp)
+    abs_g = H.abs_partials(inp.partials)
+    stats = H.check_state(p, m, v, ref, inp.p, inp.m, hp, abs_g=abs_g)
     if bits is not None:
-        stats["bf16_boundary_mismatches"] = H.check_bf16(bits, ref, inp.p, inp_m=inp.m, hp=hp)
+        stats["bf16_boundary_mismatches"] = H.check_bf16(bits, ref, inp.p, inp_m=inp.m, hp=hp, abs_g=abs_g)
         assert np.array_equal(bits, oracle.cast(p))        # the cast of the GPU's own fp32 is bit-exact
         assert stats["bf16_boundary_mismatches"] <= max(3, 1e-4 * p.size)
     return stats

@@ -105,12 +105,13 @@ def test_random_cases_against_oracle(B, torch_mod):
         inp, hp, ref, (p, m, v, bits, S) = _run(B, torch_mod, c)
         # the two-micro-batch sum rounds once more in fp32 than the oracle's exact sum: still far inside the bar
         assert abs(S - ref["sqnorm"]) <= H.REL_TOL * ref["sqnorm"], (c, S, ref["sqnorm"])
-        stats = H.check_state(p, m, v, ref, inp.p, inp.m, hp)
+        abs_g = H.abs_partials(inp.partials)
+        stats = H.check_state(p, m, v, ref, inp.p, inp.m, hp, abs_g=abs_g)
         for key in worst:
             worst[key] = max(worst[key], stats[key])
         if bits is not None:
             assert np.array_equal(bits, oracle.cast(p)), c
-            assert H.check_bf16(bits, ref, inp.p, inp_m=inp.m, hp=hp) <= max(3, 1e-4 * p.size), c
+            assert H.check_bf16(bits, ref, inp.p, inp_m=inp.m, hp=hp, abs_g=abs_g) <= max(3, 1e-4 * p.size), c
     print("worst scaled relative errors over the sweep:", worst)
 
 
@@ -163,10 +164,11 @@ def test_random_inter_tensor_models(B, torch_mod):
             ref = oracle.step(inp.partials, inp.p, inp.m, inp.v, threads=1, **hp)
             assert abs(float(d_s.item()) - ref["sqnorm"]) <= H.REL_TOL * ref["sqnorm"]
             p = dp.cpu().numpy()
-            H.check_state(p, dm.cpu().numpy(), dv.cpu().numpy(), ref, inp.p, inp.m, hp)
+            abs_g = H.abs_partials(inp.partials)
+            H.check_state(p, dm.cpu().numpy(), dv.cpu().numpy(), ref, inp.p, inp.m, hp, abs_g=abs_g)
             mine = oracle.select(out_bits, segs)
             assert np.array_equal(mine, oracle.cast(p))
-            H.check_bf16(mine, ref, inp.p, inp_m=inp.m, hp=hp)
+            H.check_bf16(mine, ref, inp.p, inp_m=inp.m, hp=hp, abs_g=abs_g)
             # the same step through the rank's compact fp32 gradient, accumulated over two "micro-batches"
             g_local = torch.full((local,), 7.0, dtype=torch.float32, device="cuda")
             half = max(1, k // 2)
@@ -182,7 +184,7 @@ def test_random_inter_tensor_models(B, torch_mod):
             torch.cuda.synchronize()
             assert abs(float(d_s2.item()) - ref["sqnorm"]) <= H.REL_TOL * ref["sqnorm"]
             p2 = dp2.cpu().numpy()
-            H.check_state(p2, dm2.cpu().numpy(), dv2.cpu().numpy(), ref, inp.p, inp.m, hp)
+            H.check_state(p2, dm2.cpu().numpy(), dv2.cpu().numpy(), ref, inp.p, inp.m, hp, abs_g=abs_g)
             bits2 = H.dev_bits(out2)
             assert np.all(bits2[elem_owner != rank] == 0x5A5A)
             assert np.array_equal(oracle.select(bits2, segs), oracle.cast(p2))
