@@ -138,6 +138,14 @@ int amsp_grad_sqnorm(const uint16_t *const *partials, uint32_t k, const float *g
  *       (no host synchronisation between the norm pass and the update), times grad_scale;
  *   d_total_sqnorm == NULL: scale = grad_scale (max_norm and clip_eps unused).
  * grad_scale is where a caller folds 1/(number of micro-batches or ranks) or a loss scale.
+ * The arithmetic is fp32, every operation correctly rounded once, in this order (fma = fused
+ * multiply-add; 1 - beta and 1/(1 - beta^step) are formed in double on the host and rounded to fp32):
+ *   gs = scale * g
+ *   m  = fma(beta1, m, (1 - beta1) * gs)
+ *   v  = fma(beta2, v, ((1 - beta2) * gs) * gs)
+ *   u  = (m * (1/(1 - beta1^step))) / (sqrt(v * (1/(1 - beta2^step))) + eps)
+ *   p  = fma(-lr, fma(weight_decay, p, u), p)
+ * so results are reproducible bit for bit from the inputs on any implementation of these operations.
  */
 typedef struct amsp_adamw_hparams {
     float lr;

@@ -569,3 +569,58 @@ def test_non_finite_gradients_propagate_like_the_oracle(B, torch_mod, poison):
     sub = {key: (val[good] if isinstance(val, np.ndarray) else val) for key, val in ref.items()}
     H.check_state(p[good], m[good], v[good], sub, inp.p[good], inp.m[good], hp)
     H.check_bf16(bits[good], sub, inp.p[good], inp_m=inp.m[good], hp=hp)
+
+
+# ------------------------------------------------------------------ the stated fp32 operation order, bit for bit
+def _emulate_step_f32(partials, p, m, v, sqnorm, hp):
+    """The update as the kernels are documented to compute it, in numpy float32: sequential fp32 sum
+    of the partials, scale from the squared norm in double, then per element
+        gs = scale*g;  m = fma(b1, m, (1-b1)*gs);  v = fma(b2, v, ((1-b2)*gs)*gs)
+        u = (m*rbc1) / (sqrt(v*rbc2) + eps);  p = fma(-lr, fma(wd, p, u), p)
+    with every operation correctly rounded once (fma through float64: the product of two float32 is
+    exact there).  Not the oracle: a model of the device arithmetic, for a bit-for-bit comparison."""
+    f32 = np.float32
+
+    def fma(a, b, c):
+        return (np.asarray(a, dtype=np.float64) * np.asarray(b, dtype=np.float64)
+                + np.asarray(c, dtype=np.float64)).astype(f32)
+
+    g = synth.bf16_bits_to_f32(partials[0]).astype(f32)
+    for q in partials[1:]:
+        g = (g + synth.bf16_bits_to_f32(q)).astype(f32)
+    b1, b2, lr, eps, wd = (f32(hp[key]) for key in ("beta1", "beta2", "lr", "eps", "weight_decay"))
+    scale = 1.0
+    if hp["max_norm"] > 0:
+        clip = float(f32(hp["max_norm"])) / (np.sqrt(sqnorm) + float(f32(hp["clip_eps"])))
+        scale = min(1.0, clip)
+    scale = f32(scale)
+    omb1, omb2 = f32(1.0 - float(b1)), f32(1.0 - float(b2))
+    rbc1 = f32(1.0 / (1.0 - float(b1) ** hp["step"]))
+    rbc2 = f32(1.0 / (1.0 - float(b2) ** hp["step"]))
+    gs = (scale * g).astype(f32)
+    m1 = fma(b1, m, (omb1 * gs).astype(f32))
+    v1 = fma(b2, v, ((omb2 * gs).astype(f32) * gs).astype(f32))
+    den = (np.sqrt((v1 * rbc2).astype(f32)).astype(f32) + eps).astype(f32)
+    u = ((m1 * rbc1).astype(f32) / den).astype(f32)
+    p1 = fma(-lr, fma(wd, p, u), p)
+    return p1, m1, v1
+
+
+@pytest.mark.parametrize("k,step,max_norm", [(1, 1, 0.0), (8, 10, 0.05), (16, 1000, 1.0), (32, 3, 1e9)])
+def test_fp32_results_follow_the_stated_operation_order(B, torch_mod, k, step, max_norm):
+    """master/m/v from the device equal a float32 model of the documented operation order bit for
+    bit (no reassociation, no contraction beyond the stated fused multiply-adds, correctly rounded
+    divide and square root), up to the model's own double rounding in its float64 fma (at most a
+    handful of last-bit differences in 300,000 elements)."""
+    w = workloads.get(0)
+    n = 300_007
+    inp = H.host_inputs(w, 7_000_000, n, k=k)
+    hp = H.hparams_of(w, max_norm=max_norm, step=step)
+    p, m, v, bits, S = _run_step(B, torch_mod, w, inp, n, hp, shift=1)
+    ep, em, ev = _emulate_step_f32(inp.partials, inp.p, inp.m, inp.v, S, hp)
+    for name, got, want in (("p", p, ep), ("m", m, em), ("v", v, ev)):
+        diff = np.nonzero(got.view(np.uint32) != want.view(np.uint32))[0]
+        assert diff.size <= 4, (name, diff.size, diff[:5])
+        if diff.size:
+            ulps = np.abs(got.view(np.int32)[diff].astype(np.int64) - want.view(np.int32)[diff].astype(np.int64))
+            assert ulps.max() <= 1, (name, ulps)
