@@ -800,6 +800,39 @@ __global__ void __launch_bounds__(kThreads) cast_fp8_kernel(const float *__restr
     }
 }
 
+// Step 1 for short segments, 32 to a launch: out_local[local + i] (=|+=) sum_j partials[j][flat + i].
+__global__ void __launch_bounds__(kRwThreads) reduce_table_kernel(PartialPtrs pp, int k, float *__restrict__ out,
+                                                                  int accumulate, RangeTable t) {
+    constexpr int VEC = kVecRW;
+    uint32_t r = 0;
+#pragma unroll
+    for (int i = 1; i < kMaxTableRanges; ++i) r += blockIdx.x >= t.first_block[i] ? 1u : 0u;
+    const uint32_t lb = blockIdx.x - t.first_block[r];
+    const uint64_t len = t.len[r], flat = t.flat_off[r], local = t.local_off[r];
+    const uint32_t head = t.head[r];
+    const uint64_t nvec = (len - head) / VEC;
+    const uint32_t tail = (uint32_t)(len - head - nvec * VEC);
+    const uint64_t vi = (uint64_t)lb * kRwThreads + threadIdx.x;
+    if (vi < nvec) {
+        const uint64_t i = head + vi * VEC;
+        float g[VEC], o[VEC];
+        if (accumulate) ld_f32<VEC>(out, local + i, o);
+        grad_vec<-1, VEC>(pp, k, nullptr, flat + i, g);
+        if (accumulate) {
+#pragma unroll
+            for (int c = 0; c < VEC; ++c) g[c] = o[c] + g[c];
+        }
+        st_f32<VEC>(out, local + i, g);
+    }
+    if (lb == 0)
+        for (uint32_t e = threadIdx.x; e < head + tail; e += kRwThreads) {
+            const uint64_t i = e < head ? (uint64_t)e : (uint64_t)head + nvec * VEC + (e - head);
+            float g1 = grad1<-1>(pp, k, nullptr, flat + i);
+            if (accumulate) g1 = out[local + i] + g1;
+            out[local + i] = g1;
+        }
+}
+
 // The FP8 payload of short segments, 32 to a launch like the update above.  CAST = false: the largest
 // |x| of each range into slots[segment] (integer atomic max, sent only when it beats the word's current
 // value); CAST = true: codes = e4m3(x * d_scale[segment]) at the range's flat position.
@@ -1590,15 +1623,53 @@ int amsp_reduce_grad_segments(const uint16_t *const *partials_flat, uint32_t k, 
         if (too_long(segments[i].length, 0)) return AMSP_EINVAL;
     }
     if (misaligned(grad_f32_local, 4)) return AMSP_EALIGN;
+    hipStream_t hs = (hipStream_t)stream;
+    RangeTable table;
+    uint32_t in_table = 0, table_blocks = 0;
+    auto flush_table = [&]() -> int {
+        if (in_table == 0) return AMSP_OK;
+        for (uint32_t j = in_table; j < (uint32_t)kMaxTableRanges; ++j) {
+            table.first_block[j] = 0xFFFFFFFFu;
+            table.head[j] = 0; table.segment[j] = 0; table.flat_off[j] = 0; table.local_off[j] = 0; table.len[j] = 0;
+        }
+        const unsigned lds = occupancy_lds(8 * k + (accumulate ? 16 : 0), reduce_target());
+        clear_stale_error();
+        hipLaunchKernelGGL(reduce_table_kernel, dim3(table_blocks), dim3(kRwThreads), lds, hs, pp, (int)k,
+                           grad_f32_local, accumulate, table);
+        in_table = 0;
+        table_blocks = 0;
+        return launched();
+    };
     for (uint32_t i = 0; i < num_segments; ++i) {
         const amsp_segment &g = segments[i];
         if (g.length == 0) continue;
         PartialPtrs q = offset_partials(pp, k, g.flat_offset);
+        if (g.length < kShortSegment) {
+            Stream16 st[AMSP_MAX_K + 1];
+            int ns = add_partial_streams(st, 0, q, k);
+            st[ns++] = Stream16{grad_f32_local + g.local_offset, 4};
+            const Span sp = make_span(g.length, st, ns, kVecRW);
+            if (sp.vectorised || g.length <= 16 * kRwThreads) {
+                table.first_block[in_table] = table_blocks;
+                table.head[in_table] = sp.vectorised ? sp.head : (uint32_t)g.length;
+                table.segment[in_table] = i;
+                table.flat_off[in_table] = g.flat_offset;
+                table.local_off[in_table] = g.local_offset;
+                table.len[in_table] = g.length;
+                const uint64_t blocks = sp.vectorised ? (sp.nvec + kRwThreads - 1) / kRwThreads : 0;
+                table_blocks += (uint32_t)(blocks ? blocks : 1);
+                if (++in_table == (uint32_t)kMaxTableRanges) {
+                    rc = flush_table();
+                    if (rc != AMSP_OK) return rc;
+                }
+                continue;
+            }
+        }
         rc = amsp_reduce_grad_shard(q.p, k, g.length, 0, grad_f32_local + g.local_offset, accumulate, nullptr, 0,
                                     nullptr, 0, stream);
         if (rc != AMSP_OK) return rc;
     }
-    return AMSP_OK;
+    return flush_table();
 }
 
 size_t amsp_amax_workspace_bytes(uint32_t num_segments) {
