@@ -1265,6 +1265,38 @@ struct NormRanges {
     }
 };
 
+// Collects short segments for one table launch.  A segment qualifies when it is shorter than
+// kShortSegment and either has a common vector phase or is so short that the edge loop of one wave
+// takes all of it; everything else gets a launch of its own.
+struct TableBuilder {
+    RangeTable table;
+    uint32_t count = 0, blocks = 0;
+
+    static bool takes(const amsp_segment &g, const Span &sp) {
+        return g.length < kShortSegment && (sp.vectorised || g.length <= 16 * (uint64_t)kRwThreads);
+    }
+    // Adds segment `index`; true when the table is now full and must be launched.
+    bool add(uint32_t index, const amsp_segment &g, const Span &sp) {
+        table.first_block[count] = blocks;
+        table.head[count] = sp.vectorised ? sp.head : (uint32_t)g.length;
+        table.segment[count] = index;
+        table.flat_off[count] = g.flat_offset;
+        table.local_off[count] = g.local_offset;
+        table.len[count] = g.length;
+        const uint64_t b = sp.vectorised ? (sp.nvec + kRwThreads - 1) / kRwThreads : 0;
+        blocks += (uint32_t)(b ? b : 1);
+        return ++count == (uint32_t)kMaxTableRanges;
+    }
+    // Marks the unused entries; call before a launch, reset() after it.
+    void pad() {
+        for (uint32_t j = count; j < (uint32_t)kMaxTableRanges; ++j) {
+            table.first_block[j] = 0xFFFFFFFFu;
+            table.head[j] = 0; table.segment[j] = 0; table.flat_off[j] = 0; table.local_off[j] = 0; table.len[j] = 0;
+        }
+    }
+    void reset() { count = 0; blocks = 0; }
+};
+
 }  // namespace
 
 // ================================================================ C ABI
@@ -1624,20 +1656,15 @@ int amsp_reduce_grad_segments(const uint16_t *const *partials_flat, uint32_t k, 
     }
     if (misaligned(grad_f32_local, 4)) return AMSP_EALIGN;
     hipStream_t hs = (hipStream_t)stream;
-    RangeTable table;
-    uint32_t in_table = 0, table_blocks = 0;
+    TableBuilder tb;
     auto flush_table = [&]() -> int {
-        if (in_table == 0) return AMSP_OK;
-        for (uint32_t j = in_table; j < (uint32_t)kMaxTableRanges; ++j) {
-            table.first_block[j] = 0xFFFFFFFFu;
-            table.head[j] = 0; table.segment[j] = 0; table.flat_off[j] = 0; table.local_off[j] = 0; table.len[j] = 0;
-        }
+        if (tb.count == 0) return AMSP_OK;
+        tb.pad();
         const unsigned lds = occupancy_lds(8 * k + (accumulate ? 16 : 0), reduce_target());
         clear_stale_error();
-        hipLaunchKernelGGL(reduce_table_kernel, dim3(table_blocks), dim3(kRwThreads), lds, hs, pp, (int)k,
-                           grad_f32_local, accumulate, table);
-        in_table = 0;
-        table_blocks = 0;
+        hipLaunchKernelGGL(reduce_table_kernel, dim3(tb.blocks), dim3(kRwThreads), lds, hs, pp, (int)k,
+                           grad_f32_local, accumulate, tb.table);
+        tb.reset();
         return launched();
     };
     for (uint32_t i = 0; i < num_segments; ++i) {
@@ -1649,16 +1676,8 @@ int amsp_reduce_grad_segments(const uint16_t *const *partials_flat, uint32_t k, 
             int ns = add_partial_streams(st, 0, q, k);
             st[ns++] = Stream16{grad_f32_local + g.local_offset, 4};
             const Span sp = make_span(g.length, st, ns, kVecRW);
-            if (sp.vectorised || g.length <= 16 * kRwThreads) {
-                table.first_block[in_table] = table_blocks;
-                table.head[in_table] = sp.vectorised ? sp.head : (uint32_t)g.length;
-                table.segment[in_table] = i;
-                table.flat_off[in_table] = g.flat_offset;
-                table.local_off[in_table] = g.local_offset;
-                table.len[in_table] = g.length;
-                const uint64_t blocks = sp.vectorised ? (sp.nvec + kRwThreads - 1) / kRwThreads : 0;
-                table_blocks += (uint32_t)(blocks ? blocks : 1);
-                if (++in_table == (uint32_t)kMaxTableRanges) {
+            if (TableBuilder::takes(g, sp)) {
+                if (tb.add(i, g, sp)) {
                     rc = flush_table();
                     if (rc != AMSP_OK) return rc;
                 }
@@ -1723,29 +1742,24 @@ int amsp_adamw_step_segments(const uint16_t *const *partials_flat, uint32_t k, c
     }
     // Segments shorter than kShortSegment share launches, up to kMaxTableRanges each (a launch costs more
     // than such a segment's traffic); the others get a launch of their own with every k loaded at once.
-    RangeTable table;
-    uint32_t in_table = 0, table_blocks = 0;
+    TableBuilder tb;
     auto flush_table = [&]() -> int {
-        if (in_table == 0) return AMSP_OK;
-        for (uint32_t j = in_table; j < (uint32_t)kMaxTableRanges; ++j) {
-            table.first_block[j] = 0xFFFFFFFFu;
-            table.head[j] = 0; table.segment[j] = 0; table.flat_off[j] = 0; table.local_off[j] = 0; table.len[j] = 0;
-        }
+        if (tb.count == 0) return AMSP_OK;
+        tb.pad();
         const unsigned lane_bytes = (k != 0 ? 8 * k : 16) + 48;
         const unsigned lds = occupancy_lds(lane_bytes, adamw_target(lane_bytes));
-        const dim3 grid(table_blocks), block(kRwThreads);
+        const dim3 grid(tb.blocks), block(kRwThreads);
         clear_stale_error();
 #define AMSP_LAUNCH_TABLE(KV, B16, AM)                                                                          \
         hipLaunchKernelGGL((adamw_table_kernel<KV, B16, AM>), grid, block, lds, hs, pp, (int)k, grad_f32_local, \
-                           master_local, exp_avg_local, exp_avg_sq_local, param_bf16_flat, words, c, table)
+                           master_local, exp_avg_local, exp_avg_sq_local, param_bf16_flat, words, c, tb.table)
 #define AMSP_LAUNCH_TABLE_K(KV)                                                                                  \
         if (param_bf16_flat) { if (words) AMSP_LAUNCH_TABLE(KV, true, true); else AMSP_LAUNCH_TABLE(KV, true, false); } \
         else { if (words) AMSP_LAUNCH_TABLE(KV, false, true); else AMSP_LAUNCH_TABLE(KV, false, false); }
         if (k == 0) { AMSP_LAUNCH_TABLE_K(0) } else { AMSP_LAUNCH_TABLE_K(-1) }
 #undef AMSP_LAUNCH_TABLE_K
 #undef AMSP_LAUNCH_TABLE
-        in_table = 0;
-        table_blocks = 0;
+        tb.reset();
         return launched();
     };
     for (uint32_t i = 0; i < num_segments; ++i) {
@@ -1762,17 +1776,8 @@ int amsp_adamw_step_segments(const uint16_t *const *partials_flat, uint32_t k, c
             st[ns++] = Stream16{exp_avg_sq_local + g.local_offset, 4};
             if (param_bf16_flat) st[ns++] = Stream16{param_bf16_flat + g.flat_offset, 2};
             const Span sp = make_span(g.length, st, ns, kVecRW);
-            // no common phase: still fine for the table when the edge loop of one wave can take it all
-            if (sp.vectorised || g.length <= 16 * kRwThreads) {
-                table.first_block[in_table] = table_blocks;
-                table.head[in_table] = sp.vectorised ? sp.head : (uint32_t)g.length;
-                table.segment[in_table] = i;
-                table.flat_off[in_table] = g.flat_offset;
-                table.local_off[in_table] = g.local_offset;
-                table.len[in_table] = g.length;
-                const uint64_t blocks = sp.vectorised ? (sp.nvec + kRwThreads - 1) / kRwThreads : 0;
-                table_blocks += (uint32_t)(blocks ? blocks : 1);
-                if (++in_table == (uint32_t)kMaxTableRanges) {
+            if (TableBuilder::takes(g, sp)) {
+                if (tb.add(i, g, sp)) {
                     rc = flush_table();
                     if (rc != AMSP_OK) return rc;
                 }
@@ -1823,40 +1828,27 @@ int amsp_fp8_payload_segments(const float *master_local, uint64_t local_elems, c
     uint32_t *slots = reinterpret_cast<uint32_t *>(d_amax);
     clear_stale_error();
     // short segments share launches (tables of kMaxTableRanges); `cast` selects the pass
-    RangeTable table;
-    uint32_t in_table = 0, table_blocks = 0;
+    TableBuilder tb;
     auto flush_table = [&](bool cast) -> int {
-        if (in_table == 0) return AMSP_OK;
-        for (uint32_t j = in_table; j < (uint32_t)kMaxTableRanges; ++j) {
-            table.first_block[j] = 0xFFFFFFFFu;
-            table.head[j] = 0; table.segment[j] = 0; table.flat_off[j] = 0; table.local_off[j] = 0; table.len[j] = 0;
-        }
+        if (tb.count == 0) return AMSP_OK;
+        tb.pad();
         if (cast)
-            hipLaunchKernelGGL((fp8_table_kernel<true>), dim3(table_blocks), dim3(kRwThreads), 0, hs, master_local,
-                               d_scale, param_fp8_flat, slots, table);
+            hipLaunchKernelGGL((fp8_table_kernel<true>), dim3(tb.blocks), dim3(kRwThreads), 0, hs, master_local,
+                               d_scale, param_fp8_flat, slots, tb.table);
         else
-            hipLaunchKernelGGL((fp8_table_kernel<false>), dim3(table_blocks), dim3(kRwThreads), 0, hs, master_local,
-                               d_scale, param_fp8_flat, slots, table);
-        in_table = 0;
-        table_blocks = 0;
+            hipLaunchKernelGGL((fp8_table_kernel<false>), dim3(tb.blocks), dim3(kRwThreads), 0, hs, master_local,
+                               d_scale, param_fp8_flat, slots, tb.table);
+        tb.reset();
         return launched();
     };
-    // true when segment i went into the table (short, and vectorisable or tiny)
+    // true when segment i went into the table
     auto tabled = [&](uint32_t i, bool cast, int *rc_out) -> bool {
         const amsp_segment &g = segments[i];
         if (g.length >= kShortSegment) return false;
         Stream16 st[2] = {{master_local + g.local_offset, 4}, {param_fp8_flat + g.flat_offset, 1}};
         const Span sp = make_span(g.length, st, cast ? 2 : 1, 4);
-        if (!sp.vectorised && g.length > 16 * kRwThreads) return false;
-        table.first_block[in_table] = table_blocks;
-        table.head[in_table] = sp.vectorised ? sp.head : (uint32_t)g.length;
-        table.segment[in_table] = i;
-        table.flat_off[in_table] = g.flat_offset;
-        table.local_off[in_table] = g.local_offset;
-        table.len[in_table] = g.length;
-        const uint64_t blocks = sp.vectorised ? (sp.nvec + kRwThreads - 1) / kRwThreads : 0;
-        table_blocks += (uint32_t)(blocks ? blocks : 1);
-        *rc_out = ++in_table == (uint32_t)kMaxTableRanges ? flush_table(cast) : (int)AMSP_OK;
+        if (!TableBuilder::takes(g, sp)) return false;
+        *rc_out = tb.add(i, g, sp) ? flush_table(cast) : (int)AMSP_OK;
         return true;
     };
     if (!amax_ready) {
