@@ -133,11 +133,6 @@ def check_state(got_p, got_m, got_v, ref: dict, inp_p, inp_m, hp: dict, tol: flo
     return stats
 
 
-def _bf16_neighbours(bits: np.ndarray):
-    f = synth.bf16_bits_to_f32(bits).astype(np.float64)
-    return f
-
-
 def check_bf16(got_bits: np.ndarray, ref: dict, inp_p: np.ndarray, tol: float = REL_TOL, inp_m=None,
                hp=None, abs_g=None) -> int:
     """bf16 parameters: identical to bf16(fp32(p')) of the oracle, except where the fp32 tolerance
