@@ -100,8 +100,6 @@ def test_planted_mistake_is_caught(name, old, new, golden_dir):
 
 
 # --------------------------------------------------------------------------- the planner oracle
-import importlib.util
-import sys
 import types
 
 import test_planner as planner_pins
