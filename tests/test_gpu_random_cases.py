@@ -207,3 +207,58 @@ def test_random_inter_tensor_models(B, torch_mod):
             d_scale_b = torch.zeros(len(segs), dtype=torch.float32, device="cuda")
             B.amsp_fp8_payload_segments(dp, local, segs, total, fp8b, d_amax_fused, d_scale_b, amax_ready=True)
             assert torch.equal(fp8b, fp8) and torch.equal(d_scale_b, d_scale)
+
+
+def test_shard_of_thousands_of_small_tensors(B, torch_mod):
+    """3,000 tensors of 1 ... 20,000 elements over two ranks: ~900 segments per rank after neighbours merge, far more than
+    one launch's table of short segments holds, with a few long tensors in between that get launches
+    of their own.  Partition, segments, norm, update, write-back and FP8 payload against the oracle."""
+    torch = torch_mod
+    rng = np.random.default_rng(20231107)
+    w = workloads.get(0)
+    sizes = [int(x) for x in rng.integers(1, 20_000, size=3000)]
+    for pos in (17, 1500, 2999):
+        sizes[pos] = 1_200_000 + pos                          # longer than a short segment: own launches
+    total, s, k = sum(sizes), 2, 2
+    owner = B.amsp_partition_tensors(sizes, s)
+    assert owner == oracle.partition_tensors(sizes, s)
+    elem_owner = np.repeat(np.array(owner), sizes)
+    flat = H.host_inputs(w, 123_456_789, total, k=k, threads=4)
+    dparts = [H.to_dev_bf16(g) for g in flat.partials]
+    ws = torch.empty(B.amsp_workspace_bytes() // 8, dtype=torch.float64, device="cuda")
+    hp = H.hparams_of(w, max_norm=0.5)
+    for rank in range(s):
+        segs, local = B.amsp_owned_segments(sizes, owner, rank)
+        assert segs == oracle.owned_segments(sizes, owner, rank) and len(segs) > 500
+        print("rank", rank, "segments", len(segs), "elements", local, flush=True)
+        inp = H.HostInputs([oracle.select(g, segs) for g in flat.partials], oracle.select(flat.p, segs),
+                           oracle.select(flat.m, segs), oracle.select(flat.v, segs))
+        ref = oracle.step(inp.partials, inp.p, inp.m, inp.v, threads=4, **hp)
+        marshalled = B.marshal_segments(segs)
+        dp, dm, dv = H.to_dev_f32(inp.p), H.to_dev_f32(inp.m), H.to_dev_f32(inp.v)
+        out = torch.full((total,), 0x5A5A, dtype=torch.int16, device="cuda")
+        d_s = torch.full((1,), -3.0, dtype=torch.float64, device="cuda")
+        d_amax = torch.full((len(segs),), -1.0, dtype=torch.float32, device="cuda")
+        amax_ws = torch.empty(B.amsp_amax_workspace_bytes(len(segs)) // 4, dtype=torch.int32, device="cuda")
+        B.amsp_grad_sqnorm_segments(dparts, total, marshalled, d_s, ws)
+        B.amsp_adamw_step_segments(dparts, total, marshalled, local, dp, dm, dv, out,
+                                   B.AdamWHparams(d_total_sqnorm=d_s, **hp), d_amax=d_amax, amax_workspace=amax_ws)
+        torch.cuda.synchronize()
+        assert abs(float(d_s.item()) - ref["sqnorm"]) <= H.REL_TOL * ref["sqnorm"]
+        p = dp.cpu().numpy()
+        abs_g = H.abs_partials(inp.partials)
+        H.check_state(p, dm.cpu().numpy(), dv.cpu().numpy(), ref, inp.p, inp.m, hp, abs_g=abs_g)
+        out_bits = H.dev_bits(out)
+        assert np.all(out_bits[elem_owner != rank] == 0x5A5A)
+        mine = oracle.select(out_bits, segs)
+        assert np.array_equal(mine, oracle.cast(p))
+        assert H.check_bf16(mine, ref, inp.p, inp_m=inp.m, hp=hp, abs_g=abs_g) <= max(3, 1e-4 * p.size)
+        codes, scales, amaxes = oracle.fp8_payload_segments(p, segs)
+        assert d_amax.cpu().numpy().tolist() == [float(np.float32(a)) for a in amaxes]
+        fp8 = torch.full((total,), 0xA5, dtype=torch.uint8, device="cuda")
+        d_scale = torch.zeros(len(segs), dtype=torch.float32, device="cuda")
+        B.amsp_fp8_payload_segments(dp, local, marshalled, total, fp8, d_amax, d_scale, amax_ready=True)
+        got = fp8.cpu().numpy()
+        assert np.array_equal(oracle.select(got, segs), codes)
+        assert np.all(got[elem_owner != rank] == 0xA5)
+        assert d_scale.cpu().numpy().tolist() == [float(np.float32(x)) for x in scales]
