@@ -237,3 +237,17 @@ int main(void) {
     out = subprocess.run([str(exe)], capture_output=True, text=True, timeout=60)
     assert out.returncode == 0, (out.returncode, out.stderr[-500:])
     assert "workspace" in out.stdout
+
+
+def test_library_sources_keep_their_promises():
+    """The header promises that no entry point allocates, frees or synchronises, and the kernels are
+    built without packed-fp32 instructions: checked on the sources the library is built from."""
+    csrc = os.path.join(ROOT, "paper_2311_00257_amd", "csrc")
+    text = ""
+    for name in ("amsp_kernels.hip", "amsp_device.h", "amsp_geometry.h", "amsp_planner.cpp"):
+        text += open(os.path.join(csrc, name)).read()
+    for banned in ("hipMalloc", "hipFree", "hipMemset", "hipMemcpy", "hipDeviceSynchronize", "hipStreamSynchronize",
+                   "hipHostRegister", "hipStreamCreate", "hipEventSynchronize"):
+        assert banned not in text, banned
+    flags = open(os.path.join(ROOT, "paper_2311_00257_amd", "build.py")).read()
+    assert '"-target-feature", "-Xclang", "-packed-fp32-ops"' in flags and "gfx950" in flags
