@@ -18,8 +18,10 @@
  * amsp_adamw_step_shard fuses 1 + 3 + 4 in one streaming pass (2k + 26 bytes per element).
  *
  * Conventions, for every function below
- *   - Returns an int status: AMSP_OK (0) or a negative AMSP_E* code.  Never throws, aborts,
- *     allocates or frees.  On an error nothing has been enqueued and outputs are untouched.
+ *   - Returns an int status: AMSP_OK (0) or a negative AMSP_E* code.  Never throws or aborts,
+ *     never allocates, frees or copies device memory and never waits for the device (the two
+ *     host-only helpers amsp_partition_tensors and amsp_plan_sharding use a little host memory
+ *     of their own).  On an error nothing has been enqueued and outputs are untouched.
  *   - "device" pointers are HIP device memory valid on the current device; "host" pointers
  *     are ordinary host memory read during the call only.  The caller owns every buffer.
  *   - Every data pointer addresses the FIRST element of the range to process (the caller
