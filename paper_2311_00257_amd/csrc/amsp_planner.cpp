@@ -66,8 +66,8 @@ bool lex_less(const amsp_plan &x, const amsp_plan &y) {
 
 }  // namespace
 
-extern "C" int amsp_plan_sharding(const amsp_plan_problem *pb, const amsp_bw_sample *table, uint32_t rows,
-                                  amsp_plan *best, uint32_t *feasible_count) {
+static int plan_sharding(const amsp_plan_problem *pb, const amsp_bw_sample *table, uint32_t rows, amsp_plan *best,
+                         uint32_t *feasible_count) {
     if (pb == nullptr || best == nullptr) return AMSP_ENULL;
     if (rows > 0 && table == nullptr) return AMSP_ENULL;
     if (pb->modules_per_layer > 0 && pb->module_params == nullptr) return AMSP_ENULL;
@@ -119,4 +119,15 @@ extern "C" int amsp_plan_sharding(const amsp_plan_problem *pb, const amsp_bw_sam
             }
     if (feasible_count != nullptr) *feasible_count = count;
     return found ? AMSP_OK : AMSP_ENOPLAN;
+}
+
+// Nothing may leave through the C boundary: running out of host memory for the (small) working lists is
+// reported as "no plan".
+extern "C" int amsp_plan_sharding(const amsp_plan_problem *pb, const amsp_bw_sample *table, uint32_t rows,
+                                  amsp_plan *best, uint32_t *feasible_count) {
+    try {
+        return plan_sharding(pb, table, rows, best, feasible_count);
+    } catch (...) {
+        return AMSP_ENOPLAN;
+    }
 }
