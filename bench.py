@@ -91,8 +91,8 @@ def cpu_baseline(w, begin, sample):
 
 
 def alt_step(args, torch, B, w, n, parts, master, exp_avg, exp_avg_sq, param_bf16, d_sqnorm):
-    """The other composition of the same steps, timed after the primary one: amsp_reduce_grad_shard with
-    the norm fused in writes the fp32 gradient (2k + 4 bytes/element), then amsp_adamw_step_shard on that
+    """The other composition of the same steps, timed after the primary one: amsp_reduce_grad_sqnorm_shard
+    writes the fp32 gradient (2k + 4 bytes/element), then amsp_adamw_step_shard on that
     gradient with the bf16 cast (30 bytes/element): 2k + 34 in all instead of 4k + 26."""
     g32 = torch.empty(n, dtype=torch.float32, device="cuda")
     ws = torch.empty(B.amsp_reduce_workspace_bytes(n, w.bucket_elems) // 8, dtype=torch.float64, device="cuda")
@@ -102,7 +102,7 @@ def alt_step(args, torch, B, w, n, parts, master, exp_avg, exp_avg_sq, param_bf1
                             step=t, max_norm=w.max_norm, clip_eps=w.clip_eps, d_total_sqnorm=d_sqnorm)
         if ev:
             ev[0].record()
-        B.amsp_reduce_grad_shard(parts, n, g32, bucket_elems=w.bucket_elems, d_sqnorm=d_sqnorm, workspace=ws)
+        B.amsp_reduce_grad_sqnorm_shard(parts, n, g32, d_sqnorm, ws, bucket_elems=w.bucket_elems)
         if ev:
             ev[1].record()
         B.amsp_adamw_step_shard(None, g32, n, master, exp_avg, exp_avg_sq, param_bf16, hp,

@@ -21,7 +21,13 @@
  *   - Returns an int status: AMSP_OK (0) or a negative AMSP_E* code.  Never throws or aborts,
  *     never allocates, frees or copies device memory and never waits for the device (the two
  *     host-only helpers amsp_partition_tensors and amsp_plan_sharding use a little host memory
- *     of their own).  On an error nothing has been enqueued and outputs are untouched.
+ *     of their own).  Arguments are checked before anything is enqueued: on every error but
+ *     AMSP_EDEVICE nothing has been enqueued and outputs are untouched.  AMSP_EDEVICE (a launch
+ *     the runtime refused) may come after earlier launches of the same call went out (calls that
+ *     take several launches: buckets, segment lists, the norm's finishing pass), so the outputs
+ *     are then undefined.
+ *   - The library keeps no state between calls and reads no environment variables; launch shapes
+ *     are compile-time constants.
  *   - "device" pointers are HIP device memory valid on the current device; "host" pointers
  *     are ordinary host memory read during the call only.  The caller owns every buffer.
  *   - Every data pointer addresses the FIRST element of the range to process (the caller
@@ -90,27 +96,36 @@ int amsp_shard_range(uint64_t total_elems, uint32_t shard_factor, uint32_t rank,
                      uint64_t *begin, uint64_t *end);
 
 /*
- * Step 1 alone: grad_out[i] (=|+=) sum_{j<k} partials[j][i], in fp32, j ascending; optionally with
- * step 2 fused in for callers that keep the fp32 gradient (then the update reads 4 bytes per
- * element instead of re-reading 2k).
+ * Step 1 alone: grad_out[i] (=|+=) sum_{j<k} partials[j][i], in fp32, j ascending: the arithmetic
+ * half of the ReduceScatter / AllReduce-then-select of Sections II-C and IV-C.
  *   partials    host array of k device pointers, each bf16[n]
  *   k           1..AMSP_MAX_K
  *   grad_out    device fp32[n]
  *   accumulate  0: overwrite; 1: add the sum to what grad_out holds (gradient accumulation
  *               over micro-batches, Section IV-C.3)
- *   d_sqnorm    device double or NULL.  Not NULL: *d_sqnorm (=|+=) sum_i grad_out[i]^2 of the
- *               values just written (after `accumulate`), in fp64 in a fixed order, added in
- *               bucket order; sqnorm_accumulate 0 overwrites, 1 adds to the value already there
- *   workspace   device, >= amsp_reduce_workspace_bytes(n, bucket_elems) (about n/256 doubles: the
- *               block sums of every bucket side by side, added once after the last bucket),
- *               8-byte aligned, used only when d_sqnorm != NULL (else may be NULL); no
- *               initialisation needed, clobbered
+ * Errors: AMSP_EINVAL (k == 0, k > AMSP_MAX_K, range too long), AMSP_ENULL, AMSP_EALIGN, AMSP_EDEVICE.
+ */
+int amsp_reduce_grad_shard(const uint16_t *const *partials, uint32_t k, uint64_t n,
+                           uint64_t bucket_elems, float *grad_out, int accumulate, void *stream);
+
+/*
+ * Steps 1 and 2 in one pass, for callers that keep the fp32 gradient anyway (gradient accumulation
+ * over micro-batches, Section IV-C.3): as amsp_reduce_grad_shard, and
+ * *d_sqnorm (=|+=) sum_i grad_out[i]^2 of the values just written (after `accumulate`), in fp64 in a
+ * fixed order, the buckets added in bucket order.  The update then reads 4 bytes per element of
+ * gradient (amsp_adamw_step_shard with k = 0) instead of re-reading the 2k of the partials.
+ *   d_sqnorm           device double, required
+ *   sqnorm_accumulate  0: overwrite; 1: add to the value already there
+ *   workspace          device, >= amsp_reduce_workspace_bytes(n, bucket_elems) (about n/256 doubles:
+ *                      the block sums of every bucket side by side, added once after the last
+ *                      bucket), 8-byte aligned; no initialisation needed, clobbered
+ * Errors: as amsp_reduce_grad_shard, and AMSP_EWORKSPACE.
  */
 size_t amsp_reduce_workspace_bytes(uint64_t n, uint64_t bucket_elems);
-int amsp_reduce_grad_shard(const uint16_t *const *partials, uint32_t k, uint64_t n,
-                           uint64_t bucket_elems, float *grad_out, int accumulate,
-                           double *d_sqnorm, int sqnorm_accumulate,
-                           void *workspace, size_t workspace_bytes, void *stream);
+int amsp_reduce_grad_sqnorm_shard(const uint16_t *const *partials, uint32_t k, uint64_t n,
+                                  uint64_t bucket_elems, float *grad_out, int accumulate,
+                                  double *d_sqnorm, int sqnorm_accumulate,
+                                  void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Step 2: *d_sqnorm (=|+=) sum_i g[i]^2 with g the reduced gradient, accumulated in fp64 in a

@@ -20,7 +20,8 @@ AMSP_OP_ALLGATHER, AMSP_OP_REDUCESCATTER, AMSP_OP_ALLREDUCE, AMSP_OP_BROADCAST =
 AMSP_MAX_K = 32
 
 EXPORTS = ("amsp_status_string", "amsp_workspace_bytes", "amsp_reduce_workspace_bytes",
-           "amsp_amax_workspace_bytes", "amsp_shard_range", "amsp_reduce_grad_shard", "amsp_grad_sqnorm", "amsp_adamw_step_shard", "amsp_cast_param_shard",
+           "amsp_amax_workspace_bytes", "amsp_shard_range", "amsp_reduce_grad_shard", "amsp_grad_sqnorm",
+           "amsp_adamw_step_shard", "amsp_cast_param_shard", "amsp_reduce_grad_sqnorm_shard",
            "amsp_partition_tensors", "amsp_owned_segments", "amsp_reduce_grad_segments", "amsp_grad_sqnorm_segments",
            "amsp_adamw_step_segments", "amsp_cast_param_fp8_shard", "amsp_fp8_payload_segments",
            "amsp_plan_sharding")
@@ -100,7 +101,8 @@ def load() -> ctypes.CDLL:
         lib.amsp_shard_range.argtypes = [u64, u32, u32, ctypes.POINTER(u64), ctypes.POINTER(u64)]
         lib.amsp_reduce_workspace_bytes.argtypes = [u64, u64]
         lib.amsp_reduce_workspace_bytes.restype = ctypes.c_size_t
-        lib.amsp_reduce_grad_shard.argtypes = [vp, u32, u64, u64, vp, ci, vp, ci, vp, ctypes.c_size_t, vp]
+        lib.amsp_reduce_grad_shard.argtypes = [vp, u32, u64, u64, vp, ci, vp]
+        lib.amsp_reduce_grad_sqnorm_shard.argtypes = [vp, u32, u64, u64, vp, ci, vp, ci, vp, ctypes.c_size_t, vp]
         lib.amsp_grad_sqnorm.argtypes = [vp, u32, vp, u64, u64, vp, ci, vp, ctypes.c_size_t, vp]
         lib.amsp_adamw_step_shard.argtypes = [vp, u32, vp, u64, u64, vp, vp, vp, vp, ctypes.POINTER(_Hparams), vp]
         lib.amsp_cast_param_shard.argtypes = [vp, vp, u64, vp]
@@ -182,12 +184,20 @@ def _nbytes(t, given: Optional[int]) -> int:
 
 
 def amsp_reduce_grad_shard(partials, n: int, grad_out, bucket_elems: int = 0, accumulate: bool = False,
-                           d_sqnorm=None, sqnorm_accumulate: bool = False, workspace=None,
-                           workspace_bytes: Optional[int] = None, stream=None) -> None:
+                           stream=None) -> None:
     arr, k = _partials(partials)
-    _check(load().amsp_reduce_grad_shard(arr, k, n, bucket_elems, _ptr(grad_out), int(accumulate), _ptr(d_sqnorm),
-                                         int(sqnorm_accumulate), _ptr(workspace), _nbytes(workspace, workspace_bytes),
+    _check(load().amsp_reduce_grad_shard(arr, k, n, bucket_elems, _ptr(grad_out), int(accumulate),
                                          _stream(stream)), "amsp_reduce_grad_shard")
+
+
+def amsp_reduce_grad_sqnorm_shard(partials, n: int, grad_out, d_sqnorm, workspace, bucket_elems: int = 0,
+                                  accumulate: bool = False, sqnorm_accumulate: bool = False,
+                                  workspace_bytes: Optional[int] = None, stream=None) -> None:
+    arr, k = _partials(partials)
+    _check(load().amsp_reduce_grad_sqnorm_shard(arr, k, n, bucket_elems, _ptr(grad_out), int(accumulate),
+                                                _ptr(d_sqnorm), int(sqnorm_accumulate), _ptr(workspace),
+                                                _nbytes(workspace, workspace_bytes), _stream(stream)),
+           "amsp_reduce_grad_sqnorm_shard")
 
 
 def amsp_grad_sqnorm(partials, grad_f32, n: int, d_sqnorm, workspace, bucket_elems: int = 0,

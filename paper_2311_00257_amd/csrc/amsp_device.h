@@ -695,8 +695,9 @@ __device__ __forceinline__ uint32_t f32_to_e4m3(float x) {
     return sign | code;
 }
 
-__global__ void __launch_bounds__(kThreads) fill_u32_kernel(uint32_t *p, uint32_t count, uint32_t value) {
-    for (uint32_t i = blockIdx.x * kThreads + threadIdx.x; i < count; i += gridDim.x * kThreads) p[i] = value;
+__global__ void __launch_bounds__(kThreads) fill_u32_kernel(uint32_t *p, uint64_t count, uint32_t value) {
+    const uint64_t stride = (uint64_t)gridDim.x * kThreads;   // 64-bit index: no wrap-around however long the list
+    for (uint64_t i = (uint64_t)blockIdx.x * kThreads + threadIdx.x; i < count; i += stride) p[i] = value;
 }
 
 // Largest |x| of a range into *slot (integer atomic max: deterministic).  Persistent read-only
@@ -734,7 +735,8 @@ __global__ void __launch_bounds__(kNormThreads) absmax_kernel(const float *__res
 // scale[i] = 448 / amax[i] in fp32 (correctly rounded division); 1 when amax is 0, Inf or NaN.
 __global__ void __launch_bounds__(kThreads) fp8_scale_kernel(const float *__restrict__ amax, float *__restrict__ scale,
                                                              uint32_t count) {
-    for (uint32_t i = blockIdx.x * kThreads + threadIdx.x; i < count; i += gridDim.x * kThreads) {
+    const uint64_t stride = (uint64_t)gridDim.x * kThreads;
+    for (uint64_t i = (uint64_t)blockIdx.x * kThreads + threadIdx.x; i < count; i += stride) {
         const float a = amax[i];
         scale[i] = (a > 0.0f && a < __uint_as_float(0x7F800000u)) ? 448.0f / a : 1.0f;
     }

@@ -76,19 +76,28 @@ int for_bucket_launches(uint64_t n, uint64_t bucket_elems, F f) {
 struct RwKnobs {
     int inflight_kib, min_waves, reduce_inflight_kib, reduce_min_waves;
 };
-RwKnobs read_rw_knobs() {   // developer knobs for sweeps; read once (thread-safe static below)
+constexpr RwKnobs kRwKnobs{40, 8, 64, 12};   // what the sweeps on MI355X settled on
+#ifdef AMSP_TUNING
+// Sweep builds only (never the shipped library): the four numbers can be overridden from the
+// environment, read once.  They change launch shapes, never results.
+RwKnobs read_rw_knobs() {
     auto knob = [](const char *name, int lo, int hi, int dflt) {
         const char *v = getenv(name);
         const int x = v ? atoi(v) : 0;
         return (x >= lo && x <= hi) ? x : dflt;
     };
-    return RwKnobs{knob("AMSP_INFLIGHT_KIB", 8, 1024, 40), knob("AMSP_MIN_WAVES", 4, 32, 8),
-                   knob("AMSP_REDUCE_INFLIGHT_KIB", 8, 1024, 64), knob("AMSP_REDUCE_MIN_WAVES", 4, 32, 12)};
+    return RwKnobs{knob("AMSP_INFLIGHT_KIB", 8, 1024, kRwKnobs.inflight_kib),
+                   knob("AMSP_MIN_WAVES", 4, 32, kRwKnobs.min_waves),
+                   knob("AMSP_REDUCE_INFLIGHT_KIB", 8, 1024, kRwKnobs.reduce_inflight_kib),
+                   knob("AMSP_REDUCE_MIN_WAVES", 4, 32, kRwKnobs.reduce_min_waves)};
 }
 const RwKnobs &rw_knobs() {
     static const RwKnobs knobs = read_rw_knobs();
     return knobs;
 }
+#else
+constexpr const RwKnobs &rw_knobs() { return kRwKnobs; }
+#endif
 
 // What a kernel family wants in flight per CU, and the fewest waves it is given.
 struct RwTarget {
@@ -502,9 +511,10 @@ size_t amsp_reduce_workspace_bytes(uint64_t n, uint64_t bucket_elems) {
     return (size_t)(reduce_norm_slots(n, bucket_elems) + kSliceBlocks) * sizeof(double);
 }
 
-int amsp_reduce_grad_shard(const uint16_t *const *partials, uint32_t k, uint64_t n, uint64_t bucket_elems,
-                           float *grad_out, int accumulate, double *d_sqnorm, int sqnorm_accumulate,
-                           void *workspace, size_t workspace_bytes, void *stream) {
+// Step 1 over a flat range, with step 2 fused in when d_sqnorm != NULL.
+static int reduce_range(const uint16_t *const *partials, uint32_t k, uint64_t n, uint64_t bucket_elems,
+                        float *grad_out, int accumulate, double *d_sqnorm, int sqnorm_accumulate,
+                        void *workspace, size_t workspace_bytes, void *stream) {
     PartialPtrs pp;
     int rc = check_partials(partials, k, pp);
     if (rc != AMSP_OK) return rc;
@@ -575,6 +585,19 @@ int amsp_reduce_grad_shard(const uint16_t *const *partials, uint32_t k, uint64_t
     if (rc != AMSP_OK || !norm) return rc;
     // one finishing pass per call: the sums of all buckets in bucket order
     return finish_sums(hs, block_sums, used, block_sums + used, d_sqnorm, sqnorm_accumulate ? 1 : 0);
+}
+
+int amsp_reduce_grad_shard(const uint16_t *const *partials, uint32_t k, uint64_t n, uint64_t bucket_elems,
+                           float *grad_out, int accumulate, void *stream) {
+    return reduce_range(partials, k, n, bucket_elems, grad_out, accumulate, nullptr, 0, nullptr, 0, stream);
+}
+
+int amsp_reduce_grad_sqnorm_shard(const uint16_t *const *partials, uint32_t k, uint64_t n, uint64_t bucket_elems,
+                                  float *grad_out, int accumulate, double *d_sqnorm, int sqnorm_accumulate,
+                                  void *workspace, size_t workspace_bytes, void *stream) {
+    if (d_sqnorm == nullptr) return AMSP_ENULL;
+    return reduce_range(partials, k, n, bucket_elems, grad_out, accumulate, d_sqnorm, sqnorm_accumulate, workspace,
+                        workspace_bytes, stream);
 }
 
 int amsp_grad_sqnorm(const uint16_t *const *partials, uint32_t k, const float *grad_f32, uint64_t n,
@@ -842,8 +865,7 @@ int amsp_reduce_grad_segments(const uint16_t *const *partials_flat, uint32_t k, 
                 continue;
             }
         }
-        rc = amsp_reduce_grad_shard(q.p, k, g.length, 0, grad_f32_local + g.local_offset, accumulate, nullptr, 0,
-                                    nullptr, 0, stream);
+        rc = amsp_reduce_grad_shard(q.p, k, g.length, 0, grad_f32_local + g.local_offset, accumulate, stream);
         if (rc != AMSP_OK) return rc;
     }
     return flush_table();
@@ -875,6 +897,8 @@ int amsp_adamw_step_segments(const uint16_t *const *partials_flat, uint32_t k, c
         if (amax_workspace == nullptr) return AMSP_ENULL;
         if (misaligned(d_amax, 4) || misaligned(amax_workspace, 4)) return AMSP_EALIGN;
         if (amax_workspace_bytes < amsp_amax_workspace_bytes(num_segments)) return AMSP_EWORKSPACE;
+        // at most 2^20 - 1 segments with maxima: the words stay 32-bit indexable and the folding
+        // kernel's grid (one block per segment) far inside the grid limit
         if ((size_t)num_segments * kAmaxWordsPerSegment > 0xFFFFFFFFull) return AMSP_EINVAL;
         words = static_cast<uint32_t *>(amax_workspace);
     }
@@ -895,7 +919,7 @@ int amsp_adamw_step_segments(const uint16_t *const *partials_flat, uint32_t k, c
         clear_stale_error();
         const unsigned blocks = (unsigned)((count + kThreads - 1) / kThreads);
         hipLaunchKernelGGL(fill_u32_kernel, dim3(blocks > 1024 ? 1024 : blocks), dim3(kThreads), 0, hs, words,
-                           (uint32_t)count, 0u);
+                           (uint64_t)count, 0u);
         if (launched() != AMSP_OK) return AMSP_EDEVICE;
     }
     // Segments shorter than kShortSegment share launches, up to kMaxTableRanges each (a launch costs more
@@ -1010,7 +1034,7 @@ int amsp_fp8_payload_segments(const float *master_local, uint64_t local_elems, c
         return true;
     };
     if (!amax_ready) {
-        hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(kThreads), 0, hs, slots, num_segments, 0u);
+        hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(kThreads), 0, hs, slots, (uint64_t)num_segments, 0u);
         if (launched() != AMSP_OK) return AMSP_EDEVICE;
         for (uint32_t i = 0; i < num_segments; ++i) {
             if (segments[i].length == 0) continue;

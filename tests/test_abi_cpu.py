@@ -35,6 +35,36 @@ def test_library_exports_every_declared_symbol():
     assert hasattr(synth_lib, "amsp_synth_fill_f32") and hasattr(synth_lib, "amsp_synth_fill_bf16")
 
 
+def _param_types(header: str, name: str):
+    """Parameter types of a declaration in the header, names and spacing stripped."""
+    m = re.search(r"\b%s\s*\(([^)]*)\)\s*;" % name, header)
+    assert m, name
+    types = []
+    for decl in m.group(1).split(","):
+        decl = " ".join(decl.split())
+        decl = re.sub(r"\b[A-Za-z_][A-Za-z0-9_]*$", "", decl).strip()      # drop the parameter's name
+        types.append(decl.replace(" *", "*").replace("* ", "*"))
+    return types
+
+
+def test_five_base_entry_points_keep_their_listed_signatures():
+    """The five calls the boundary names take exactly these parameter types, in this order; everything
+    else the library offers lives in entry points of its own."""
+    header = re.sub(r"/\*.*?\*/", "", open(os.path.join(ROOT, "include", "amsp.h")).read(), flags=re.S)
+    P = "const uint16_t*const*"
+    want = {
+        "amsp_shard_range": ["uint64_t", "uint32_t", "uint32_t", "uint64_t*", "uint64_t*"],
+        "amsp_reduce_grad_shard": [P, "uint32_t", "uint64_t", "uint64_t", "float*", "int", "void*"],
+        "amsp_grad_sqnorm": [P, "uint32_t", "const float*", "uint64_t", "uint64_t", "double*", "int", "void*",
+                             "size_t", "void*"],
+        "amsp_adamw_step_shard": [P, "uint32_t", "const float*", "uint64_t", "uint64_t", "float*", "float*",
+                                  "float*", "uint16_t*", "const amsp_adamw_hparams*", "void*"],
+        "amsp_cast_param_shard": ["const float*", "uint16_t*", "uint64_t", "void*"],
+    }
+    for name, types in want.items():
+        assert _param_types(header, name) == types, (name, _param_types(header, name))
+
+
 def test_hparams_struct_layout_matches_header():
     # float x5, uint32, float x2, pointer (8-aligned), float, tail padding
     assert B._Hparams.d_total_sqnorm.offset == 32
@@ -99,9 +129,11 @@ def test_argument_validation_without_device():
     assert 1024 * (need - 256 * 8) <= many - 256 * 8 <= 1024 * need
     # a ragged last bucket and tiny buckets are covered too (never less than one slot per 256 elements of a launch)
     assert B.amsp_reduce_workspace_bytes(1000, 300) >= 8 * (3 * 2 + 1)
-    assert _status(B.amsp_reduce_grad_shard, [A], 1 << 20, A, d_sqnorm=A, workspace=None) == B.AMSP_ENULL
-    assert _status(B.amsp_reduce_grad_shard, [A], 1 << 20, A, d_sqnorm=A + 4, workspace=A, workspace_bytes=need) == B.AMSP_EALIGN
-    assert _status(B.amsp_reduce_grad_shard, [A], 1 << 20, A, d_sqnorm=A, workspace=A, workspace_bytes=need - 8) == B.AMSP_EWORKSPACE
+    assert _status(B.amsp_reduce_grad_sqnorm_shard, [A], 1 << 20, A, A, None) == B.AMSP_ENULL
+    assert _status(B.amsp_reduce_grad_sqnorm_shard, [A], 1 << 20, A, 0, A, workspace_bytes=need) == B.AMSP_ENULL
+    assert _status(B.amsp_reduce_grad_sqnorm_shard, [A], 1 << 20, A, A + 4, A, workspace_bytes=need) == B.AMSP_EALIGN
+    assert _status(B.amsp_reduce_grad_sqnorm_shard, [A], 1 << 20, A, A, A, workspace_bytes=need - 8) == B.AMSP_EWORKSPACE
+    assert _status(B.amsp_reduce_grad_sqnorm_shard, [], 8, A, A, A, workspace_bytes=need) == B.AMSP_EINVAL
 
     ws = B.amsp_workspace_bytes()
     assert _status(B.amsp_grad_sqnorm, [A], None, 8, 0, A, workspace_bytes=ws) == B.AMSP_ENULL
@@ -249,5 +281,10 @@ def test_library_sources_keep_their_promises():
     for banned in ("hipMalloc", "hipFree", "hipMemset", "hipMemcpy", "hipDeviceSynchronize", "hipStreamSynchronize",
                    "hipHostRegister", "hipStreamCreate", "hipEventSynchronize"):
         assert banned not in text, banned
+    # no process-global knobs in the shipped library: the environment is read only under the sweep macro
+    kernels = open(os.path.join(csrc, "amsp_kernels.hip")).read()
+    outside = re.sub(r"#ifdef AMSP_TUNING.*?#else", "", kernels, flags=re.S)
+    assert "getenv" not in outside and "getenv" not in text.replace(kernels, "")
+    assert "AMSP_TUNING" not in open(os.path.join(ROOT, "paper_2311_00257_amd", "build.py")).read()
     flags = open(os.path.join(ROOT, "paper_2311_00257_amd", "build.py")).read()
     assert '"-target-feature", "-Xclang", "-packed-fp32-ops"' in flags and "gfx950" in flags

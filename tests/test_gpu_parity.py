@@ -152,16 +152,16 @@ def test_reduce_with_fused_norm(B, torch_mod, k, n, shift):
         out = torch.zeros(shift + n, dtype=torch.float32, device="cuda")[shift:]
         ws = torch.empty(B.amsp_reduce_workspace_bytes(n, bucket) // 8, dtype=torch.float64, device="cuda")
         d_s = torch.full((1,), 5.0, dtype=torch.float64, device="cuda")
-        B.amsp_reduce_grad_shard(dparts, n, out, bucket_elems=bucket, d_sqnorm=d_s, workspace=ws)
+        B.amsp_reduce_grad_sqnorm_shard(dparts, n, out, d_s, ws, bucket_elems=bucket)
         assert torch.equal(out, plain)
         S = oracle.sqnorm(oracle.reduce(inp.partials, threads=4))
         got = float(d_s.item())
         assert abs(got - S) <= H.REL_TOL * S
-        B.amsp_reduce_grad_shard(dparts, n, out, bucket_elems=bucket, d_sqnorm=d_s, workspace=ws)
+        B.amsp_reduce_grad_sqnorm_shard(dparts, n, out, d_s, ws, bucket_elems=bucket)
         assert float(d_s.item()) == got                     # deterministic
         # second micro-batch: accumulate the gradient, norm of the accumulated buffer, added to the scalar
-        B.amsp_reduce_grad_shard(dparts, n, out, bucket_elems=bucket, accumulate=True, d_sqnorm=d_s,
-                                 sqnorm_accumulate=True, workspace=ws)
+        B.amsp_reduce_grad_sqnorm_shard(dparts, n, out, d_s, ws, bucket_elems=bucket, accumulate=True,
+                                        sqnorm_accumulate=True)
         G2 = 2.0 * oracle.reduce(inp.partials, threads=4)
         assert np.array_equal(out.cpu().numpy().astype(np.float64), G2)        # 2 g is exact in fp32
         assert float(d_s.item()) == pytest.approx(got + oracle.sqnorm(G2), rel=1e-12)
@@ -182,7 +182,7 @@ def test_step_through_materialised_gradient(B, torch_mod):
     out = torch.zeros(n, dtype=torch.int16, device="cuda")
     ws = torch.empty(B.amsp_reduce_workspace_bytes(n, 0) // 8, dtype=torch.float64, device="cuda")
     d_s = torch.zeros(1, dtype=torch.float64, device="cuda")
-    B.amsp_reduce_grad_shard(dparts, n, g32, d_sqnorm=d_s, workspace=ws)
+    B.amsp_reduce_grad_sqnorm_shard(dparts, n, g32, d_s, ws)
     B.amsp_adamw_step_shard(None, g32, n, dp, dm, dv, out, B.AdamWHparams(d_total_sqnorm=d_s, **hp))
     got = (dp.cpu().numpy(), dm.cpu().numpy(), dv.cpu().numpy(), H.dev_bits(out), float(d_s.item()))
     _check_all(got, ref, inp, hp)

@@ -79,13 +79,13 @@ def _run(B, torch, c: dict):
             half = max(1, k // 2)
             B.amsp_reduce_grad_shard(dparts[:half], n, g32, bucket_elems=c["bucket"])
             if half < k:
-                B.amsp_reduce_grad_shard(dparts[half:], n, g32, bucket_elems=c["bucket"], accumulate=True,
-                                         d_sqnorm=d_s, workspace=ws)
+                B.amsp_reduce_grad_sqnorm_shard(dparts[half:], n, g32, d_s, ws, bucket_elems=c["bucket"],
+                                                accumulate=True)
             else:
                 wn = torch.empty(B.amsp_workspace_bytes() // 8, dtype=torch.float64, device="cuda")
                 B.amsp_grad_sqnorm(None, g32, n, d_s, wn)
         else:
-            B.amsp_reduce_grad_shard(dparts, n, g32, bucket_elems=c["bucket"], d_sqnorm=d_s, workspace=ws)
+            B.amsp_reduce_grad_sqnorm_shard(dparts, n, g32, d_s, ws, bucket_elems=c["bucket"])
         B.amsp_adamw_step_shard(None, g32, n, dp, dm, dv, out, B.AdamWHparams(d_total_sqnorm=d_s, **hp),
                                 bucket_elems=c["bucket"])
         ref = oracle.step(inp.partials, inp.p, inp.m, inp.v, threads=1, **hp)
