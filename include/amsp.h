@@ -27,7 +27,8 @@
  *     take several launches: buckets, segment lists, the norm's finishing pass), so the outputs
  *     are then undefined.
  *   - The library keeps no state between calls and reads no environment variables; launch shapes
- *     are compile-time constants.
+ *     are compile-time constants.  (amsp_grad_sqnorm_static alone writes to a buffer of the
+ *     library's own; see there.)
  *   - "device" pointers are HIP device memory valid on the current device; "host" pointers
  *     are ordinary host memory read during the call only.  The caller owns every buffer.
  *   - Every data pointer addresses the FIRST element of the range to process (the caller
@@ -73,7 +74,8 @@ enum {
     AMSP_EALIGN = -3,     /* a pointer is not aligned to its element size */
     AMSP_EWORKSPACE = -4, /* workspace smaller than the entry point's requirement */
     AMSP_EDEVICE = -5,    /* a HIP call failed */
-    AMSP_ENOPLAN = -6     /* amsp_plan_sharding: no sharding fits the memory limit and the table */
+    AMSP_ENOPLAN = -6,    /* amsp_plan_sharding: no sharding fits the memory limit and the table */
+    AMSP_ESIZE = -7       /* amsp_grad_sqnorm_static: n above AMSP_STATIC_MAX_ELEMS */
 };
 
 #define AMSP_MAX_K 32u
@@ -143,6 +145,27 @@ int amsp_reduce_grad_sqnorm_shard(const uint16_t *const *partials, uint32_t k, u
 int amsp_grad_sqnorm(const uint16_t *const *partials, uint32_t k, const float *grad_f32,
                      uint64_t n, uint64_t bucket_elems, double *d_sqnorm, int accumulate,
                      void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * amsp_grad_sqnorm for callers that cannot allocate or bring device memory of their own for it: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * meaning, kernels and bits as amsp_grad_sqnorm, without the workspace: the block sums go to a buffer
+ * inside the library, a file-scope device array of 526,336 bytes (65,792 doubles) of which every GPU
+ * the library runs on holds one copy until the process ends.  The call allocates and frees nothing.
+ *   - n above AMSP_STATIC_MAX_ELEMS (2^34 elements) is refused with AMSP_ESIZE and a line on stderr
+ *     before anything is enqueued; longer ranges go through amsp_grad_sqnorm.
+ *   - Every call on a GPU shares that GPU's buffer: calls that overlap in time on one GPU (different
+ *     streams, different threads) race on it and give undefined sums; order them on one stream.
+ *     The buffer needs no clearing between calls (every sum is written before it is read); it keeps
+ *     the previous call's contents.
+ *   - The buffer's device address is looked up on the first call on each device (with that device
+ *     current); make that first call outside any stream capture.
+ * Errors: as amsp_grad_sqnorm, AMSP_ESIZE, and AMSP_EDEVICE if the address lookup fails.
+ */
+#define AMSP_STATIC_MAX_ELEMS (1ull << 34)
+int amsp_grad_sqnorm_static(const uint16_t *const *partials, uint32_t k, const float *grad_f32,
+                            uint64_t n, uint64_t bucket_elems, double *d_sqnorm, int accumulate,
+                            void *stream);
 
 /*
  * Hyper-parameters of one AdamW step.  With g' = scale * g:

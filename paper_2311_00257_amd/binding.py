@@ -15,13 +15,15 @@ from typing import Optional, Sequence
 
 from . import build as _build
 
-AMSP_OK, AMSP_EINVAL, AMSP_ENULL, AMSP_EALIGN, AMSP_EWORKSPACE, AMSP_EDEVICE, AMSP_ENOPLAN = 0, -1, -2, -3, -4, -5, -6
+AMSP_OK, AMSP_EINVAL, AMSP_ENULL, AMSP_EALIGN, AMSP_EWORKSPACE, AMSP_EDEVICE, AMSP_ENOPLAN, AMSP_ESIZE = \
+    0, -1, -2, -3, -4, -5, -6, -7
+AMSP_STATIC_MAX_ELEMS = 1 << 34
 AMSP_OP_ALLGATHER, AMSP_OP_REDUCESCATTER, AMSP_OP_ALLREDUCE, AMSP_OP_BROADCAST = 0, 1, 2, 3
 AMSP_MAX_K = 32
 
 EXPORTS = ("amsp_status_string", "amsp_workspace_bytes", "amsp_reduce_workspace_bytes",
            "amsp_amax_workspace_bytes", "amsp_shard_range", "amsp_reduce_grad_shard", "amsp_grad_sqnorm",
-           "amsp_adamw_step_shard", "amsp_cast_param_shard", "amsp_reduce_grad_sqnorm_shard",
+           "amsp_adamw_step_shard", "amsp_cast_param_shard", "amsp_reduce_grad_sqnorm_shard", "amsp_grad_sqnorm_static",
            "amsp_partition_tensors", "amsp_owned_segments", "amsp_reduce_grad_segments", "amsp_grad_sqnorm_segments",
            "amsp_adamw_step_segments", "amsp_cast_param_fp8_shard", "amsp_fp8_payload_segments",
            "amsp_plan_sharding")
@@ -104,6 +106,7 @@ def load() -> ctypes.CDLL:
         lib.amsp_reduce_grad_shard.argtypes = [vp, u32, u64, u64, vp, ci, vp]
         lib.amsp_reduce_grad_sqnorm_shard.argtypes = [vp, u32, u64, u64, vp, ci, vp, ci, vp, ctypes.c_size_t, vp]
         lib.amsp_grad_sqnorm.argtypes = [vp, u32, vp, u64, u64, vp, ci, vp, ctypes.c_size_t, vp]
+        lib.amsp_grad_sqnorm_static.argtypes = [vp, u32, vp, u64, u64, vp, ci, vp]
         lib.amsp_adamw_step_shard.argtypes = [vp, u32, vp, u64, u64, vp, vp, vp, vp, ctypes.POINTER(_Hparams), vp]
         lib.amsp_cast_param_shard.argtypes = [vp, vp, u64, vp]
         pu64, pu32 = ctypes.POINTER(u64), ctypes.POINTER(u32)
@@ -206,6 +209,13 @@ def amsp_grad_sqnorm(partials, grad_f32, n: int, d_sqnorm, workspace, bucket_ele
     _check(load().amsp_grad_sqnorm(arr, k, _ptr(grad_f32), n, bucket_elems, _ptr(d_sqnorm), int(accumulate),
                                    _ptr(workspace), _nbytes(workspace, workspace_bytes), _stream(stream)),
            "amsp_grad_sqnorm")
+
+
+def amsp_grad_sqnorm_static(partials, grad_f32, n: int, d_sqnorm, bucket_elems: int = 0, accumulate: bool = False,
+                            stream=None) -> None:
+    arr, k = _partials(partials)
+    _check(load().amsp_grad_sqnorm_static(arr, k, _ptr(grad_f32), n, bucket_elems, _ptr(d_sqnorm), int(accumulate),
+                                          _stream(stream)), "amsp_grad_sqnorm_static")
 
 
 def amsp_adamw_step_shard(partials, grad_f32, n: int, master, exp_avg, exp_avg_sq, param_bf16_out,

@@ -466,6 +466,37 @@ struct TableBuilder {
 
 }  // namespace
 
+// ---------------------------------------------------------------- the entry point that allocates nothing
+// Block sums of amsp_grad_sqnorm_static: one copy of this array per GPU the library runs on, held until
+// the process ends.  In host code the name is only a handle for hipGetSymbolAddress; the device address
+// it yields (one per device) is what kernels and the batch logic are given.
+static __device__ __align__(256) double scratch[kNormSlots + kSliceBlocks];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::atomic<double *> scratch_address[kMaxDevices];   // per device; null until first asked
+
+// The current device's copy of `scratch`, looked up once per device.
+int static_scratch(double **out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return AMSP_EDEVICE;
+    double *p = scratch_address[dev].load(std::memory_order_acquire);
+    if (p == nullptr) {
+        void *addr = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&addr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || addr == nullptr) {
+            fprintf(stderr, "amsp: hipGetSymbolAddress(scratch) failed on device %d: %s\n", dev, hipGetErrorString(e));
+            (void)hipGetLastError();
+            return AMSP_EDEVICE;
+        }
+        p = static_cast<double *>(addr);
+        scratch_address[dev].store(p, std::memory_order_release);   // any thread may store it: same value
+    }
+    *out = p;
+    return AMSP_OK;
+}
+}  // namespace
+
 // ================================================================ C ABI
 extern "C" {
 
@@ -478,6 +509,7 @@ const char *amsp_status_string(int status) {
         case AMSP_EWORKSPACE: return "workspace too small";
         case AMSP_EDEVICE: return "HIP call failed";
         case AMSP_ENOPLAN: return "no sharding plan is feasible";
+        case AMSP_ESIZE: return "range longer than the entry point without a workspace supports";
         default: return "unknown status";
     }
 }
@@ -600,9 +632,9 @@ int amsp_reduce_grad_sqnorm_shard(const uint16_t *const *partials, uint32_t k, u
                         workspace_bytes, stream);
 }
 
-int amsp_grad_sqnorm(const uint16_t *const *partials, uint32_t k, const float *grad_f32, uint64_t n,
-                     uint64_t bucket_elems, double *d_sqnorm, int accumulate, void *workspace,
-                     size_t workspace_bytes, void *stream) {
+// Step 2 over a flat range; `sums` is the block-sum buffer ((kNormSlots + kSliceBlocks) doubles, checked by the caller).
+static int sqnorm_range(const uint16_t *const *partials, uint32_t k, const float *grad_f32, uint64_t n,
+                        uint64_t bucket_elems, double *d_sqnorm, int accumulate, double *sums, void *stream) {
     PartialPtrs pp{};
     if (k > 0) {
         int rc = check_partials(partials, k, pp);
@@ -611,10 +643,9 @@ int amsp_grad_sqnorm(const uint16_t *const *partials, uint32_t k, const float *g
         if (grad_f32 == nullptr) return AMSP_ENULL;
         if (misaligned(grad_f32, 4)) return AMSP_EALIGN;
     }
-    if (d_sqnorm == nullptr || workspace == nullptr) return AMSP_ENULL;
-    if (misaligned(d_sqnorm, 8) || misaligned(workspace, 8)) return AMSP_EALIGN;
-    if (workspace_bytes < amsp_workspace_bytes()) return AMSP_EWORKSPACE;
-    NormBatch batch{(hipStream_t)stream, static_cast<double *>(workspace), d_sqnorm, 0, accumulate != 0};
+    if (d_sqnorm == nullptr) return AMSP_ENULL;
+    if (misaligned(d_sqnorm, 8)) return AMSP_EALIGN;
+    NormBatch batch{(hipStream_t)stream, sums, d_sqnorm, 0, accumulate != 0};
     clear_stale_error();
     if (n == 0) {
         if (!accumulate) return finish_sums(batch.hs, batch.sums, 0, batch.sums + kNormSlots, d_sqnorm, 0);
@@ -625,6 +656,31 @@ int amsp_grad_sqnorm(const uint16_t *const *partials, uint32_t k, const float *g
     if (rc == AMSP_OK) rc = ranges.flush();
     if (rc != AMSP_OK) return rc;
     return batch.flush();
+}
+
+int amsp_grad_sqnorm(const uint16_t *const *partials, uint32_t k, const float *grad_f32, uint64_t n,
+                     uint64_t bucket_elems, double *d_sqnorm, int accumulate, void *workspace,
+                     size_t workspace_bytes, void *stream) {
+    if (k > AMSP_MAX_K) return AMSP_EINVAL;
+    if (workspace == nullptr) return AMSP_ENULL;
+    if (misaligned(workspace, 8)) return AMSP_EALIGN;
+    if (workspace_bytes < amsp_workspace_bytes()) return AMSP_EWORKSPACE;
+    return sqnorm_range(partials, k, grad_f32, n, bucket_elems, d_sqnorm, accumulate, static_cast<double *>(workspace),
+                        stream);
+}
+
+int amsp_grad_sqnorm_static(const uint16_t *const *partials, uint32_t k, const float *grad_f32, uint64_t n,
+                            uint64_t bucket_elems, double *d_sqnorm, int accumulate, void *stream) {
+    if (k > AMSP_MAX_K) return AMSP_EINVAL;
+    if (n > AMSP_STATIC_MAX_ELEMS) {
+        fprintf(stderr, "amsp_grad_sqnorm_static: n = %llu exceeds AMSP_STATIC_MAX_ELEMS = %llu; use amsp_grad_sqnorm "
+                        "with a workspace\n", (unsigned long long)n, (unsigned long long)AMSP_STATIC_MAX_ELEMS);
+        return AMSP_ESIZE;
+    }
+    double *sums = nullptr;
+    const int rc = static_scratch(&sums);
+    if (rc != AMSP_OK) return rc;
+    return sqnorm_range(partials, k, grad_f32, n, bucket_elems, d_sqnorm, accumulate, sums, stream);
 }
 
 // Hyper-parameters checked and turned into the constants the kernels use (bias corrections in double).
