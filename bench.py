@@ -5,10 +5,13 @@ A step is one pass of the whole path over one rank's shard, inputs resident in H
     amsp_grad_sqnorm (k bf16 partials -> squared norm)           2k   bytes/element
     amsp_adamw_step_shard (reduce + clip + AdamW + bf16 cast)    2k+26 bytes/element
 The other composition of the same steps (reduce with the norm fused in -> fp32 gradient ->
-AdamW + cast, 2k+34 bytes/element in all) is timed afterwards and reported as "alt_step".
+AdamW + cast, 2k+34 bytes/element in all) is timed afterwards and reported as "alt_step"; "best_step"
+names the faster of the two for the workload's k.
 Default workload: LLaMA-7B at shard factor 8, rank 3, k = 8 (842,301,952 elements).
 Prints ONE JSON line: throughput in elements/s, the HBM roofline of the fused kernel from
-HIP-event timing of that kernel alone, and the CPU oracle timed on a bounded slice.
+HIP-event timing of that kernel alone, "ceilings" (traffic-only kernels in the fused kernel's access
+shape, timed in the same process), the other workloads in short form ("other_workloads"), and the CPU
+oracle timed on a bounded slice.
 """
 from __future__ import annotations
 
@@ -34,7 +37,10 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-alt", action="store_true", help="skip the materialised-gradient composition")
     ap.add_argument("--no-ceilings", action="store_true",
-                    help="skip the plain device copy timed for context beside the kernels")
+                    help="skip the traffic-only kernels timed for context beside the product kernel")
+    ap.add_argument("--no-others", action="store_true",
+                    help="skip the short runs of the other workloads (default run of workload 1 only)")
+    ap.add_argument("--other-steps", type=int, default=8, help="timed steps of each of the other workloads")
     ap.add_argument("--cpu-sample-elems", type=int, default=512 * 1024 * 1024)
     ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "adamw_kernel_llama7b_s8r3_k8_hbm_traffic.txt"),
                     help="rocprofv3 --pmc summary holding the fused kernel's measured HBM bytes per launch")
@@ -44,25 +50,41 @@ def parse_args():
     return ap.parse_args()
 
 
-def ceilings(torch, out, master, n):
-    """What plain streaming reaches on this machine in this run, for context beside roofline.frac: the
-    runtime's own device-to-device copy of the fp32 master shard (4n bytes read + 4n written), and the
-    library's read-only norm pass already timed above.  Boxes differ by a few per cent."""
-    scratch = torch.empty_like(master)
-    scratch.copy_(master)
-    times = []
-    for _ in range(7):
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        scratch.copy_(master)
-        e1.record()
-        torch.cuda.synchronize()
-        times.append(e0.elapsed_time(e1))
-    del scratch
-    copy_ms = sorted(times)[len(times) // 2]
-    return {"device_copy": {"GB/s": 8 * n / (copy_ms * 1e-3) / 1e9, "ms": copy_ms, "bytes": 8 * n,
-                            "what": "torch copy_ of the fp32 master shard, read + written bytes"},
-            "read_only": {"GB/s": out["norm_pass"]["GB/s"], "what": "the norm pass over the k partials"}}
+def ceilings(torch, k, parts, master, exp_avg, exp_avg_sq, param_bf16, n, reps=7):
+    """What the memory system gives the fused kernel's access shape with the arithmetic taken out, in this
+    process on this machine: csrc/traffic_probe.hip reads the k bf16 + 3 fp32 streams only, writes the 3 fp32 +
+    1 bf16 streams only, and does both, with the product kernel's lane layout, one-wave workgroups and
+    occupancy cap (swept over the caps the product uses; the best of each is reported).  Overwrites the
+    state: run last."""
+    from paper_2311_00257_amd import traffic_probe as T
+
+    n256 = n & ~255
+    aligned = all(t.data_ptr() % 1024 == 0 for t in list(parts) + [master, exp_avg, exp_avg_sq, param_bf16])
+    if not aligned or n256 == 0 or k > 16:
+        return None
+    bytes_of = {T.READ_ONLY: (2 * k + 12) * n256, T.WRITE_ONLY: 14 * n256, T.READ_WRITE: (2 * k + 26) * n256}
+    names = {T.READ_ONLY: "read_only", T.WRITE_ONLY: "write_only", T.READ_WRITE: "mixed"}
+    res = {name: {"GB/s": 0.0} for name in names.values()}
+    for waves in (6, 7, 8, 9, 10, 12):
+        for mode in (T.READ_ONLY, T.READ_WRITE, T.WRITE_ONLY):
+            run = lambda: T.traffic(mode, parts, master, exp_avg, exp_avg_sq, param_bf16, n256, waves)
+            for _ in range(2):
+                run()
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+            ev[0].record()
+            for i in range(reps):
+                run()
+                ev[i + 1].record()
+            torch.cuda.synchronize()
+            ms = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(reps))[reps // 2]
+            gbps = bytes_of[mode] / (ms * 1e-3) / 1e9
+            if gbps > res[names[mode]]["GB/s"]:
+                res[names[mode]] = {"GB/s": gbps, "ms": ms, "waves_per_cu": waves,
+                                    "bytes_per_element": bytes_of[mode] // n256}
+    res["what"] = ("traffic-only kernels in the fused kernel's access shape (k bf16 + 3 fp32 streams read, 3 fp32 + "
+                   "1 bf16 written, one-wave workgroups under the occupancy cap), median of %d launches each at "
+                   "6-12 waves per CU, best cap reported" % reps)
+    return res
 
 
 def cpu_baseline(w, begin, sample):
@@ -70,7 +92,8 @@ def cpu_baseline(w, begin, sample):
     import oracle
     from paper_2311_00257_amd import synth
 
-    cores = min(len(os.sched_getaffinity(0)), 16)
+    usable = len(os.sched_getaffinity(0))
+    cores = min(usable, 16)
     parts = [synth.fill_bf16(w.key(synth.TENSOR_PARTIAL0 + j), begin, sample, w.sigma_grad, threads=cores)
              for j in range(w.k)]
     p = synth.fill_f32(w.key(synth.TENSOR_MASTER), begin, sample, w.sigma_param, threads=cores)
@@ -87,10 +110,10 @@ def cpu_baseline(w, begin, sample):
     return {"value": res["all"], "unit": "elements/s", "cores": cores, "kind": "oracle",
             "sample": "first %d elements of the %s shard, whole step (reduce, norm, clip, AdamW, cast) in fp64; "
                       "one contiguous chunk per thread" % (sample, w.name),
-            "single_thread_value": res["one"]}
+            "single_thread_value": res["one"], "nproc": os.cpu_count(), "usable_cpus": usable}
 
 
-def alt_step(args, torch, B, w, n, parts, master, exp_avg, exp_avg_sq, param_bf16, d_sqnorm):
+def alt_step(steps, warmup, torch, B, w, n, parts, master, exp_avg, exp_avg_sq, param_bf16, d_sqnorm):
     """The other composition of the same steps, timed after the primary one: amsp_reduce_grad_sqnorm_shard
     writes the fp32 gradient (2k + 4 bytes/element), then amsp_adamw_step_shard on that
     gradient with the bf16 cast (30 bytes/element): 2k + 34 in all instead of 4k + 26."""
@@ -110,17 +133,17 @@ def alt_step(args, torch, B, w, n, parts, master, exp_avg, exp_avg_sq, param_bf1
         if ev:
             ev[2].record()
 
-    for i in range(args.warmup):
+    for i in range(warmup):
         step(w.step + i)
     torch.cuda.synchronize()
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
     t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(w.step + args.warmup + i, events[i])
+    for i in range(steps):
+        step(w.step + warmup + i, events[i])
     torch.cuda.synchronize()
-    ms = (time.perf_counter() - t0) * 1e3 / args.steps
-    red_ms = sum(e[0].elapsed_time(e[1]) for e in events) / args.steps
-    upd_ms = sum(e[1].elapsed_time(e[2]) for e in events) / args.steps
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    red_ms = sum(e[0].elapsed_time(e[1]) for e in events) / steps
+    upd_ms = sum(e[1].elapsed_time(e[2]) for e in events) / steps
     return {"composition": "reduce+norm -> fp32 gradient -> AdamW+cast", "bytes_per_element": 2 * w.k + 34,
             "ms_per_step": ms, "value": n / (ms * 1e-3), "unit": "elements/s",
             "reduce_norm": {"ms": red_ms, "GB/s": (2 * w.k + 4) * n / (red_ms * 1e-3) / 1e9,
@@ -128,24 +151,17 @@ def alt_step(args, torch, B, w, n, parts, master, exp_avg, exp_avg_sq, param_bf1
             "adamw_f32_grad": {"ms": upd_ms, "GB/s": 30 * n / (upd_ms * 1e-3) / 1e9, "bytes_per_element": 30}}
 
 
-def main():
-    args = parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding across GPUs); "
-              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
-        sys.exit(2)
-
+def run_workload(args, config_id, steps, warmup, headline):
+    """One workload: inputs made resident in HBM, `warmup` untimed and exactly `steps` timed steps of the
+    primary composition, then (unless switched off) the alternative composition, the FP8 legs of the
+    inter-tensor workload and, for the headline, the traffic-only ceilings.  Returns (result dict, workload,
+    first global element index, n); every device buffer is released on return."""
     import torch
 
     from paper_2311_00257_amd import binding as B
     from paper_2311_00257_amd import synth, synth_device, workloads
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(1)
-    B.load()
-    torch.cuda.set_device(0)
-    w = workloads.get(args.config)
+    w = workloads.get(config_id)
     k = w.k
     workspace = torch.empty(B.amsp_workspace_bytes() // 8, dtype=torch.float64, device="cuda")
     d_sqnorm = torch.zeros(1, dtype=torch.float64, device="cuda")
@@ -217,30 +233,29 @@ def main():
         if ev:
             ev[2].record()
 
-    if args.calibrate_copy:
+    if headline and args.calibrate_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)
         dst = torch.empty_like(src)
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
 
-    for i in range(args.warmup):
+    for i in range(warmup):
         step(w.step + i)
     torch.cuda.synchronize()
 
-    # ---- timed region: exactly --steps steps, HIP events on the launch stream around each kernel
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    # ---- timed region: exactly `steps` steps, HIP events on the launch stream around each kernel
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
     t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(w.step + args.warmup + i, events[i])
+    for i in range(steps):
+        step(w.step + warmup + i, events[i])
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
 
-    ms_per_step = wall * 1e3 / args.steps
-    norm_ms = sum(e[0].elapsed_time(e[1]) for e in events) / args.steps
-    fused_ms = sum(e[1].elapsed_time(e[2]) for e in events) / args.steps
-    fused_bytes = w.bytes_per_elem_fused() * n
-    achieved = fused_bytes / (fused_ms * 1e-3) / 1e9
+    ms_per_step = wall * 1e3 / steps
+    norm_ms = sum(e[0].elapsed_time(e[1]) for e in events) / steps
+    fused_ms = sum(e[1].elapsed_time(e[2]) for e in events) / steps
+    achieved = w.bytes_per_elem_fused() * n / (fused_ms * 1e-3) / 1e9
 
     traffic = None
     try:
@@ -251,21 +266,14 @@ def main():
         pass
 
     out = {
-        "metric": "model-state elements updated/s per GPU (norm pass + fused reduce/AdamW/bf16-cast step)",
         "value": n / (ms_per_step * 1e-3),
-        "unit": "elements/s",
-        "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
         "ms_per_step": ms_per_step,
-        "higher_is_better": True,
-        "scaling": "weak",
-        "vs_baseline": None,
-        "dtype": "f32",
-        "data": "synthetic",
+        "steps": steps,
+        "warmup": warmup,
         "config": {"workload": w.name, "elements": n, "k": k, "shard_factor": w.shard_factor, "rank": w.rank,
                    "bucket_elems": w.bucket_elems, "buckets": buckets, "launches_per_pass": launches},
-        "roofline": {"bound": "hbm", "kernel": "adamw_kernel<k=%d,bf16 out> (amsp_adamw_step_shard)" % k,
+        "roofline": {"bound": "hbm", "kernel": "adamw_kernel<k=%d,bf16 out> (amsp_adamw_step_%s)" % (
+                         k, "segments" if w.inter_tensor else "shard"),
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
                      "bytes_per_element": w.bytes_per_elem_fused(), "kernel_ms": fused_ms / launches,
@@ -284,11 +292,11 @@ def main():
             B.amsp_fp8_payload_segments(master, n, segs, w.total_elems, fp8, d_amax, d_scale)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
-        for _ in range(args.steps):
+        for _ in range(steps):
             B.amsp_fp8_payload_segments(master, n, segs, w.total_elems, fp8, d_amax, d_scale)
         e1.record()
         torch.cuda.synchronize()
-        fp8_ms = e0.elapsed_time(e1) / args.steps
+        fp8_ms = e0.elapsed_time(e1) / steps
         out["fp8_payload"] = {"ms": fp8_ms, "GB/s": 9 * n / (fp8_ms * 1e-3) / 1e9, "bytes_per_element": 9,
                               "launches": 2 * len(segs) + 2}
         # the whole step shipping FP8 instead of bf16: norm pass, update with the per-tensor maxima taken
@@ -303,22 +311,92 @@ def main():
         for i in range(2):
             fp8_step(w.step + i)
         e0.record()
-        for i in range(args.steps):
+        for i in range(steps):
             fp8_step(w.step + 2 + i)
         e1.record()
         torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / args.steps
+        ms = e0.elapsed_time(e1) / steps
         bpe = 2 * k + 2 * k + 24 + 5
         out["fp8_step"] = {"composition": "norm -> AdamW with fused per-tensor amax, no bf16 -> scales + E4M3 codes",
                            "ms_per_step": ms, "value": n / (ms * 1e-3), "unit": "elements/s",
                            "bytes_per_element": bpe, "GB/s": bpe * n / (ms * 1e-3) / 1e9}
         del fp8
-    if not args.no_ceilings and not args.calibrate_copy:   # keep the calibration run to one known copy
-        out["ceilings"] = ceilings(torch, out, master, n)
+    best = {"composition": "norm -> fused reduce+AdamW+cast", "bytes_per_element": 4 * k + 26,
+            "ms_per_step": ms_per_step, "value": out["value"], "unit": "elements/s"}
     if not args.no_alt and not w.inter_tensor:
-        out["alt_step"] = alt_step(args, torch, B, w, n, parts, master, exp_avg, exp_avg_sq, param_bf16, d_sqnorm)
+        out["alt_step"] = alt_step(steps, warmup, torch, B, w, n, parts, master, exp_avg, exp_avg_sq, param_bf16,
+                                   d_sqnorm)
+        if out["alt_step"]["ms_per_step"] < ms_per_step:
+            best = {key: out["alt_step"][key] for key in ("composition", "bytes_per_element", "ms_per_step", "value",
+                                                          "unit")}
+    out["best_step"] = best          # the faster composition for this k: what a caller free to choose would run
+    if headline and not args.no_ceilings and not args.calibrate_copy and not w.inter_tensor:
+        out["ceilings"] = ceilings(torch, k, parts, master, exp_avg, exp_avg_sq, param_bf16, n)   # overwrites the state
+    del parts, master, exp_avg, exp_avg_sq, param_bf16, norm_pass, update_pass
+    torch.cuda.empty_cache()
+    return out, w, begin, n
+
+
+def short_form(r):
+    """The other workloads in the headline line: what was timed, in a few numbers."""
+    o = {"workload": r["config"]["workload"], "elements": r["config"]["elements"], "k": r["config"]["k"],
+         "steps": r["steps"], "ms_per_step": r["ms_per_step"], "value": r["value"],
+         "fused_GBps": r["roofline"]["achieved"], "fused_frac": r["roofline"]["frac"],
+         "norm_GBps": r["norm_pass"]["GB/s"], "best_step": r["best_step"]}
+    for key in ("fp8_payload", "fp8_step"):
+        if key in r:
+            o[key] = r[key]
+    return o
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding across GPUs); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    from paper_2311_00257_amd import binding as B
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    B.load()
+    torch.cuda.set_device(0)
+
+    res, w, begin, n = run_workload(args, args.config, args.steps, args.warmup, headline=True)
+    out = {
+        "metric": "model-state elements updated/s per GPU (norm pass + fused reduce/AdamW/bf16-cast step)",
+        "value": res.pop("value"),
+        "unit": "elements/s",
+        "n_gpus": 1,
+        "steps": res.pop("steps"),
+        "warmup": res.pop("warmup"),
+        "ms_per_step": res.pop("ms_per_step"),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+    }
+    out.update(res)
+    if not args.no_others and args.config == 1 and not args.calibrate_copy:
+        # every other workload in short form (fewer steps), so that one run covers all of them
+        free, _ = torch.cuda.mem_get_info()
+        others = []
+        for cfg in (3, 2, 4, 5):
+            wl = __import__("paper_2311_00257_amd.workloads", fromlist=["get"]).get(cfg)
+            need = (wl.total_elems // wl.shard_factor) * (2 * wl.k + 18) if not wl.inter_tensor else \
+                wl.total_elems * (2 * wl.k + 3) + (wl.total_elems // wl.shard_factor) * 12
+            if need + (2 << 30) > free:
+                others.append({"workload": wl.name, "skipped": "needs %.0f GB of device memory" % (need / 1e9)})
+                continue
+            r, _, _, _ = run_workload(args, cfg, args.other_steps, 2, headline=False)
+            others.append(short_form(r))
+        out["other_workloads"] = others
     if not args.no_cpu_baseline:
-        del parts, master, exp_avg, exp_avg_sq, param_bf16, norm_pass, update_pass
         out["cpu_baseline"] = cpu_baseline(w, begin, min(args.cpu_sample_elems, n))
     print(json.dumps(out), flush=True)
 

@@ -3,6 +3,7 @@
 ``python -m paper_2311_00257_amd.build`` compiles
   csrc/amsp_kernels.hip + csrc/amsp_planner.cpp -> libamsp.so   (the C-ABI library of include/amsp.h)
   csrc/synth_fill.hip   -> libamsp_synth.so  (device fill kernels of the input generator)
+  csrc/traffic_probe.hip -> libamsp_probe.so (traffic-only kernels timed by bench.py beside the product)
 hipcc cross-compiles without a GPU.
 """
 from __future__ import annotations
@@ -18,6 +19,7 @@ INCLUDE = os.path.join(ROOT, "include")
 
 LIB_AMSP = os.path.join(PKG, "libamsp.so")
 LIB_SYNTH = os.path.join(PKG, "libamsp_synth.so")
+LIB_PROBE = os.path.join(PKG, "libamsp_probe.so")
 LIB_SYNTH_HOST = os.path.join(PKG, "libamsp_synth_host.so")
 
 # packed fp32 instructions are switched off on purpose (they have misbehaved on the test machines)
@@ -26,7 +28,8 @@ HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
                "-Wall", "-Wno-unused-command-line-argument", "-I", INCLUDE]
 
 TARGETS = (((os.path.join(CSRC, "amsp_kernels.hip"), os.path.join(CSRC, "amsp_planner.cpp")), LIB_AMSP),
-           ((os.path.join(CSRC, "synth_fill.hip"),), LIB_SYNTH))
+           ((os.path.join(CSRC, "synth_fill.hip"),), LIB_SYNTH),
+           ((os.path.join(CSRC, "traffic_probe.hip"),), LIB_PROBE))
 
 
 def hipcc() -> str:

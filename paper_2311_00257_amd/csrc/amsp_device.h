@@ -22,7 +22,8 @@ constexpr int kThreads = 256;          // helper kernels (finishing sums, fills)
 constexpr int kRwThreads = 64;         // the kernels that read and write run one-wave workgroups
 constexpr int kVecRW = 4;              // elements per lane per stream in the kernels that write
 constexpr int kVecNorm = 8;            // elements per lane per stream in the norm pass
-constexpr int kNormThreads = 1024;     // the norm pass runs 16-wave blocks, two per CU
+constexpr int kNormThreads = 64;       // the norm pass runs one-wave blocks, a few per CU (norm_waves_per_cu)
+constexpr int kWideThreads = 1024;     // 16-wave blocks: the short-range norm kernel and the absolute-maximum pass
 constexpr int kNormBlocks = 2048;      // upper bound of the norm pass's grid; sizes its workspace
 constexpr uint64_t kMaxGrid = (1ull << 31) - 1;
 
@@ -307,25 +308,41 @@ struct NormSegTable {
     NormSeg seg[kMaxNormSegs];
 };
 
-// acc += sum of g^2 over one range: this lane's share of the vectors, a grid stride apart.
+// Shape of the read-only pass, per k (measured on MI355X, GB/s of the pass): a persistent grid of
+// one-wave blocks, norm_waves_per_cu of them per CU (one per SIMD: 4), each taking per trip
+// norm_unroll consecutive wave pieces (64 lanes x 16 bytes) of every stream, all loads issued before the
+// first is used.  k = 1: 7,410 at 8 pieces per trip against 5,440 at 4; k = 2: 7,330 at 4, 6,820 at 8;
+// k = 3..8: 6,950-7,090 at 8, 1 % less at 4; k = 10..16: 7,090-7,150 at 4.  The earlier shape (two
+// 1024-thread blocks per CU, one vector per lane and trip) read 6,100-6,830.  More waves per CU lose:
+// k = 8 reads 7,060 at 4 waves, 7,000 at 6-8; pieces a grid stride apart instead of consecutive lose up
+// to 15 % at strides that are multiples of 2 MiB.
+template <int K>
+constexpr int norm_unroll() {
+    return K < 0 ? 1 : (K == 2 || K > 8) ? 4 : 8;
+}
+constexpr int norm_waves_per_cu(int K) { return K < 0 ? 8 : 4; }   // run-time k (> 16): a sequential loop over j, so more waves
+
+// acc += sum of g^2 over one range.  Block b's trip t covers the U consecutive wave pieces that start at
+// vector (t * grid + b) * 64 * U.
+// The range's head and tail (element by element, a few trips of one wave) go to block `edge_block`:
+// a different block for every range of a launch, so that no block collects the edges of all of them.
 template <int K, int VEC>
 __device__ __forceinline__ double sqnorm_span(const PartialPtrs &pp, int k, const float *__restrict__ gf32,
-                                              const uint64_t base, const Span &s, const uint64_t first,
-                                              const uint64_t stride, double acc) {
+                                              const uint64_t base, const Span &s, const uint32_t edge_block,
+                                              double acc) {
+    constexpr int U = norm_unroll<K>();
+    const uint64_t row = (uint64_t)gridDim.x * kNormThreads;   // vectors the grid takes per piece index
     if (s.vectorised) {
-        uint64_t v = first;
-        // With one or two streams a single vector per lane leaves too little in flight: take U vectors,
-        // a grid stride apart, per trip, all their loads issued before the first is used.
-        constexpr int U = (K == 0 || K == 1) ? 4 : (K == 2 ? 2 : 1);
+        uint64_t v = (uint64_t)blockIdx.x * (kNormThreads * U) + threadIdx.x;
         if constexpr (U > 1) {
             constexpr int KS = K == 0 ? 1 : K;
             typedef typename Bf16Words<VEC == 8 ? 8 : 4>::type W;
-            for (; v + (U - 1) * stride < s.nvec; v += U * stride) {
+            for (; v + (U - 1) * kNormThreads < s.nvec; v += U * row) {
                 f32x4 a[U];
                 W w[U][KS];
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
-                    const uint64_t e = base + s.head + (v + u * stride) * VEC;
+                    const uint64_t e = base + s.head + (v + u * kNormThreads) * VEC;
                     if constexpr (K == 0) {
                         a[u] = ld_stream(reinterpret_cast<const f32x4 *>(gf32 + e));
                     } else {
@@ -349,19 +366,20 @@ __device__ __forceinline__ double sqnorm_span(const PartialPtrs &pp, int k, cons
                 }
             }
         }
-        for (; v < s.nvec; v += stride) {
+        // U > 1: the pieces (fewer than U) of the block's last, partial trip; U == 1: every trip
+        for (; v < s.nvec; v += (U > 1 ? (uint64_t)kNormThreads : row)) {
             float g[VEC];
             grad_vec<K, VEC>(pp, k, gf32, base + s.head + v * VEC, g);
 #pragma unroll
             for (int c = 0; c < VEC; ++c) acc = fma((double)g[c], (double)g[c], acc);
         }
-        if (blockIdx.x == 0)
+        if (blockIdx.x == edge_block)
             for (uint32_t t = threadIdx.x; t < s.head + s.tail; t += kNormThreads) {
                 const double g = (double)grad1<K>(pp, k, gf32, base + edge_elem<VEC>(s, t));
                 acc = fma(g, g, acc);
             }
     } else {
-        for (uint64_t i = first; i < s.n; i += stride) {
+        for (uint64_t i = (uint64_t)blockIdx.x * kNormThreads + threadIdx.x; i < s.n; i += row) {
             double g = (double)grad1<K>(pp, k, gf32, base + i);
             acc = fma(g, g, acc);
         }
@@ -372,12 +390,11 @@ __device__ __forceinline__ double sqnorm_span(const PartialPtrs &pp, int k, cons
 template <int K, int VEC>
 __global__ void __launch_bounds__(kNormThreads) sqnorm_kernel(PartialPtrs pp, int k, const float *__restrict__ gf32,
                                                               double *__restrict__ block_sums, NormSegTable t) {
-    const uint64_t first = (uint64_t)blockIdx.x * kNormThreads + threadIdx.x;
-    const uint64_t stride = (uint64_t)gridDim.x * kNormThreads;
     double acc = 0.0;
-    for (int i = 0; i < t.count; ++i) acc = sqnorm_span<K, VEC>(pp, k, gf32, t.seg[i].base, t.seg[i].s, first, stride, acc);
-    const double total = block_sum<kNormThreads>(acc);
-    if (threadIdx.x == 0) block_sums[blockIdx.x] = total;
+    for (int i = 0; i < t.count; ++i)
+        acc = sqnorm_span<K, VEC>(pp, k, gf32, t.seg[i].base, t.seg[i].s, (uint32_t)i % gridDim.x, acc);
+    acc = wave_sum(acc);   // the block is one wave
+    if (threadIdx.x == 0) block_sums[blockIdx.x] = acc;
 }
 
 // Short ranges (norm gains, biases, small buckets): in the kernel above every block walks every
@@ -393,7 +410,7 @@ struct ShortNormTable {
 };
 
 template <int K, int VEC>
-__global__ void __launch_bounds__(kNormThreads) sqnorm_short_kernel(PartialPtrs pp, int k,
+__global__ void __launch_bounds__(kWideThreads) sqnorm_short_kernel(PartialPtrs pp, int k,
                                                                     const float *__restrict__ gf32,
                                                                     double *__restrict__ block_sums,
                                                                     ShortNormTable t) {
@@ -405,7 +422,7 @@ __global__ void __launch_bounds__(kNormThreads) sqnorm_short_kernel(PartialPtrs 
     const uint64_t base = t.seg[r].base;
     double acc = 0.0;
     if (s.vectorised) {
-        const uint64_t v = (uint64_t)lb * kNormThreads + threadIdx.x;
+        const uint64_t v = (uint64_t)lb * kWideThreads + threadIdx.x;
         if (v < s.nvec) {
             float g[VEC];
             grad_vec<K, VEC>(pp, k, gf32, base + s.head + v * VEC, g);
@@ -413,18 +430,18 @@ __global__ void __launch_bounds__(kNormThreads) sqnorm_short_kernel(PartialPtrs 
             for (int c = 0; c < VEC; ++c) acc = fma((double)g[c], (double)g[c], acc);
         }
         if (lb == 0)
-            for (uint32_t e = threadIdx.x; e < s.head + s.tail; e += kNormThreads) {
+            for (uint32_t e = threadIdx.x; e < s.head + s.tail; e += kWideThreads) {
                 const double g = (double)grad1<K>(pp, k, gf32, base + edge_elem<VEC>(s, e));
                 acc = fma(g, g, acc);
             }
     } else {
-        const uint64_t stride = (uint64_t)t.blocks[r] * kNormThreads;
-        for (uint64_t i = (uint64_t)lb * kNormThreads + threadIdx.x; i < s.n; i += stride) {
+        const uint64_t stride = (uint64_t)t.blocks[r] * kWideThreads;
+        for (uint64_t i = (uint64_t)lb * kWideThreads + threadIdx.x; i < s.n; i += stride) {
             const double g = (double)grad1<K>(pp, k, gf32, base + i);
             acc = fma(g, g, acc);
         }
     }
-    const double total = block_sum<kNormThreads>(acc);
+    const double total = block_sum<kWideThreads>(acc);
     if (threadIdx.x == 0) block_sums[blockIdx.x] = total;
 }
 
@@ -702,11 +719,11 @@ __global__ void __launch_bounds__(kThreads) fill_u32_kernel(uint32_t *p, uint64_
 
 // Largest |x| of a range into *slot (integer atomic max: deterministic).  Persistent read-only
 // grid like the norm pass.
-__global__ void __launch_bounds__(kNormThreads) absmax_kernel(const float *__restrict__ x, Span s,
+__global__ void __launch_bounds__(kWideThreads) absmax_kernel(const float *__restrict__ x, Span s,
                                                               uint32_t *__restrict__ slot) {
     constexpr int VEC = 4;
-    const uint64_t first = (uint64_t)blockIdx.x * kNormThreads + threadIdx.x;
-    const uint64_t stride = (uint64_t)gridDim.x * kNormThreads;
+    const uint64_t first = (uint64_t)blockIdx.x * kWideThreads + threadIdx.x;
+    const uint64_t stride = (uint64_t)gridDim.x * kWideThreads;
     uint32_t m = 0;
     if (s.vectorised) {
         for (uint64_t v = first; v < s.nvec; v += stride) {
@@ -716,18 +733,18 @@ __global__ void __launch_bounds__(kNormThreads) absmax_kernel(const float *__res
             for (int c = 0; c < VEC; ++c) m = max(m, abs_bits(t[c]));
         }
         if (blockIdx.x == 0)
-            for (uint32_t t = threadIdx.x; t < s.head + s.tail; t += kNormThreads) m = max(m, abs_bits(x[edge_elem<VEC>(s, t)]));
+            for (uint32_t t = threadIdx.x; t < s.head + s.tail; t += kWideThreads) m = max(m, abs_bits(x[edge_elem<VEC>(s, t)]));
     } else {
         for (uint64_t i = first; i < s.n; i += stride) m = max(m, abs_bits(x[i]));
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) m = max(m, (uint32_t)__shfl_down((int)m, off, 64));
-    __shared__ uint32_t wave_max[kNormThreads / 64];
+    __shared__ uint32_t wave_max[kWideThreads / 64];
     if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = m;
     __syncthreads();
     if (threadIdx.x == 0) {
 #pragma unroll
-        for (int w = 1; w < kNormThreads / 64; ++w) m = max(m, wave_max[w]);
+        for (int w = 1; w < kWideThreads / 64; ++w) m = max(m, wave_max[w]);
         atomicMax(slot, m);
     }
 }

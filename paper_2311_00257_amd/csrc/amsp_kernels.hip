@@ -78,36 +78,38 @@ struct RwKnobs {
 };
 constexpr RwKnobs kRwKnobs{40, 8, 64, 12};   // what the sweeps on MI355X settled on
 #ifdef AMSP_TUNING
-// Sweep builds only (never the shipped library): the four numbers can be overridden from the
-// environment, read once.  They change launch shapes, never results.
-RwKnobs read_rw_knobs() {
-    auto knob = [](const char *name, int lo, int hi, int dflt) {
-        const char *v = getenv(name);
-        const int x = v ? atoi(v) : 0;
-        return (x >= lo && x <= hi) ? x : dflt;
-    };
-    return RwKnobs{knob("AMSP_INFLIGHT_KIB", 8, 1024, kRwKnobs.inflight_kib),
-                   knob("AMSP_MIN_WAVES", 4, 32, kRwKnobs.min_waves),
-                   knob("AMSP_REDUCE_INFLIGHT_KIB", 8, 1024, kRwKnobs.reduce_inflight_kib),
-                   knob("AMSP_REDUCE_MIN_WAVES", 4, 32, kRwKnobs.reduce_min_waves)};
+// Sweep builds only (never the shipped library): the four numbers, or the wave count itself, can be
+// overridden from the environment, read at every call so that one process can alternate settings.
+// They change launch shapes, never results.
+int env_knob(const char *name, int lo, int hi, int dflt) {
+    const char *v = getenv(name);
+    const int x = v ? atoi(v) : 0;
+    return (x >= lo && x <= hi) ? x : dflt;
 }
-const RwKnobs &rw_knobs() {
-    static const RwKnobs knobs = read_rw_knobs();
-    return knobs;
+RwKnobs rw_knobs() {
+    return RwKnobs{env_knob("AMSP_INFLIGHT_KIB", 8, 1024, kRwKnobs.inflight_kib),
+                   env_knob("AMSP_MIN_WAVES", 4, 32, kRwKnobs.min_waves),
+                   env_knob("AMSP_REDUCE_INFLIGHT_KIB", 8, 1024, kRwKnobs.reduce_inflight_kib),
+                   env_knob("AMSP_REDUCE_MIN_WAVES", 4, 32, kRwKnobs.reduce_min_waves)};
 }
+int forced_waves() { return env_knob("AMSP_FORCE_WAVES", 3, 32, 0); }
 #else
 constexpr const RwKnobs &rw_knobs() { return kRwKnobs; }
+constexpr int forced_waves() { return 0; }
 #endif
 
 // What a kernel family wants in flight per CU, and the fewest waves it is given.
 struct RwTarget {
     int inflight_kib, min_waves;
 };
-// AdamW kernels: 40 KiB, at least 8 waves (10 waves for an fp32 gradient, 12 for k = 1, 8 from k = 4 on),
-// 7 once a wave loads more than 8 KiB (fused step from k = 9 on: k = 16 reads 6,330 GB/s at 7 waves
-// against 6,010-6,270 at 8, while k = 8 is best at 8).
+// AdamW kernels: 40 KiB, at least 8 waves (10 waves for an fp32 gradient, 12 for k = 1, 8 for k = 4..8); 7 once
+// a wave loads more than 7 KiB (fused step with k = 9..15) and 6 from 10.5 KiB on (k >= 16).  GB/s of the
+// fused step at 6 / 7 / 8 / 9 waves, alternated in one process: k = 8: 6,050 / 6,500 / 6,510 / 6,520;
+// k = 9: 6,180 / 6,540 / 6,500 / 6,500; k = 12: 6,380 / 6,520 / 6,340 / 6,340; k = 14: 6,410 / 6,420 / 6,270 /
+// 6,290; k = 16: 6,410 / 6,355 / 6,240 / 6,240.
 RwTarget adamw_target(unsigned load_bytes_per_lane) {
-    const int floor = 64u * load_bytes_per_lane > 8192u ? rw_knobs().min_waves - 1 : rw_knobs().min_waves;
+    const unsigned per_wave = 64u * load_bytes_per_lane;
+    const int floor = rw_knobs().min_waves - (per_wave > 7168u ? 1 : 0) - (per_wave >= 10752u ? 1 : 0);
     return RwTarget{rw_knobs().inflight_kib, floor};
 }
 // Reduction (its writes are a small share of the traffic): 64 KiB, at least 12 waves (k = 8: 16 waves,
@@ -118,6 +120,7 @@ int rw_waves_per_cu(unsigned load_bytes_per_lane, RwTarget t) {
     const unsigned per_wave = 64u * load_bytes_per_lane;
     int waves = (int)(((unsigned)t.inflight_kib * 1024u + per_wave - 1) / per_wave);
     if (waves < t.min_waves) waves = t.min_waves;
+    if (forced_waves() > 0) waves = forced_waves();
     return waves > 32 ? 32 : waves;
 }
 
@@ -181,16 +184,24 @@ int cu_count() {
     return n;
 }
 
-// The norm pass: two 1024-thread blocks per CU (what a CU holds), at most kNormBlocks; `work` = lanes' worth
-// of vectors (or elements on the element-wise path).
-int norm_grid(uint64_t work) {
+// The norm pass: norm_waves_per_cu one-wave blocks per CU, at most kNormBlocks; `work` = lanes' worth of
+// vectors (or elements on the element-wise path).  kk = the kernel's K (-1: run-time k).
+int norm_grid(uint64_t work, int kk) {
     uint64_t blocks = (work + kNormThreads - 1) / kNormThreads;
+    uint64_t cap = (uint64_t)norm_waves_per_cu(kk) * (uint64_t)cu_count();
+    if (cap > kNormBlocks) cap = kNormBlocks;
+    if (blocks > cap) blocks = cap;
+    return blocks == 0 ? 1 : (int)blocks;
+}
+// The absolute-maximum pass: two 1024-thread blocks per CU (what a CU holds).
+int wide_grid(const Span &s) {
+    const uint64_t work = s.vectorised ? s.nvec : s.n;
+    uint64_t blocks = (work + kWideThreads - 1) / kWideThreads;
     uint64_t cap = 2 * (uint64_t)cu_count();
     if (cap > kNormBlocks) cap = kNormBlocks;
     if (blocks > cap) blocks = cap;
     return blocks == 0 ? 1 : (int)blocks;
 }
-int norm_grid(const Span &s) { return norm_grid(s.vectorised ? s.nvec : s.n); }
 
 // One launch covers at most this many elements (one wave per 256 of them in a grid of < 2^31 blocks):
 // about 5.5e11, beyond any buffer that fits the device.
@@ -336,7 +347,7 @@ int norm_launch(NormBatch &batch, const PartialPtrs &pp, uint32_t k, const float
         t.seg[i].s = make_span(len[i], st, ns, vec);
         work += t.seg[i].s.vectorised ? t.seg[i].s.nvec : t.seg[i].s.n;
     }
-    const int grid = norm_grid(work);
+    const int grid = norm_grid(work, k > 16 ? -1 : (int)k);
     double *block_sums = nullptr;
     int rc = batch.reserve(grid, &block_sums);
     if (rc != AMSP_OK) return rc;
@@ -370,8 +381,8 @@ int norm_launch_short(NormBatch &batch, const PartialPtrs &pp, uint32_t k, const
         if (k == 0) st[ns++] = Stream16{gf + base[i], 4};
         t.seg[i].base = base[i];
         t.seg[i].s = make_span(len[i], st, ns, vec);
-        uint64_t blocks = t.seg[i].s.vectorised ? (t.seg[i].s.nvec + kNormThreads - 1) / kNormThreads
-                                                : (len[i] + kNormThreads - 1) / kNormThreads;
+        uint64_t blocks = t.seg[i].s.vectorised ? (t.seg[i].s.nvec + kWideThreads - 1) / kWideThreads
+                                                : (len[i] + kWideThreads - 1) / kWideThreads;
         if (!t.seg[i].s.vectorised && blocks > 64) blocks = 64;
         if (blocks == 0) blocks = 1;
         t.first_block[i] = blocks_total;
@@ -383,10 +394,10 @@ int norm_launch_short(NormBatch &batch, const PartialPtrs &pp, uint32_t k, const
     if (rc != AMSP_OK) return rc;
     hipStream_t hs = batch.hs;
     if (k == 0)
-        hipLaunchKernelGGL((sqnorm_short_kernel<0, 4>), dim3(blocks_total), dim3(kNormThreads), 0, hs, pp, (int)k, gf,
+        hipLaunchKernelGGL((sqnorm_short_kernel<0, 4>), dim3(blocks_total), dim3(kWideThreads), 0, hs, pp, (int)k, gf,
                            block_sums, t);
     else
-        hipLaunchKernelGGL((sqnorm_short_kernel<-1, kVecNorm>), dim3(blocks_total), dim3(kNormThreads), 0, hs, pp,
+        hipLaunchKernelGGL((sqnorm_short_kernel<-1, kVecNorm>), dim3(blocks_total), dim3(kWideThreads), 0, hs, pp,
                            (int)k, gf, block_sums, t);
     return launched();
 }
@@ -1101,7 +1112,7 @@ int amsp_fp8_payload_segments(const float *master_local, uint64_t local_elems, c
             const float *x = master_local + segments[i].local_offset;
             Stream16 st[1] = {{x, 4}};
             Span s = make_span(segments[i].length, st, 1, 4);
-            hipLaunchKernelGGL(absmax_kernel, dim3(norm_grid(s)), dim3(kNormThreads), 0, hs, x, s, slots + i);
+            hipLaunchKernelGGL(absmax_kernel, dim3(wide_grid(s)), dim3(kWideThreads), 0, hs, x, s, slots + i);
             if (launched() != AMSP_OK) return AMSP_EDEVICE;
         }
         rc = flush_table(false);

@@ -66,83 +66,162 @@ def dev_bits(t) -> np.ndarray:
     return t.view(torch.int16).cpu().numpy().view(np.uint16)
 
 
-def rel_err_scaled(got: np.ndarray, want: np.ndarray, floor: np.ndarray) -> np.ndarray:
-    """|got - want| / max(|want|, floor): relative error with the denominator kept from
-    collapsing where the true value is small only because its operands cancelled."""
-    den = np.maximum(np.abs(want), floor)
-    den = np.where(den == 0, 1.0, den)
-    return np.abs(got.astype(np.float64) - want) / den
+@dataclasses.dataclass
+class GradSum:
+    """What a comparison needs to know about a k-term fp32 gradient sum: k and sum_j |g_j[i]| in double,
+    the magnitude against which the sum is known."""
+    k: int
+    abs: np.ndarray
 
 
-def abs_partials(partials) -> np.ndarray:
-    """sum_j |g_j[i]| in double: the magnitude against which a k-term fp32 sum is known."""
+def abs_partials(partials) -> GradSum:
     total = np.zeros(partials[0].size, dtype=np.float64)
     for q in partials:
         total += np.abs(synth.bf16_bits_to_f32(q).astype(np.float64))
-    return total
+    return GradSum(len(partials), total)
 
 
-def floors(ref: dict, inp_p, inp_m, hp: dict, abs_g=None):
-    """Denominator floors (master, first moment, second moment) of the scaled relative errors:
-    'max relative error <= tol' read relative to the largest operand where a result is small by
-    cancellation, and carried forward to first order.
-      gradient      a k-term fp32 sum is known to tol of sum_j |g_j| (abs_g), not of |G|;
-      first moment  tau_m = max(beta1 |m|, (1 - beta1) scale abs_g);
-      second moment v' plus the part of (1 - beta2) g'^2 that is uncertain because g' is:
-                    2 (1 - beta2) |g'| (scale abs_g - |g'|);
-      master        max(|p|, |p' - p|), the operands of the final addition, plus what the excess of
-                    the two moments' floors over their values becomes on its way into the step
-                    lr * m_hat / (sqrt(v_hat) + eps).
-    Away from cancellation the excess terms vanish and these are |m'|-, v'- and max(|p|, step)-relative."""
+ULP = 2.0 ** -24        # unit roundoff of fp32: one correctly rounded operation errs by at most ULP * |result|
+
+
+def denominators(ref: dict, inp_p, inp_m, hp: dict):
+    """Denominators of the relative errors of (master, first moment, second moment): the result itself, or the
+    larger operand of its final addition where that addition cancels:
+      master        max(|p|, |p' - p|)         (p' = p - step)
+      first moment  max(beta1 |m|, (1 - beta1) |g'|)
+      second moment v'                         (a sum of non-negative terms: no cancellation)."""
+    b1 = float(np.float32(hp["beta1"]))
+    gp = np.abs(ref["scale"] * ref["G"])
+    den_p = np.maximum(np.abs(inp_p.astype(np.float64)), np.abs(ref["p"] - inp_p))
+    den_m = np.maximum(b1 * np.abs(inp_m.astype(np.float64)), (1 - b1) * gp)
+    den_v = ref["v"]
+    return den_p, den_m, den_v
+
+
+def rounding_allowances(ref: dict, inp_p, inp_m, hp: dict, abs_g=None):
+    """Absolute errors (master, first moment, second moment) that correctly rounded fp32 arithmetic may
+    leave, to first order, in places where a relative tolerance on the result cannot cover them:
+      e_G  = (k - 1) ULP sum_j |g_j|          a sequential k-term fp32 sum (abs_g: a GradSum; None or k = 1:
+                                              the gradient is exact)
+      e_g' = |scale| e_G + 2 ULP |g'|         scale rounded to fp32, one product
+      e_m  = (1 - beta1) e_g' + 3 ULP tau_m   tau_m = max(beta1 |m|, (1 - beta1) |g'|): the roundings of the
+                                              product and of the fused multiply-add are relative to the
+                                              operands, not to a result that cancelled
+      e_v  = (1 - beta2) (2 |g'| e_g' + e_g'^2) + 3 ULP v'
+      e_p  = lr (e_m / bc1) / (sqrt(v_hat) + eps)          the step inherits the first moment's error,
+             + lr |u| (e_v / (2 v') + 6 ULP)               the second moment's through the square root,
+             + 4 ULP max(|p|, |p' - p|)                    and its own roundings
+    These are a few ulps of the operands: far below the relative tolerance wherever nothing cancels."""
     f32 = lambda x: float(np.float32(x))
     b1, b2, lr, eps = f32(hp["beta1"]), f32(hp["beta2"]), f32(hp["lr"]), f32(hp["eps"])
     t = int(hp["step"])
     bc1, bc2 = 1.0 - b1 ** t, 1.0 - b2 ** t
+    scale = abs(float(ref["scale"]))
     gp = np.abs(ref["scale"] * ref["G"])
-    gfl = gp if abs_g is None else np.maximum(gp, np.abs(ref["scale"]) * abs_g)
-    floor_m = np.maximum(b1 * np.abs(inp_m.astype(np.float64)), (1 - b1) * gfl)
-    floor_v = ref["v"] + 2.0 * (1 - b2) * gp * (gfl - gp)
+    e_G = 0.0 if abs_g is None else max(abs_g.k - 1, 0) * ULP * abs_g.abs
+    e_g = scale * e_G + 2 * ULP * gp
+    tau_m = np.maximum(b1 * np.abs(inp_m.astype(np.float64)), (1 - b1) * gp)
+    e_m = (1 - b1) * e_g + 3 * ULP * tau_m
+    e_v = (1 - b2) * (2 * gp * e_g + e_g * e_g) + 3 * ULP * ref["v"]
     denom = np.sqrt(ref["v"] / bc2) + eps
     denom = np.where(denom > 0, denom, 1.0)
-    through_m = abs(lr) * (np.maximum(floor_m - np.abs(ref["m"]), 0.0) / bc1) / denom
     u = np.abs(ref["m"] / bc1) / denom
     with np.errstate(divide="ignore", invalid="ignore"):
-        excess_v = np.where(ref["v"] > 0, (floor_v - ref["v"]) / ref["v"], 0.0)
-    through_v = abs(lr) * u * 0.5 * excess_v
-    floor_p = np.maximum(np.abs(inp_p.astype(np.float64)), np.abs(ref["p"] - inp_p)) + through_m + through_v
-    return floor_p, floor_m, floor_v
+        rel_v = np.where(ref["v"] > 0, e_v / (2.0 * ref["v"]), 0.0)
+    den_p = np.maximum(np.abs(inp_p.astype(np.float64)), np.abs(ref["p"] - inp_p))
+    e_p = abs(lr) * (e_m / bc1) / denom + abs(lr) * u * (rel_v + 6 * ULP) + 4 * ULP * den_p
+    return e_p, e_m, e_v
 
 
-def master_floor(ref: dict, inp_p, inp_m, hp: dict, abs_g=None) -> np.ndarray:
-    return floors(ref, inp_p, inp_m, hp, abs_g)[0]
+# share of a workload's elements that may need more than the relative tolerance (see check_state)
+RARE = 1e-5
 
 
-def check_state(got_p, got_m, got_v, ref: dict, inp_p, inp_m, hp: dict, tol: float = REL_TOL, abs_g=None):
-    """fp32 master/m/v against the oracle's doubles, each relative to its floor (see floors)."""
-    floor_p, floor_m, floor_v = floors(ref, inp_p, inp_m, hp, abs_g)
-    ep = rel_err_scaled(got_p, ref["p"], floor_p)
-    em = rel_err_scaled(got_m, ref["m"], floor_m)
-    ev = rel_err_scaled(got_v, ref["v"], floor_v)
-    stats = dict(max_p=float(ep.max(initial=0)), max_m=float(em.max(initial=0)), max_v=float(ev.max(initial=0)))
-    # the strict element-wise figure, reported for audit
+def check_state(got_p, got_m, got_v, ref: dict, inp_p, inp_m, hp: dict, tol: float = REL_TOL, abs_g=None,
+                rare=None):
+    """fp32 master/m/v against the oracle's doubles: |x - x_ref| <= tol * denominator + rounding allowance
+    (see denominators and rounding_allowances).  The allowance matters only where operands cancelled; the
+    elements that needed it (error above tol * denominator alone) are counted per quantity in
+    stats["extra_p" / "extra_m" / "extra_v"], and with `rare` given their share of the n elements must not
+    exceed it (callers pass RARE on the five workloads' own inputs).  The allowance is worked out only for
+    those elements.  The strict figures |x - x_ref| / |x_ref| are reported beside them."""
+    dens = denominators(ref, inp_p, inp_m, hp)
+    stats = {}
+    suspects = np.zeros(got_p.size, dtype=bool)
+    errs = []
+    for name, got, den in zip("pmv", (got_p, got_m, got_v), dens):
+        err = np.abs(got.astype(np.float64) - ref[name])
+        errs.append(err)
+        safe = np.where(den == 0, 1.0, den)
+        stats["max_" + name] = float((err / safe).max(initial=0))            # relative to the denominator
+        over = err > tol * den
+        stats["extra_" + name] = int(np.count_nonzero(over))                   # need the rounding allowance
+        suspects |= over
+        stats["bad_" + name] = 0
+    idx = np.nonzero(suspects)[0]
+    if idx.size:
+        sub = {key: (val[idx] if isinstance(val, np.ndarray) and val.shape == got_p.shape else val)
+               for key, val in ref.items()}
+        sub_g = None if abs_g is None else GradSum(abs_g.k, abs_g.abs[idx])
+        allow = rounding_allowances(sub, inp_p[idx], inp_m[idx], hp, sub_g)
+        for name, err, den, extra in zip("pmv", errs, dens, allow):
+            stats["bad_" + name] = int(np.count_nonzero(err[idx] > tol * den[idx] + extra))
     with np.errstate(divide="ignore", invalid="ignore"):
-        strict = np.abs(got_p.astype(np.float64) - ref["p"]) / np.abs(ref["p"])
+        strict = errs[0] / np.abs(ref["p"])
     stats["strict_max_p"] = float(np.nanmax(strict)) if strict.size else 0.0
-    stats["strict_over_tol_p"] = int(np.sum(strict > tol))
-    assert stats["max_p"] <= tol and stats["max_m"] <= tol and stats["max_v"] <= tol, stats
+    stats["strict_over_tol_p"] = int(np.count_nonzero(strict > tol))
+    stats["n"] = int(got_p.size)
+    assert stats["bad_p"] == 0 and stats["bad_m"] == 0 and stats["bad_v"] == 0, stats
+    if rare is not None:
+        most = max(stats["extra_p"], stats["extra_m"], stats["extra_v"])
+        assert most <= rare * stats["n"], ("too many elements needed the rounding allowance", stats)
     return stats
+
+
+def emulate_step_f32(partials, p, m, v, sqnorm, hp):
+    """The update as the kernels are documented to compute it, in numpy float32: sequential fp32 sum
+    of the partials, scale from the squared norm in double, then per element
+        gs = scale*g;  m = fma(b1, m, (1-b1)*gs);  v = fma(b2, v, ((1-b2)*gs)*gs)
+        u = (m*rbc1) / (sqrt(v*rbc2) + eps);  p = fma(-lr, fma(wd, p, u), p)
+    with every operation correctly rounded once (fma through float64: the product of two float32 is
+    exact there).  Not the oracle: a model of the device arithmetic, for a bit-for-bit comparison."""
+    f32 = np.float32
+
+    def fma(a, b, c):
+        return (np.asarray(a, dtype=np.float64) * np.asarray(b, dtype=np.float64)
+                + np.asarray(c, dtype=np.float64)).astype(f32)
+
+    g = synth.bf16_bits_to_f32(partials[0]).astype(f32)
+    for q in partials[1:]:
+        g = (g + synth.bf16_bits_to_f32(q)).astype(f32)
+    b1, b2, lr, eps, wd = (f32(hp[key]) for key in ("beta1", "beta2", "lr", "eps", "weight_decay"))
+    scale = 1.0
+    if hp["max_norm"] > 0:
+        clip = float(f32(hp["max_norm"])) / (np.sqrt(sqnorm) + float(f32(hp["clip_eps"])))
+        scale = min(1.0, clip)
+    scale = f32(scale)
+    omb1, omb2 = f32(1.0 - float(b1)), f32(1.0 - float(b2))
+    rbc1 = f32(1.0 / (1.0 - float(b1) ** hp["step"]))
+    rbc2 = f32(1.0 / (1.0 - float(b2) ** hp["step"]))
+    gs = (scale * g).astype(f32)
+    m1 = fma(b1, m, (omb1 * gs).astype(f32))
+    v1 = fma(b2, v, ((omb2 * gs).astype(f32) * gs).astype(f32))
+    den = (np.sqrt((v1 * rbc2).astype(f32)).astype(f32) + eps).astype(f32)
+    u = ((m1 * rbc1).astype(f32) / den).astype(f32)
+    p1 = fma(-lr, fma(wd, p, u), p)
+    return p1, m1, v1
 
 
 def check_bf16(got_bits: np.ndarray, ref: dict, inp_p: np.ndarray, tol: float = REL_TOL, inp_m=None,
                hp=None, abs_g=None) -> int:
-    """bf16 parameters: identical to bf16(fp32(p')) of the oracle, except where the fp32 tolerance
-    lets p' round elsewhere: with delta = `tol` * max(|p'|, |p|, |p' - p|) (check_state's tolerance
-    for the master; with inp_m and hp given, master_floor's), the shipped value must be the rounding of some value in [p' - delta, p' + delta],
-    i.e. lie between bf16(p' - delta) and bf16(p' + delta).  Away from cancellation delta is 1/400
-    of a bf16 step, so this is "exact, or the other neighbour when p' is within delta of the midpoint";
-    where p and the step cancel (p' a million times smaller than its operands) it is as wide as the
-    fp32 result is allowed to be.  That the shipped value is exactly bf16 of the device's own fp32
-    master is checked separately by the callers.  Returns the number of mismatches."""
+    """bf16 parameters: identical to bf16(fp32(p')) of the oracle, except where the fp32 tolerance lets p'
+    round elsewhere: with delta = what check_state allows the master (tol * max(|p|, |p' - p|), plus the
+    rounding allowance when inp_m and hp are given), the shipped value must be the rounding of some value in
+    [p' - delta, p' + delta], i.e. lie between bf16(p' - delta) and bf16(p' + delta).  Away from
+    cancellation delta is 1/400 of a bf16 step, so this is "exact, or the other neighbour when p' is
+    within delta of the midpoint"; where p and the step cancel (p' a million times smaller than its
+    operands) it is as wide as the fp32 result is allowed to be.  That the shipped value is exactly bf16
+    of the device's own fp32 master is checked separately by the callers.  Returns the number of mismatches."""
     import oracle
 
     want = ref["p_bf16"]
@@ -151,11 +230,9 @@ def check_bf16(got_bits: np.ndarray, ref: dict, inp_p: np.ndarray, tol: float = 
         return 0
     pp = ref["p"][bad]
     p_in = inp_p[bad].astype(np.float64)
+    delta = tol * np.maximum(np.abs(p_in), np.abs(pp - p_in))
     if inp_m is not None and hp is not None:
-        floor = np.maximum(np.abs(ref["p"]), master_floor(ref, inp_p, inp_m, hp, abs_g))[bad]
-    else:
-        floor = np.maximum(np.abs(pp), np.maximum(np.abs(p_in), np.abs(pp - p_in)))
-    delta = tol * floor
+        delta = delta + rounding_allowances(ref, inp_p, inp_m, hp, abs_g)[0][bad]
     lo = synth.bf16_bits_to_f32(oracle.cast(oracle.round_f32(pp - delta))).astype(np.float64)
     hi = synth.bf16_bits_to_f32(oracle.cast(oracle.round_f32(pp + delta))).astype(np.float64)
     g = synth.bf16_bits_to_f32(got_bits[bad]).astype(np.float64)

@@ -1,9 +1,21 @@
 """GPU parity at the workloads' full sizes, in the launch configuration bench.py times.
 
-The device runs the whole step (norm pass, then the fused update) on the full shard.  The
-oracle streams the same seeded inputs chunk by chunk on the host to get the full squared
-norm (so the clip scale is the oracle's own), then recomputes a seeded sample of chunks,
-plus the first and last elements and a bucket boundary, element by element."""
+The device runs the whole step (norm pass, then the fused update) on the full shard.  Then
+
+  * the oracle streams the same seeded inputs chunk by chunk on the host for the full squared norm (so
+    the clip scale is the oracle's own);
+  * master / m / v / bf16 are compared with the oracle element by element: on workloads 1 and 3 over the
+    WHOLE shard, chunk after chunk; workloads 2 and 4 (6.7 G and 4.1 G elements) are SAMPLED: the first
+    and the last 2^20 elements, a window around every bucket border (all 162 of workload 4), and a seeded
+    sixteenth of all chunks; workload 5 (inter-tensor) over every element of its 31 segments;
+  * two checks that need no oracle cover every element of every workload: the fused pass against the
+    unfused composition (reduce with the norm -> AdamW on the fp32 gradient -> cast) on a copy of the
+    state, bit for bit, and amsp_cast_param_shard of the device's own master against the bf16 the fused
+    pass wrote.
+
+Coverage is printed per workload."""
+from concurrent.futures import ThreadPoolExecutor
+
 import numpy as np
 import pytest
 
@@ -15,6 +27,9 @@ pytestmark = pytest.mark.gpu
 
 CHUNK = 1 << 24
 THREADS = 16
+WORKERS = 3          # chunks compared side by side (each with THREADS // WORKERS oracle threads)
+EDGE = 1 << 20       # elements compared at the very start and end of a sampled workload
+BORDER = 2048        # elements compared on either side of a bucket or segment border
 
 
 def _oracle_sqnorm_streamed(w, begin, n):
@@ -29,19 +44,75 @@ def _oracle_sqnorm_streamed(w, begin, n):
     return total
 
 
-def _sample_windows(w, n, count, width, seed):
+def _merge(ranges):
+    """Sorted, disjoint union of half-open ranges."""
+    out = []
+    for a, b in sorted(r for r in ranges if r[1] > r[0]):
+        if out and a <= out[-1][1]:
+            out[-1][1] = max(out[-1][1], b)
+        else:
+            out.append([a, b])
+    return [(a, b) for a, b in out]
+
+
+def _ranges_to_compare(n, full, borders, seed):
+    """Element ranges of [0, n) the oracle recomputes: everything, or the documented sample."""
+    if full:
+        return [(a, min(a + CHUNK, n)) for a in range(0, n, CHUNK)]
     rng = np.random.default_rng(seed)
-    starts = {0, n - width}
-    if w.bucket_elems:
-        nb = -(-n // w.bucket_elems)
-        for b in (1, nb // 2, nb - 1):                      # windows straddling bucket boundaries
-            starts.add(b * w.bucket_elems - width // 2)
-    while len(starts) < count:
-        starts.add(int(rng.integers(0, n - width)))
-    return sorted(starts)
+    chunks = [(a, min(a + CHUNK, n)) for a in range(0, n, CHUNK)]
+    picked = [chunks[i] for i in sorted(rng.choice(len(chunks), size=max(1, len(chunks) // 16), replace=False))]
+    edges = [(0, min(EDGE, n)), (max(0, n - EDGE), n)]
+    around = [(max(0, b - BORDER), min(n, b + BORDER)) for b in borders]
+    return _merge(picked + edges + around)
 
 
-def _run_fullsize(cfg, windows=24, width=1 << 16):
+class _Tally:
+    def __init__(self):
+        self.worst = dict(max_p=0.0, max_m=0.0, max_v=0.0, extra_p=0, extra_m=0, extra_v=0, mismatches=0, elements=0)
+
+    def add(self, st, mismatches):
+        for key in ("max_p", "max_m", "max_v"):
+            self.worst[key] = max(self.worst[key], st[key])
+        for key in ("extra_p", "extra_m", "extra_v"):
+            self.worst[key] += st[key]
+        self.worst["mismatches"] += mismatches
+        self.worst["elements"] += st["n"]
+
+    def finish(self):
+        w = self.worst
+        assert w["mismatches"] <= max(3, 1e-4 * w["elements"]), w
+        # on the workload's own inputs the rounding allowance is an exception: at most 1e-5 of the elements
+        assert max(w["extra_p"], w["extra_m"], w["extra_v"]) <= max(2, H.RARE * w["elements"]), w
+        return w
+
+
+def _compare(w, hp, scale, index0, lo, hi, dp, dm, dv, out, state_off, out_off, threads):
+    """Elements [lo, hi) of the range that starts at global index `index0`: the oracle's update of the seeded
+    inputs against the device's state[state_off + i] and out[out_off + i]."""
+    inp = H.host_inputs(w, index0 + lo, hi - lo, threads=threads)
+    G = oracle.reduce(inp.partials, threads=threads)
+    p1, m1, v1 = oracle.adamw(G, scale, inp.p, inp.m, inp.v, lr=hp["lr"], beta1=hp["beta1"], beta2=hp["beta2"],
+                              eps=hp["eps"], weight_decay=hp["weight_decay"], step=hp["step"], threads=threads)
+    ref = dict(G=G, scale=scale, p=p1, m=m1, v=v1, p_bf16=oracle.cast(oracle.round_f32(p1)))
+    sl = slice(state_off + lo, state_off + hi)
+    gp, gm, gv = dp[sl].cpu().numpy(), dm[sl].cpu().numpy(), dv[sl].cpu().numpy()
+    abs_g = H.abs_partials(inp.partials)
+    st = H.check_state(gp, gm, gv, ref, inp.p, inp.m, hp, abs_g=abs_g)
+    bits = H.dev_bits(out[out_off + lo:out_off + hi])
+    mism = H.check_bf16(bits, ref, inp.p, inp_m=inp.m, hp=hp, abs_g=abs_g)
+    assert np.array_equal(bits, oracle.cast(gp))             # the cast of the GPU's own fp32 is bit-exact
+    return st, mism
+
+
+def _compare_ranges(tally, ranges, *args):
+    with ThreadPoolExecutor(WORKERS) as ex:
+        for st, mism in ex.map(lambda r: _compare(*args[:4], r[0], r[1], *args[4:], max(1, THREADS // WORKERS)),
+                               ranges):
+            tally.add(st, mism)
+
+
+def _run_fullsize(cfg, full):
     import torch
 
     from paper_2311_00257_amd import binding as B
@@ -56,6 +127,7 @@ def _run_fullsize(cfg, windows=24, width=1 << 16):
     free, _ = torch.cuda.mem_get_info()
     if free < need:
         pytest.skip("needs %.0f GB of device memory, %.0f free" % (need / 1e9, free / 1e9))
+    cross = free >= need + n * 18 + (1 << 30)                # a copy of the state, an fp32 gradient, a second bf16
 
     print("workload %d (%s): n=%d k=%d on device" % (cfg, w.name, n, w.k), flush=True)
     parts = []
@@ -73,11 +145,37 @@ def _run_fullsize(cfg, windows=24, width=1 << 16):
     ws = torch.empty(B.amsp_workspace_bytes() // 8, dtype=torch.float64, device="cuda")
     d_s = torch.zeros(1, dtype=torch.float64, device="cuda")
     hp = H.hparams_of(w)
+    if cross:
+        p2, m2, v2 = dp.clone(), dm.clone(), dv.clone()
     B.amsp_grad_sqnorm(parts, None, n, d_s, ws, bucket_elems=w.bucket_elems)
     B.amsp_adamw_step_shard(parts, None, n, dp, dm, dv, out, B.AdamWHparams(d_total_sqnorm=d_s, **hp),
                             bucket_elems=w.bucket_elems)
     torch.cuda.synchronize()
     S_gpu = float(d_s.item())
+
+    # ---- every element, no oracle: the unfused composition on a copy of the state, and the stand-alone cast
+    if cross:
+        g32 = torch.empty(n, dtype=torch.float32, device="cuda")
+        out2 = torch.full((n,), 0x5A5A, dtype=torch.int16, device="cuda")
+        ws2 = torch.empty(B.amsp_reduce_workspace_bytes(n, w.bucket_elems) // 8, dtype=torch.float64, device="cuda")
+        d_s2 = torch.zeros(1, dtype=torch.float64, device="cuda")
+        B.amsp_reduce_grad_sqnorm_shard(parts, n, g32, d_s2, ws2, bucket_elems=w.bucket_elems)
+        assert abs(float(d_s2.item()) - S_gpu) <= 1e-12 * S_gpu          # same squares, another fixed order
+        d_s2.copy_(d_s)                                                  # the same scale bits for both compositions
+        B.amsp_adamw_step_shard(None, g32, n, p2, m2, v2, None, B.AdamWHparams(d_total_sqnorm=d_s2, **hp),
+                                bucket_elems=w.bucket_elems)
+        B.amsp_cast_param_shard(p2, out2, n)
+        torch.cuda.synchronize()
+        assert torch.equal(p2, dp) and torch.equal(m2, dm) and torch.equal(v2, dv) and torch.equal(out2, out)
+        del g32, ws2, p2, m2, v2
+        out2.fill_(0x5A5A)
+        B.amsp_cast_param_shard(dp, out2, n)
+        assert torch.equal(out2, out)
+        del out2
+        print("  all %d elements: fused == reduce -> AdamW(fp32 g) -> cast, and cast(master) == bf16 out, bit for bit"
+              % n, flush=True)
+    else:
+        print("  (no room for the copy of the state: unfused cross-check skipped)", flush=True)
 
     print("  oracle: streaming the full squared norm on the host", flush=True)
     S = _oracle_sqnorm_streamed(w, begin, n)
@@ -88,46 +186,44 @@ def _run_fullsize(cfg, windows=24, width=1 << 16):
     scale = oracle.clip_scale(S, hp["max_norm"], hp["clip_eps"])
     assert scale < 1.0                                       # clipping is active in every full workload
 
-    worst = dict(max_p=0.0, max_m=0.0, max_v=0.0, mismatches=0, elements=0)
-    for start in _sample_windows(w, n, windows, width, seed=cfg):
-        inp = H.host_inputs(w, begin + start, width, threads=THREADS)
-        G = oracle.reduce(inp.partials, threads=THREADS)
-        p1, m1, v1 = oracle.adamw(G, scale, inp.p, inp.m, inp.v, lr=hp["lr"], beta1=hp["beta1"], beta2=hp["beta2"],
-                                  eps=hp["eps"], weight_decay=hp["weight_decay"], step=hp["step"], threads=THREADS)
-        ref = dict(G=G, scale=scale, p=p1, m=m1, v=v1, p_bf16=oracle.cast(oracle.round_f32(p1)))
-        sl = slice(start, start + width)
-        gp, gm, gv = dp[sl].cpu().numpy(), dm[sl].cpu().numpy(), dv[sl].cpu().numpy()
-        abs_g = H.abs_partials(inp.partials)
-        st = H.check_state(gp, gm, gv, ref, inp.p, inp.m, hp, abs_g=abs_g)
-        bits = H.dev_bits(out[sl])
-        worst["mismatches"] += H.check_bf16(bits, ref, inp.p, inp_m=inp.m, hp=hp, abs_g=abs_g)
-        assert np.array_equal(bits, oracle.cast(gp))         # the cast of the GPU's own fp32 is bit-exact
-        for key in ("max_p", "max_m", "max_v"):
-            worst[key] = max(worst[key], st[key])
-        worst["elements"] += width
-    assert worst["mismatches"] <= max(3, 1e-4 * worst["elements"])
-    print("  sqnorm gpu %.12g oracle %.12g scale %.6g; sampled %s" % (S_gpu, S, scale, worst), flush=True)
+    borders = list(range(w.bucket_elems, n, w.bucket_elems)) if w.bucket_elems else []
+    ranges = _ranges_to_compare(n, full, borders, seed=cfg)
+    tally = _Tally()
+    _compare_ranges(tally, ranges, w, hp, scale, begin, dp, dm, dv, out, 0, 0)
+    worst = tally.finish()
+    covered = sum(b - a for a, b in ranges)
+    assert covered == worst["elements"] and (not full or covered == n)
+    print("  sqnorm gpu %.12g oracle %.12g scale %.6g" % (S_gpu, S, scale), flush=True)
+    print("  element-wise against the oracle: %d of %d elements (%.2f %%)%s, %d bucket borders: %s" % (
+        covered, n, 100.0 * covered / n, "" if full else " SAMPLED", len(borders), worst), flush=True)
 
 
 def test_workload1_llama7b_factor8_full():
-    _run_fullsize(1)
+    """Whole shard against the oracle, element by element."""
+    _run_fullsize(1, full=True)
 
 
 def test_workload3_llama13b_factor16_full():
-    _run_fullsize(3)
+    """Whole shard against the oracle, element by element."""
+    _run_fullsize(3, full=True)
 
 
 def test_workload4_llama30b_bucketed_full():
-    _run_fullsize(4)
+    """Sampled against the oracle (every one of the 162 bucket borders, the first and last 2^20 elements, a
+    seeded sixteenth of the chunks); every element against the unfused composition."""
+    _run_fullsize(4, full=False)
 
 
 def test_workload2_llama7b_full_replica_full():
-    _run_fullsize(2)
+    """Sampled against the oracle (the first and last 2^20 elements, a seeded sixteenth of the chunks); every
+    element against the unfused composition."""
+    _run_fullsize(2, full=False)
 
 
 def test_workload5_llama7b_inter_tensor_full():
     """LLaMA-7B, inter-tensor shards at factor 8: rank 3 selects its 31 segments (843 M elements) from
-    one all-reduced flat bf16 gradient buffer of the whole model."""
+    one all-reduced flat bf16 gradient buffer of the whole model.  Every element of every segment against
+    the oracle."""
     import torch
 
     from paper_2311_00257_amd import binding as B
@@ -174,32 +270,24 @@ def test_workload5_llama7b_inter_tensor_full():
     scale = oracle.clip_scale(S, hp["max_norm"], hp["clip_eps"])
     assert scale < 1.0
 
-    worst = dict(max_p=0.0, max_m=0.0, max_v=0.0, mismatches=0, elements=0)
-    rng = np.random.default_rng(5)
-    width = 1 << 15
-    for f, l, n in segs:                                    # one window at the start, end and a random place of every segment
-        wd = min(width, n)
-        for a in sorted({0, n - wd, int(rng.integers(0, n - wd + 1))}):
-            inp = H.host_inputs(w, f + a, wd, threads=THREADS)
-            G = oracle.reduce(inp.partials, threads=THREADS)
-            p1, m1, v1 = oracle.adamw(G, scale, inp.p, inp.m, inp.v, lr=hp["lr"], beta1=hp["beta1"],
-                                      beta2=hp["beta2"], eps=hp["eps"], weight_decay=hp["weight_decay"],
-                                      step=hp["step"], threads=THREADS)
-            ref = dict(G=G, scale=scale, p=p1, m=m1, v=v1, p_bf16=oracle.cast(oracle.round_f32(p1)))
-            sl = slice(l + a, l + a + wd)
-            gp = dp[sl].cpu().numpy()
-            abs_g = H.abs_partials(inp.partials)
-            st = H.check_state(gp, dm[sl].cpu().numpy(), dv[sl].cpu().numpy(), ref, inp.p, inp.m, hp, abs_g=abs_g)
-            bits = H.dev_bits(out[f + a:f + a + wd])
-            worst["mismatches"] += H.check_bf16(bits, ref, inp.p, inp_m=inp.m, hp=hp, abs_g=abs_g)
-            assert np.array_equal(bits, oracle.cast(gp))
-            for key in ("max_p", "max_m", "max_v"):
-                worst[key] = max(worst[key], st[key])
-            worst["elements"] += wd
-    assert worst["mismatches"] <= max(3, 1e-4 * worst["elements"])
+    tally = _Tally()
+    covered = 0
+    for f, l, n in segs:
+        ranges = _ranges_to_compare(n, True, [], seed=0)
+        _compare_ranges(tally, ranges, w, hp, scale, f, dp, dm, dv, out, l, f)
+        covered += sum(b - a for a, b in ranges)
+    worst = tally.finish()
+    assert covered == worst["elements"] == local
     # drop: the elements just outside every segment still hold the fill pattern
     for f, l, n in segs:
         for lo, hi in ((max(0, f - 64), f), (f + n, min(total, f + n + 64))):
             if hi > lo:
                 assert bool(torch.all(out[lo:hi] == 0x5A5A))
-    print("  sqnorm gpu %.12g oracle %.12g scale %.6g; sampled %s" % (S_gpu, S, scale, worst), flush=True)
+    # every element, no oracle: the stand-alone cast of each segment's master equals the bf16 written at its flat place
+    for f, l, n in segs:
+        tmp = torch.empty(n, dtype=torch.int16, device="cuda")
+        B.amsp_cast_param_shard(dp[l:l + n], tmp, n)
+        assert torch.equal(tmp, out[f:f + n])
+    print("  sqnorm gpu %.12g oracle %.12g scale %.6g" % (S_gpu, S, scale), flush=True)
+    print("  element-wise against the oracle: %d of %d elements (%.2f %%), all %d segments: %s"
+          % (covered, local, 100.0 * covered / local, len(segs), worst), flush=True)

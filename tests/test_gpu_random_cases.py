@@ -98,6 +98,7 @@ def test_random_cases_against_oracle(B, torch_mod):
     # AMSP_RANDOM_CASES / AMSP_RANDOM_SEED widen the sweep for an occasional long run
     rng = np.random.default_rng(int(os.environ.get("AMSP_RANDOM_SEED", "231100257")))
     worst = dict(max_p=0.0, max_m=0.0, max_v=0.0)
+    elements = extra = 0
     for idx in range(int(os.environ.get("AMSP_RANDOM_CASES", "400"))):
         c = _case(rng, idx)
         print("case", c, flush=True)
@@ -109,10 +110,15 @@ def test_random_cases_against_oracle(B, torch_mod):
         stats = H.check_state(p, m, v, ref, inp.p, inp.m, hp, abs_g=abs_g)
         for key in worst:
             worst[key] = max(worst[key], stats[key])
+        elements += stats["n"]
+        extra += max(stats["extra_p"], stats["extra_m"], stats["extra_v"])
         if bits is not None:
             assert np.array_equal(bits, oracle.cast(p)), c
             assert H.check_bf16(bits, ref, inp.p, inp_m=inp.m, hp=hp, abs_g=abs_g) <= max(3, 1e-4 * p.size), c
-    print("worst scaled relative errors over the sweep:", worst)
+    print("worst relative errors over the sweep: %s; %d of %d elements needed the rounding allowance" % (
+        worst, extra, elements))
+    # errors above 1e-5 of the denominator (covered only by the first-order rounding allowance) stay exceptions
+    assert extra <= max(2, H.RARE * elements), (extra, elements)
 
 
 def test_random_inter_tensor_models(B, torch_mod):
