@@ -49,8 +49,8 @@
  *     counted in elements): 0 processes [0,n) in one launch; U > 0 processes the buckets
  *     [bU, min((b+1)U, n)) in order, each bucket a range of its own with its own ragged head
  *     and tail; buckets of one call may share a launch.
- *   - One launch covers at most (2^31 - 1) * 64 elements (about 5.5e11, more than fits the device);
- *     a longer range, or a longer bucket, is AMSP_EINVAL.
+ *   - n is not limited by the launch size: a range (or a bucket) of more than 2^33 elements is cut
+ *     on the host into consecutive launches of at most 2^25 workgroups (2^33 elements) each.
  *   - n == 0 is valid: AMSP_OK, nothing launched (amsp_grad_sqnorm still writes 0 when
  *     accumulate == 0).
  *   - The reduction order over j = 0..k-1 is fixed and fp32, identical in every entry point,
@@ -105,7 +105,7 @@ int amsp_shard_range(uint64_t total_elems, uint32_t shard_factor, uint32_t rank,
  *   grad_out    device fp32[n]
  *   accumulate  0: overwrite; 1: add the sum to what grad_out holds (gradient accumulation
  *               over micro-batches, Section IV-C.3)
- * Errors: AMSP_EINVAL (k == 0, k > AMSP_MAX_K, range too long), AMSP_ENULL, AMSP_EALIGN, AMSP_EDEVICE.
+ * Errors: AMSP_EINVAL (k == 0, k > AMSP_MAX_K), AMSP_ENULL, AMSP_EALIGN, AMSP_EDEVICE.
  */
 int amsp_reduce_grad_shard(const uint16_t *const *partials, uint32_t k, uint64_t n,
                            uint64_t bucket_elems, float *grad_out, int accumulate, void *stream);

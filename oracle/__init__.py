@@ -22,13 +22,18 @@ _lib = None
 
 
 def build(force: bool = False) -> str:
-    """Compile the oracle with gcc -O2 (no fast-math) into ``libamsp_oracle.so``."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        tmp = _LIB + ".tmp%d" % os.getpid()
-        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-Wall", "-Wextra",
+    """Compile the oracle with gcc -O2 (no fast-math) into ``libamsp_oracle.so``.  With AMSP_ORACLE_UBSAN=1
+    in the environment (the sanitizer tier of the tests sets it for a run of the pins) a second library,
+    instrumented with -fsanitize=undefined and aborting on the first report, is built and used instead."""
+    ubsan = os.environ.get("AMSP_ORACLE_UBSAN") == "1"
+    lib = _LIB.replace(".so", "_ubsan.so") if ubsan else _LIB
+    if force or not os.path.exists(lib) or os.path.getmtime(lib) < os.path.getmtime(_SRC):
+        tmp = lib + ".tmp%d" % os.getpid()
+        flags = ["-O1", "-g", "-fsanitize=undefined", "-fno-sanitize-recover=all"] if ubsan else ["-O2"]
+        subprocess.check_call(["gcc", *flags, "-std=c11", "-fPIC", "-shared", "-Wall", "-Wextra",
                                "-o", tmp, _SRC, "-lm"])
-        os.replace(tmp, _LIB)
-    return _LIB
+        os.replace(tmp, lib)
+    return lib
 
 
 def _bind(lib):

@@ -163,7 +163,7 @@ __device__ __forceinline__ float grad1(const PartialPtrs &pp, int k, const float
 
 using amsp_geom::Span;
 using amsp_geom::Buckets;
-static_assert(kRwThreads == amsp_geom::kWaveLanes, "the geometry assumes one-wave workgroups on the vector path");
+static_assert(kRwThreads == amsp_geom::kWaveLanes && kNormThreads == amsp_geom::kWaveLanes, "the geometry assumes one-wave workgroups on the vector path");
 
 // Element index of the t-th edge element, t < head + tail.
 template <int VEC>
@@ -322,8 +322,7 @@ constexpr int norm_unroll() {
 }
 constexpr int norm_waves_per_cu(int K) { return K < 0 ? 8 : 4; }   // run-time k (> 16): a sequential loop over j, so more waves
 
-// acc += sum of g^2 over one range.  Block b's trip t covers the U consecutive wave pieces that start at
-// vector (t * grid + b) * 64 * U.
+// acc += sum of g^2 over one range, its vectors visited as amsp_geom::norm_walk lays down.
 // The range's head and tail (element by element, a few trips of one wave) go to block `edge_block`:
 // a different block for every range of a launch, so that no block collects the edges of all of them.
 template <int K, int VEC>
@@ -331,21 +330,21 @@ __device__ __forceinline__ double sqnorm_span(const PartialPtrs &pp, int k, cons
                                               const uint64_t base, const Span &s, const uint32_t edge_block,
                                               double acc) {
     constexpr int U = norm_unroll<K>();
-    const uint64_t row = (uint64_t)gridDim.x * kNormThreads;   // vectors the grid takes per piece index
     if (s.vectorised) {
-        uint64_t v = (uint64_t)blockIdx.x * (kNormThreads * U) + threadIdx.x;
-        if constexpr (U > 1) {
-            constexpr int KS = K == 0 ? 1 : K;
-            typedef typename Bf16Words<VEC == 8 ? 8 : 4>::type W;
-            for (; v + (U - 1) * kNormThreads < s.nvec; v += U * row) {
+        constexpr int KS = K <= 0 ? 1 : K;
+        typedef typename Bf16Words<VEC == 8 ? 8 : 4>::type W;
+        const uint64_t first = base + s.head;
+        amsp_geom::norm_walk<U>(
+            s.nvec, gridDim.x, blockIdx.x, threadIdx.x,
+            [&](uint64_t v) {   // U vectors, every load in flight before the first is used
                 f32x4 a[U];
                 W w[U][KS];
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
-                    const uint64_t e = base + s.head + (v + u * kNormThreads) * VEC;
+                    const uint64_t e = first + (v + (uint64_t)u * kNormThreads) * VEC;
                     if constexpr (K == 0) {
                         a[u] = ld_stream(reinterpret_cast<const f32x4 *>(gf32 + e));
-                    } else {
+                    } else if constexpr (K > 0) {
 #pragma unroll
                         for (int j = 0; j < KS; ++j) w[u][j] = ld_stream(reinterpret_cast<const W *>(pp.p[j] + e));
                     }
@@ -356,7 +355,7 @@ __device__ __forceinline__ double sqnorm_span(const PartialPtrs &pp, int k, cons
                     float g[VEC];
                     if constexpr (K == 0) {
                         g[0] = a[u].x; g[1] = a[u].y; g[2] = a[u].z; g[3] = a[u].w;
-                    } else {
+                    } else if constexpr (K > 0) {
                         widen_first<VEC>(w[u][0], g);
 #pragma unroll
                         for (int j = 1; j < KS; ++j) widen_add<VEC>(w[u][j], g);
@@ -364,21 +363,20 @@ __device__ __forceinline__ double sqnorm_span(const PartialPtrs &pp, int k, cons
 #pragma unroll
                     for (int c = 0; c < VEC; ++c) acc = fma((double)g[c], (double)g[c], acc);
                 }
-            }
-        }
-        // U > 1: the pieces (fewer than U) of the block's last, partial trip; U == 1: every trip
-        for (; v < s.nvec; v += (U > 1 ? (uint64_t)kNormThreads : row)) {
-            float g[VEC];
-            grad_vec<K, VEC>(pp, k, gf32, base + s.head + v * VEC, g);
+            },
+            [&](uint64_t v) {
+                float g[VEC];
+                grad_vec<K, VEC>(pp, k, gf32, first + v * VEC, g);
 #pragma unroll
-            for (int c = 0; c < VEC; ++c) acc = fma((double)g[c], (double)g[c], acc);
-        }
+                for (int c = 0; c < VEC; ++c) acc = fma((double)g[c], (double)g[c], acc);
+            });
         if (blockIdx.x == edge_block)
             for (uint32_t t = threadIdx.x; t < s.head + s.tail; t += kNormThreads) {
                 const double g = (double)grad1<K>(pp, k, gf32, base + edge_elem<VEC>(s, t));
                 acc = fma(g, g, acc);
             }
     } else {
+        const uint64_t row = (uint64_t)gridDim.x * kNormThreads;
         for (uint64_t i = (uint64_t)blockIdx.x * kNormThreads + threadIdx.x; i < s.n; i += row) {
             double g = (double)grad1<K>(pp, k, gf32, base + i);
             acc = fma(g, g, acc);

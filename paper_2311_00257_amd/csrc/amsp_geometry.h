@@ -73,6 +73,22 @@ AMSP_HOST_DEVICE inline void block_range(const Buckets &bk, uint32_t block, int 
     }
 }
 
+// The read-only pass over a range's nvec vectors: a persistent grid of `grid` one-wave blocks.  Block b's
+// trip t covers the U consecutive wave pieces (kWaveLanes vectors each) that start at vector
+// (t * grid + b) * kWaveLanes * U, so that a trip of the whole grid is one contiguous window of every
+// stream.  full(v): lane's vectors v, v + kWaveLanes, ..., v + (U - 1) kWaveLanes are all inside the range
+// (their loads are issued together); one(v): a single vector, the pieces (fewer than U) of the block's
+// last, partial trip, or with U == 1 every trip.  Every vector in [0, nvec) is visited exactly once.
+template <int U, typename Full, typename One>
+AMSP_HOST_DEVICE inline void norm_walk(uint64_t nvec, uint32_t grid, uint32_t block, uint32_t lane, Full full,
+                                       One one) {
+    const uint64_t row = (uint64_t)grid * kWaveLanes;   // vectors the grid takes per piece index
+    uint64_t v = (uint64_t)block * (kWaveLanes * U) + lane;
+    if (U > 1)
+        for (; v + (uint64_t)(U - 1) * kWaveLanes < nvec; v += (uint64_t)U * row) full(v);
+    for (; v < nvec; v += (U > 1 ? (uint64_t)kWaveLanes : row)) one(v);
+}
+
 // ---------------------------------------------------------------- host side
 struct Stream {
     const void *ptr;
@@ -138,6 +154,26 @@ inline Span make_span(uint64_t n, const Stream *st, int ns, int vec) {
         break;
     }
     return s;
+}
+
+// A launch is given at most kMaxLaunchBlocks workgroups (2^25: 8.6e9 elements of the kernels that write,
+// above the largest launch the workloads make, 2.6e7 workgroups; the hardware's own limit is 2^31 - 1).
+// Longer ranges are cut on the host into consecutive pieces, each an ordinary launch with its own head and
+// tail; a piece's length is a multiple of 1024 elements, so every piece after the first starts at the
+// alignment phase of the range's own start.
+constexpr uint64_t kMaxLaunchBlocks = 1ull << 25;
+constexpr uint64_t kElemsPerBlock = (uint64_t)kWaveLanes * 4;   // one-wave workgroups, 4 elements per lane
+constexpr uint64_t kMaxLaunchElems = kMaxLaunchBlocks * kElemsPerBlock;
+
+// Calls f(off, len) for the pieces of [begin, begin + n): consecutive, disjoint, covering, each of at most
+// `limit` elements (a multiple of 1024).  Stops at the first non-zero return and hands it on.
+template <typename F>
+inline int for_pieces(uint64_t begin, uint64_t n, uint64_t limit, F f) {
+    for (uint64_t off = 0; off < n; off += limit) {
+        const int rc = f(begin + off, n - off < limit ? n - off : limit);
+        if (rc != 0) return rc;
+    }
+    return 0;
 }
 
 // Geometry of one launch over the buckets of [0, n) whose streams start at `st`; false when the streams

@@ -50,15 +50,27 @@ typedef amsp_geom::Stream Stream16;
 using amsp_geom::make_span;
 using amsp_geom::make_buckets;
 
-// Calls f(off, len, U).  U == 0: one launch over the single range [off, off + len).  U > 0: one launch
-// over the buckets of U elements of [off, off + len): as many buckets as the grid limit allows.
+using amsp_geom::for_pieces;
+using amsp_geom::kMaxLaunchBlocks;
+using amsp_geom::kMaxLaunchElems;
+
+// Calls f(off, len, U), one call per launch.  U == 0: a launch over the single range [off, off + len),
+// len <= kMaxLaunchElems (a flat range, or a bucket, longer than that is cut into pieces).  U > 0: a launch
+// over the buckets of U elements of [off, off + len): as many buckets as kMaxLaunchBlocks workgroups allow.
 template <typename F>
 int for_bucket_launches(uint64_t n, uint64_t bucket_elems, F f) {
-    if (bucket_elems == 0 || bucket_elems >= n) return f((uint64_t)0, n, (uint64_t)0);
-    const uint64_t blocks_per_bucket = bucket_elems / ((uint64_t)kRwThreads * kVecRW) + 1;
-    uint64_t per_launch = kMaxGrid / blocks_per_bucket;
-    if (per_launch == 0) per_launch = 1;
-    const uint64_t step = per_launch > (~0ull) / bucket_elems ? n : per_launch * bucket_elems;
+    auto piece = [&](uint64_t off, uint64_t len) { return f(off, len, (uint64_t)0); };
+    if (bucket_elems == 0 || bucket_elems >= n) return for_pieces(0, n, kMaxLaunchElems, piece);
+    if (bucket_elems >= kMaxLaunchElems) {   // every bucket needs several launches of its own
+        for (uint64_t off = 0; off < n; off += bucket_elems) {
+            const int rc = for_pieces(off, n - off < bucket_elems ? n - off : bucket_elems, kMaxLaunchElems, piece);
+            if (rc != AMSP_OK) return rc;
+        }
+        return AMSP_OK;
+    }
+    const uint64_t blocks_per_bucket = bucket_elems / ((uint64_t)kRwThreads * kVecRW) + 1;   // <= kMaxLaunchBlocks
+    const uint64_t per_launch = kMaxLaunchBlocks / blocks_per_bucket;                          // >= 1
+    const uint64_t step = per_launch * bucket_elems;                                           // < 2^34: no overflow
     for (uint64_t off = 0; off < n; off += step) {
         const uint64_t len = n - off < step ? n - off : step;
         const int rc = f(off, len, bucket_elems);
@@ -141,7 +153,7 @@ struct RwLaunch {
 RwLaunch rw_launch(const Span &s, unsigned load_bytes_per_lane, RwTarget t) {
     const uint64_t work = s.vectorised ? s.nvec : s.n;
     const unsigned threads = s.vectorised ? kRwThreads : kThreads;
-    uint64_t blocks = (work + threads - 1) / threads;   // <= kMaxGrid: the entry points refuse larger launches
+    uint64_t blocks = (work + threads - 1) / threads;   // <= kMaxLaunchBlocks: longer ranges come in pieces
     if (blocks == 0) blocks = 1;
     return RwLaunch{dim3((unsigned)blocks), dim3(threads),
                     s.vectorised ? occupancy_lds(load_bytes_per_lane, t) : 0u};
@@ -162,8 +174,11 @@ uint64_t reduce_norm_grid(const Span &s) {
     return blocks == 0 ? 1 : blocks;
 }
 
-// Upper bound of reduce_norm_grid over every alignment of a launch of `len` elements.
-uint64_t reduce_norm_blocks_max(uint64_t len) { return len / ((uint64_t)kRwThreads * kVecRW) + 2; }
+// Upper bound of the block sums one range of `len` elements leaves, over every alignment: one per 256
+// elements and two more (a ragged head and tail) for each launch the range is cut into.
+uint64_t reduce_norm_blocks_max(uint64_t len) {
+    return len / ((uint64_t)kRwThreads * kVecRW) + 2 * (len / kMaxLaunchElems + 1);
+}
 
 // Block sums of every bucket of a call lie side by side and are added once, after the last bucket.
 uint64_t reduce_norm_slots(uint64_t n, uint64_t bucket_elems) {
@@ -201,13 +216,6 @@ int wide_grid(const Span &s) {
     if (cap > kNormBlocks) cap = kNormBlocks;
     if (blocks > cap) blocks = cap;
     return blocks == 0 ? 1 : (int)blocks;
-}
-
-// One launch covers at most this many elements (one wave per 256 of them in a grid of < 2^31 blocks):
-// about 5.5e11, beyond any buffer that fits the device.
-constexpr uint64_t kMaxLaunchElems = kMaxGrid * (uint64_t)kRwThreads;
-bool too_long(uint64_t n, uint64_t bucket_elems) {
-    return ((bucket_elems != 0 && bucket_elems < n) ? bucket_elems : n) > kMaxLaunchElems;
 }
 
 bool misaligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
@@ -539,15 +547,17 @@ int amsp_shard_range(uint64_t total_elems, uint32_t shard_factor, uint32_t rank,
 
 int amsp_cast_param_shard(const float *master, uint16_t *param_bf16_out, uint64_t n, void *stream) {
     if (n == 0) return AMSP_OK;
-    if (too_long(n, 0)) return AMSP_EINVAL;
     if (master == nullptr || param_bf16_out == nullptr) return AMSP_ENULL;
     if (misaligned(master, 4) || misaligned(param_bf16_out, 2)) return AMSP_EALIGN;
-    Stream16 st[2] = {{master, 4}, {param_bf16_out, 2}};
-    Span s = make_span(n, st, 2, kVecRW);
     clear_stale_error();
-    const RwLaunch L = rw_launch(s, 16, adamw_target(16));
-    hipLaunchKernelGGL(cast_kernel, L.grid, L.block, L.lds, (hipStream_t)stream, master, param_bf16_out, s);
-    return launched();
+    return for_pieces(0, n, kMaxLaunchElems, [&](uint64_t off, uint64_t len) -> int {
+        Stream16 st[2] = {{master + off, 4}, {param_bf16_out + off, 2}};
+        Span s = make_span(len, st, 2, kVecRW);
+        const RwLaunch L = rw_launch(s, 16, adamw_target(16));
+        hipLaunchKernelGGL(cast_kernel, L.grid, L.block, L.lds, (hipStream_t)stream, master + off,
+                           param_bf16_out + off, s);
+        return launched();
+    });
 }
 
 size_t amsp_reduce_workspace_bytes(uint64_t n, uint64_t bucket_elems) {
@@ -577,7 +587,6 @@ static int reduce_range(const uint16_t *const *partials, uint32_t k, uint64_t n,
         }
         return AMSP_OK;
     }
-    if (too_long(n, bucket_elems)) return AMSP_EINVAL;
     if (grad_out == nullptr) return AMSP_ENULL;
     if (misaligned(grad_out, 4)) return AMSP_EALIGN;
     uint64_t used = 0;   // block sums written so far, bucket after bucket
@@ -731,7 +740,6 @@ static int adamw_step_range(const uint16_t *const *partials, uint32_t k, const f
         if (rc != AMSP_OK) return rc;
     }
     if (n == 0) return AMSP_OK;
-    if (too_long(n, bucket_elems)) return AMSP_EINVAL;
     if (master == nullptr || exp_avg == nullptr || exp_avg_sq == nullptr) return AMSP_ENULL;
     if (k == 0 && grad_f32 == nullptr) return AMSP_ENULL;
     if (misaligned(master, 4) || misaligned(exp_avg, 4) || misaligned(exp_avg_sq, 4) ||
@@ -900,7 +908,6 @@ int amsp_reduce_grad_segments(const uint16_t *const *partials_flat, uint32_t k, 
     for (uint32_t i = 0; i < num_segments; ++i) {
         if (segments[i].length == 0) continue;
         if (grad_f32_local == nullptr) return AMSP_ENULL;
-        if (too_long(segments[i].length, 0)) return AMSP_EINVAL;
     }
     if (misaligned(grad_f32_local, 4)) return AMSP_EALIGN;
     hipStream_t hs = (hipStream_t)stream;
@@ -974,7 +981,6 @@ int amsp_adamw_step_segments(const uint16_t *const *partials_flat, uint32_t k, c
         if (master_local == nullptr || exp_avg_local == nullptr || exp_avg_sq_local == nullptr ||
             (k == 0 && grad_f32_local == nullptr))
             return AMSP_ENULL;
-        if (too_long(segments[i].length, 0)) return AMSP_EINVAL;
     }
     if (misaligned(master_local, 4) || misaligned(exp_avg_local, 4) || misaligned(exp_avg_sq_local, 4) ||
         (k == 0 && misaligned(grad_f32_local, 4)) || (param_bf16_flat && misaligned(param_bf16_flat, 2)))
@@ -1054,15 +1060,17 @@ int amsp_adamw_step_segments(const uint16_t *const *partials_flat, uint32_t k, c
 int amsp_cast_param_fp8_shard(const float *master, uint64_t n, const float *d_scale, uint8_t *param_fp8_out,
                               void *stream) {
     if (n == 0) return AMSP_OK;
-    if (too_long(n, 0)) return AMSP_EINVAL;
     if (master == nullptr || d_scale == nullptr || param_fp8_out == nullptr) return AMSP_ENULL;
     if (misaligned(master, 4) || misaligned(d_scale, 4)) return AMSP_EALIGN;
-    Stream16 st[2] = {{master, 4}, {param_fp8_out, 1}};
-    Span s = make_span(n, st, 2, 4);
     clear_stale_error();
-    const RwLaunch L = rw_launch(s, 16, adamw_target(16));
-    hipLaunchKernelGGL(cast_fp8_kernel, L.grid, L.block, L.lds, (hipStream_t)stream, master, d_scale, param_fp8_out, s);
-    return launched();
+    return for_pieces(0, n, kMaxLaunchElems, [&](uint64_t off, uint64_t len) -> int {
+        Stream16 st[2] = {{master + off, 4}, {param_fp8_out + off, 1}};
+        Span s = make_span(len, st, 2, 4);
+        const RwLaunch L = rw_launch(s, 16, adamw_target(16));
+        hipLaunchKernelGGL(cast_fp8_kernel, L.grid, L.block, L.lds, (hipStream_t)stream, master + off, d_scale,
+                           param_fp8_out + off, s);
+        return launched();
+    });
 }
 
 int amsp_fp8_payload_segments(const float *master_local, uint64_t local_elems, const amsp_segment *segments,

@@ -2,7 +2,9 @@
 // and bucket sizes, emulate every block and lane of a launch and verify that
 //   - every element of [0, n) is touched exactly once (head, vectors, tail; across all buckets),
 //   - every vector access of every stream is aligned for its width,
-//   - the best alignment level that exists is the one taken (a wave's piece, else a line, else a vector).
+//   - the best alignment level that exists is the one taken (a wave's piece, else a line, else a vector),
+// and, for the persistent read-only pass, that the trips of all blocks and lanes visit every vector of a
+// range exactly once, never one outside it, with the vectors of a "full" trip all inside the range.
 // Prints "ok <cases>" and exits 0, or names the failing case and exits 1.
 #include <stdint.h>
 #include <stdio.h>
@@ -134,7 +136,69 @@ static int check(const Case &c) {
     return 0;
 }
 
+// The read-only pass: every (block, lane) of a persistent grid walks its trips; count the visits per vector.
+template <int U>
+static int check_norm_walk(uint64_t nvec, uint32_t grid) {
+    std::vector<uint8_t> seen(nvec, 0);
+    int bad = 0;
+    for (uint32_t block = 0; block < grid && !bad; ++block)
+        for (uint32_t lane = 0; lane < (uint32_t)kWaveLanes && !bad; ++lane)
+            norm_walk<U>(
+                nvec, grid, block, lane,
+                [&](uint64_t v) {
+                    for (int u = 0; u < U; ++u) {
+                        const uint64_t x = v + (uint64_t)u * kWaveLanes;
+                        if (x >= nvec) { bad = 1; return; }
+                        // the U pieces of a trip are consecutive: one contiguous window per block
+                        if (x / kWaveLanes != v / kWaveLanes + (uint64_t)u || x % kWaveLanes != lane) { bad = 1; return; }
+                        ++seen[x];
+                    }
+                },
+                [&](uint64_t v) {
+                    if (v >= nvec || v % kWaveLanes != lane) { bad = 1; return; }
+                    ++seen[v];
+                });
+    for (uint64_t v = 0; v < nvec && !bad; ++v)
+        if (seen[v] != 1) bad = 1;
+    if (bad) printf("FAIL: norm walk U=%d nvec=%llu grid=%u\n", U, (unsigned long long)nvec, grid);
+    return bad;
+}
+
+// Ranges longer than a launch: the pieces tile the range in order, none longer than the limit, and (the
+// limit being a multiple of 1024 elements) every piece starts at the alignment phase of the range's start.
+static int check_pieces(uint64_t begin, uint64_t n, uint64_t limit) {
+    uint64_t next = begin, count = 0;
+    const int rc = for_pieces(begin, n, limit, [&](uint64_t off, uint64_t len) -> int {
+        if (off != next || len == 0 || len > limit || (off - begin) % 1024 != 0) return 7;
+        next = off + len;
+        ++count;
+        return 0;
+    });
+    if (rc != 0 || next != begin + n || count != (n + limit - 1) / limit) {
+        printf("FAIL: pieces begin=%llu n=%llu limit=%llu\n", (unsigned long long)begin, (unsigned long long)n,
+               (unsigned long long)limit);
+        return 1;
+    }
+    // an error stops the walk and is handed on
+    int calls = 0;
+    if (n > limit && (for_pieces(begin, n, limit, [&](uint64_t, uint64_t) { return ++calls == 1 ? -5 : 0; }) != -5 || calls != 1)) return 1;
+    return 0;
+}
+
 int main() {
+    static_assert(kMaxLaunchElems % 1024 == 0 && kMaxLaunchElems == kMaxLaunchBlocks * 256, "piece length");
+    if (check_pieces(0, 0, kMaxLaunchElems) || check_pieces(5, 1, kMaxLaunchElems) ||
+        check_pieces(0, kMaxLaunchElems, kMaxLaunchElems) || check_pieces(3, kMaxLaunchElems + 1, kMaxLaunchElems) ||
+        check_pieces(0, 5 * kMaxLaunchElems - 1, kMaxLaunchElems) || check_pieces(1ull << 40, (1ull << 36) + 12345, kMaxLaunchElems))
+        return 1;
+    for (int iter = 0; iter < 2000; ++iter)
+        if (check_pieces(below(1ull << 40), below(1ull << 20), 1024 * (1 + below(64)))) return 1;
+    for (int iter = 0; iter < 3000; ++iter) {
+        const uint64_t nvec = below(4) == 0 ? below(70) : below(30000);
+        const uint32_t grid = 1 + (uint32_t)below(below(2) ? 8 : 48);
+        if (check_norm_walk<1>(nvec, grid) || check_norm_walk<4>(nvec, grid) || check_norm_walk<8>(nvec, grid)) return 1;
+    }
+
     const uint64_t lengths[] = {1, 2, 3, 4, 5, 63, 64, 65, 255, 256, 257, 258, 259, 260, 511, 512, 513, 1023, 1024, 1025};
     const uint64_t buckets[] = {0, 0, 1, 2, 3, 4, 5, 7, 63, 64, 255, 256, 257, 258, 259, 260, 261, 300, 511, 512, 513, 1000, 1025};
     int cases = 0;

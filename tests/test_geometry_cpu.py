@@ -53,6 +53,18 @@ MUTATIONS = [
      "return (uintptr_t)vec * elem < 16 ? (uintptr_t)vec * elem : 16;", "return elem;"),
     ("period of the line level taken from the widest element",
      "if (st[i].elem < smallest) smallest = st[i].elem;", "if (st[i].elem > smallest) smallest = st[i].elem;"),
+    ("norm pass: a trip's pieces not counted into the block's start",
+     "uint64_t v = (uint64_t)block * (kWaveLanes * U) + lane;", "uint64_t v = (uint64_t)block * kWaveLanes + lane;"),
+    ("norm pass: the grid advances by one piece per trip",
+     "v += (uint64_t)U * row) full(v);", "v += row) full(v);"),
+    ("norm pass: a full trip taken when only its first piece is inside",
+     "for (; v + (uint64_t)(U - 1) * kWaveLanes < nvec;", "for (; v < nvec;"),
+    ("long range: the last piece as long as the others",
+     "const int rc = f(begin + off, n - off < limit ? n - off : limit);", "const int rc = f(begin + off, limit);"),
+    ("long range: pieces overlap by one element",
+     "for (uint64_t off = 0; off < n; off += limit) {", "for (uint64_t off = 0; off < n; off += limit - 1) {"),
+    ("norm pass: the partial last trip walks a grid row apart",
+     "v += (U > 1 ? (uint64_t)kWaveLanes : row)) one(v);", "v += row) one(v);"),
 ]
 
 

@@ -150,10 +150,11 @@ def test_table_iv_rows_are_feasible_and_priced():
         assert 2 * phi / sp + 2 * phi / sg + 12 * phi / so < 80e9       # fits an 80 GB GPU (Section VI)
 
 
-def test_library_search_equals_the_exhaustive_oracle():
-    rng = np.random.default_rng(21)
-    checked = 0
-    for trial in range(60):
+def random_problems(trials=60, seed=21):
+    """Seeded planner problems: argument tuples of P.plan / B.amsp_plan_sharding, with ring-model
+    profiles, some of them with holes."""
+    rng = np.random.default_rng(seed)
+    for trial in range(trials):
         R = int(rng.choice([1, 2, 4, 6, 8]))
         N = int(rng.choice([1, 2, 3, 4, 6, 8]))
         table = ring_table(R, N, intra=float(rng.uniform(50e9, 400e9)), inter=float(rng.uniform(5e9, 60e9)),
@@ -165,7 +166,12 @@ def test_library_search_equals_the_exhaustive_oracle():
         M = int(rng.integers(1, 9))
         U = float(rng.choice([25e6, 256e6, 1e9]))
         mem = float(rng.uniform(0.3, 18.0)) * phi
-        args = (phi, int(rng.integers(1, 80)), mods, M, U, R, N, mem, float(rng.uniform(0, 0.2)) * phi, 1e8, table)
+        yield (phi, int(rng.integers(1, 80)), mods, M, U, R, N, mem, float(rng.uniform(0, 0.2)) * phi, 1e8, table)
+
+
+def test_library_search_equals_the_exhaustive_oracle():
+    checked = 0
+    for args in random_problems():
         want, count = P.plan(*args)
         if want is None:
             with pytest.raises(B.AmspError) as ei:
