@@ -41,6 +41,9 @@ def parse_args():
     ap.add_argument("--no-others", action="store_true",
                     help="skip the short runs of the other workloads (default run of workload 1 only)")
     ap.add_argument("--other-steps", type=int, default=8, help="timed steps of each of the other workloads")
+    ap.add_argument("--stagger", type=int, default=4096,
+                    help="bytes by which consecutive streams' bases are shifted inside their allocations "
+                         "(paper_2311_00257_amd/layout.py; 0 = plain allocations, all on 2 MiB boundaries)")
     ap.add_argument("--cpu-sample-elems", type=int, default=512 * 1024 * 1024)
     ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "adamw_kernel_llama7b_s8r3_k8_hbm_traffic.txt"),
                     help="rocprofv3 --pmc summary holding the fused kernel's measured HBM bytes per launch")
@@ -113,11 +116,13 @@ def cpu_baseline(w, begin, sample):
             "single_thread_value": res["one"], "nproc": os.cpu_count(), "usable_cpus": usable}
 
 
-def alt_step(steps, warmup, torch, B, w, n, parts, master, exp_avg, exp_avg_sq, param_bf16, d_sqnorm):
+def alt_step(steps, warmup, torch, B, w, n, parts, master, exp_avg, exp_avg_sq, param_bf16, d_sqnorm, stagger):
     """The other composition of the same steps, timed after the primary one: amsp_reduce_grad_sqnorm_shard
     writes the fp32 gradient (2k + 4 bytes/element), then amsp_adamw_step_shard on that
     gradient with the bf16 cast (30 bytes/element): 2k + 34 in all instead of 4k + 26."""
-    g32 = torch.empty(n, dtype=torch.float32, device="cuda")
+    from paper_2311_00257_amd import layout
+
+    (g32,) = layout.staggered_empty([(n, torch.float32)], stagger, first_index=4 + w.k)   # the next stream in line
     ws = torch.empty(B.amsp_reduce_workspace_bytes(n, w.bucket_elems) // 8, dtype=torch.float64, device="cuda")
 
     def step(t, ev=None):
@@ -159,7 +164,7 @@ def run_workload(args, config_id, steps, warmup, headline):
     import torch
 
     from paper_2311_00257_amd import binding as B
-    from paper_2311_00257_amd import synth, synth_device, workloads
+    from paper_2311_00257_amd import layout, synth, synth_device, workloads
 
     w = workloads.get(config_id)
     k = w.k
@@ -176,18 +181,14 @@ def run_workload(args, config_id, steps, warmup, headline):
         n = end - begin - w.drop_tail
         launches = 1                       # the buckets of one call share a launch (until the grid limit)
         buckets = 1 if not w.bucket_elems else -(-n // w.bucket_elems)
-        parts = []
+        # the streams' bases shifted against each other inside their allocations (see layout.py)
+        master, exp_avg, exp_avg_sq, param_bf16, *parts = layout.staggered_empty(
+            [(n, torch.float32)] * 3 + [(n, torch.int16)] * (1 + k), args.stagger)
         for j in range(k):
-            t = torch.empty(n, dtype=torch.int16, device="cuda")
-            synth_device.fill_bf16(t, w.key(synth.TENSOR_PARTIAL0 + j), begin, w.sigma_grad)
-            parts.append(t)
-        master = torch.empty(n, dtype=torch.float32, device="cuda")
-        exp_avg = torch.empty(n, dtype=torch.float32, device="cuda")
-        exp_avg_sq = torch.empty(n, dtype=torch.float32, device="cuda")
+            synth_device.fill_bf16(parts[j], w.key(synth.TENSOR_PARTIAL0 + j), begin, w.sigma_grad)
         synth_device.fill_f32(master, w.key(synth.TENSOR_MASTER), begin, w.sigma_param)
         synth_device.fill_f32(exp_avg, w.key(synth.TENSOR_EXP_AVG), begin, w.sigma_m)
         synth_device.fill_f32(exp_avg_sq, w.key(synth.TENSOR_EXP_AVG_SQ), begin, w.scale_v, absolute=True)
-        param_bf16 = torch.empty(n, dtype=torch.int16, device="cuda")
 
         def norm_pass():
             B.amsp_grad_sqnorm(parts, None, n, d_sqnorm, workspace, bucket_elems=w.bucket_elems)
@@ -202,19 +203,14 @@ def run_workload(args, config_id, steps, warmup, headline):
         segs, n = B.amsp_owned_segments(sizes, owner, w.rank)
         begin, launches, buckets = 0, len(segs), 1
         seg_tuples, segs = segs, B.marshal_segments(segs)      # the C array, built once
-        parts = []
+        master, exp_avg, exp_avg_sq, param_bf16, *parts = layout.staggered_empty(
+            [(n, torch.float32)] * 3 + [(total, torch.int16)] * (1 + k), args.stagger)
         for j in range(k):
-            t = torch.empty(total, dtype=torch.int16, device="cuda")
-            synth_device.fill_bf16(t, w.key(synth.TENSOR_PARTIAL0 + j), 0, w.sigma_grad)
-            parts.append(t)
-        master = torch.empty(n, dtype=torch.float32, device="cuda")
-        exp_avg = torch.empty(n, dtype=torch.float32, device="cuda")
-        exp_avg_sq = torch.empty(n, dtype=torch.float32, device="cuda")
+            synth_device.fill_bf16(parts[j], w.key(synth.TENSOR_PARTIAL0 + j), 0, w.sigma_grad)
         for f, l, m in seg_tuples:
             synth_device.fill_f32(master[l:l + m], w.key(synth.TENSOR_MASTER), f, w.sigma_param)
             synth_device.fill_f32(exp_avg[l:l + m], w.key(synth.TENSOR_EXP_AVG), f, w.sigma_m)
             synth_device.fill_f32(exp_avg_sq[l:l + m], w.key(synth.TENSOR_EXP_AVG_SQ), f, w.scale_v, absolute=True)
-        param_bf16 = torch.empty(total, dtype=torch.int16, device="cuda")
 
         def norm_pass():
             B.amsp_grad_sqnorm_segments(parts, total, segs, d_sqnorm, workspace)
@@ -271,7 +267,8 @@ def run_workload(args, config_id, steps, warmup, headline):
         "steps": steps,
         "warmup": warmup,
         "config": {"workload": w.name, "elements": n, "k": k, "shard_factor": w.shard_factor, "rank": w.rank,
-                   "bucket_elems": w.bucket_elems, "buckets": buckets, "launches_per_pass": launches},
+                   "bucket_elems": w.bucket_elems, "buckets": buckets, "launches_per_pass": launches,
+                   "stream_stagger_bytes": args.stagger},
         "roofline": {"bound": "hbm", "kernel": "adamw_kernel<k=%d,bf16 out> (amsp_adamw_step_%s)" % (
                          k, "segments" if w.inter_tensor else "shard"),
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
@@ -325,7 +322,7 @@ def run_workload(args, config_id, steps, warmup, headline):
             "ms_per_step": ms_per_step, "value": out["value"], "unit": "elements/s"}
     if not args.no_alt and not w.inter_tensor:
         out["alt_step"] = alt_step(steps, warmup, torch, B, w, n, parts, master, exp_avg, exp_avg_sq, param_bf16,
-                                   d_sqnorm)
+                                   d_sqnorm, args.stagger)
         if out["alt_step"]["ms_per_step"] < ms_per_step:
             best = {key: out["alt_step"][key] for key in ("composition", "bytes_per_element", "ms_per_step", "value",
                                                           "unit")}

@@ -42,6 +42,12 @@
  *     offset from a 1 KiB boundary (as separately allocated buffers are): the leading elements
  *     up to the first such boundary (at most 255) are then done one by one and every wave's
  *     accesses are aligned to their own size.
+ *   - Where the buffers lie matters for speed, not for results.  Large device allocations start on
+ *     2 MiB boundaries, which puts element i of every stream at the same offset modulo 8 KiB; on
+ *     MI355X a wave's accesses to the 2k + 7 streams then wait on each other in the memory system
+ *     and the fused step runs 4-6 % slower for k = 8 and 16.  Shifting the streams' bases against
+ *     each other by an odd multiple of 4 KiB (stream j at allocation base + j * 4 KiB: still aligned
+ *     to 1 KiB) avoids it; multiples of 8 KiB do not.  The kernels cannot do this for the caller.
  *   - bf16 values are passed as uint16_t bit patterns.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is
  *     enqueued and the call returns without waiting; amsp_shard_range alone is synchronous.

@@ -116,7 +116,7 @@ def _run_fullsize(cfg, full):
     import torch
 
     from paper_2311_00257_amd import binding as B
-    from paper_2311_00257_amd import synth_device
+    from paper_2311_00257_amd import layout, synth_device
 
     w = workloads.get(cfg)
     begin, end = B.amsp_shard_range(w.total_elems, w.shard_factor, w.rank)
@@ -130,18 +130,13 @@ def _run_fullsize(cfg, full):
     cross = free >= need + n * 18 + (1 << 30)                # a copy of the state, an fp32 gradient, a second bf16
 
     print("workload %d (%s): n=%d k=%d on device" % (cfg, w.name, n, w.k), flush=True)
-    parts = []
+    # the streams placed as bench.py places them: bases shifted by 4 KiB against each other (layout.py)
+    dp, dm, dv, out, *parts = layout.staggered_empty([(n, torch.float32)] * 3 + [(n, torch.int16)] * (1 + w.k))
     for j in range(w.k):
-        t = torch.empty(n, dtype=torch.int16, device="cuda")
-        synth_device.fill_bf16(t, w.key(synth.TENSOR_PARTIAL0 + j), begin, w.sigma_grad)
-        parts.append(t)
-    dp = torch.empty(n, dtype=torch.float32, device="cuda")
-    dm = torch.empty(n, dtype=torch.float32, device="cuda")
-    dv = torch.empty(n, dtype=torch.float32, device="cuda")
+        synth_device.fill_bf16(parts[j], w.key(synth.TENSOR_PARTIAL0 + j), begin, w.sigma_grad)
     synth_device.fill_f32(dp, w.key(synth.TENSOR_MASTER), begin, w.sigma_param)
     synth_device.fill_f32(dm, w.key(synth.TENSOR_EXP_AVG), begin, w.sigma_m)
     synth_device.fill_f32(dv, w.key(synth.TENSOR_EXP_AVG_SQ), begin, w.scale_v, absolute=True)
-    out = torch.empty(n, dtype=torch.int16, device="cuda")
     ws = torch.empty(B.amsp_workspace_bytes() // 8, dtype=torch.float64, device="cuda")
     d_s = torch.zeros(1, dtype=torch.float64, device="cuda")
     hp = H.hparams_of(w)
@@ -227,7 +222,7 @@ def test_workload5_llama7b_inter_tensor_full():
     import torch
 
     from paper_2311_00257_amd import binding as B
-    from paper_2311_00257_amd import synth_device
+    from paper_2311_00257_amd import layout, synth_device
 
     w = workloads.get(5)
     sizes, total = w.tensor_sizes, w.total_elems
@@ -242,19 +237,14 @@ def test_workload5_llama7b_inter_tensor_full():
         pytest.skip("needs %.0f GB of device memory, %.0f free" % (need / 1e9, free / 1e9))
     print("workload 5 (%s): %d segments, %d of %d elements" % (w.name, len(segs), local, total), flush=True)
 
-    parts = []
+    dp, dm, dv, out, *parts = layout.staggered_empty([(local, torch.float32)] * 3 + [(total, torch.int16)] * (1 + w.k))
     for j in range(w.k):
-        t = torch.empty(total, dtype=torch.int16, device="cuda")
-        synth_device.fill_bf16(t, w.key(synth.TENSOR_PARTIAL0 + j), 0, w.sigma_grad)
-        parts.append(t)
-    dp = torch.empty(local, dtype=torch.float32, device="cuda")
-    dm = torch.empty(local, dtype=torch.float32, device="cuda")
-    dv = torch.empty(local, dtype=torch.float32, device="cuda")
+        synth_device.fill_bf16(parts[j], w.key(synth.TENSOR_PARTIAL0 + j), 0, w.sigma_grad)
     for f, l, n in segs:                                    # compact states: element values follow the flat index
         synth_device.fill_f32(dp[l:l + n], w.key(synth.TENSOR_MASTER), f, w.sigma_param)
         synth_device.fill_f32(dm[l:l + n], w.key(synth.TENSOR_EXP_AVG), f, w.sigma_m)
         synth_device.fill_f32(dv[l:l + n], w.key(synth.TENSOR_EXP_AVG_SQ), f, w.scale_v, absolute=True)
-    out = torch.full((total,), 0x5A5A, dtype=torch.int16, device="cuda")
+    out.fill_(0x5A5A)
     ws = torch.empty(B.amsp_workspace_bytes() // 8, dtype=torch.float64, device="cuda")
     d_s = torch.zeros(1, dtype=torch.float64, device="cuda")
     hp = H.hparams_of(w)
