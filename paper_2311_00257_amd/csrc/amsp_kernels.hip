@@ -86,11 +86,11 @@ int for_bucket_launches(uint64_t n, uint64_t bucket_elems, F f) {
 // less.  The cap is imposed by giving every workgroup an unused slice of the CU's 160 KiB of LDS.
 // `load_bytes_per_lane` is what one lane has in flight before it waits.
 struct RwKnobs {
-    int inflight_kib, min_waves, reduce_inflight_kib, reduce_min_waves;
+    int inflight_kib, min_waves;
 };
-constexpr RwKnobs kRwKnobs{40, 8, 64, 12};   // what the sweeps on MI355X settled on
+constexpr RwKnobs kRwKnobs{40, 8};   // the AdamW kernels: what the sweeps on MI355X settled on
 #ifdef AMSP_TUNING
-// Sweep builds only (never the shipped library): the four numbers, or the wave count itself, can be
+// Sweep builds only (never the shipped library): the two numbers, or the wave count itself, can be
 // overridden from the environment, read at every call so that one process can alternate settings.
 // They change launch shapes, never results.
 int env_knob(const char *name, int lo, int hi, int dflt) {
@@ -100,9 +100,7 @@ int env_knob(const char *name, int lo, int hi, int dflt) {
 }
 RwKnobs rw_knobs() {
     return RwKnobs{env_knob("AMSP_INFLIGHT_KIB", 8, 1024, kRwKnobs.inflight_kib),
-                   env_knob("AMSP_MIN_WAVES", 4, 32, kRwKnobs.min_waves),
-                   env_knob("AMSP_REDUCE_INFLIGHT_KIB", 8, 1024, kRwKnobs.reduce_inflight_kib),
-                   env_knob("AMSP_REDUCE_MIN_WAVES", 4, 32, kRwKnobs.reduce_min_waves)};
+                   env_knob("AMSP_MIN_WAVES", 4, 32, kRwKnobs.min_waves)};
 }
 int forced_waves() { return env_knob("AMSP_FORCE_WAVES", 3, 32, 0); }
 #else
@@ -110,28 +108,42 @@ constexpr const RwKnobs &rw_knobs() { return kRwKnobs; }
 constexpr int forced_waves() { return 0; }
 #endif
 
-// What a kernel family wants in flight per CU, and the fewest waves it is given.
+// What a kernel family wants in flight per CU and the fewest waves it is given, or (waves > 0) the number of
+// waves itself.
 struct RwTarget {
-    int inflight_kib, min_waves;
+    int inflight_kib, min_waves, waves;
 };
 // AdamW kernels: 40 KiB, at least 8 waves (10 waves for an fp32 gradient, 12 for k = 1, 8 for k = 4..8); 7 once
-// a wave loads more than 7 KiB (fused step with k = 9..15) and 6 from 10.5 KiB on (k >= 16).  GB/s of the
-// fused step at 6 / 7 / 8 / 9 waves, alternated in one process: k = 8: 6,050 / 6,500 / 6,510 / 6,520;
-// k = 9: 6,180 / 6,540 / 6,500 / 6,500; k = 12: 6,380 / 6,520 / 6,340 / 6,340; k = 14: 6,410 / 6,420 / 6,270 /
-// 6,290; k = 16: 6,410 / 6,355 / 6,240 / 6,240.
+// a wave loads more than 7 KiB (fused step with k = 9..13) and 6 from 10 KiB on (k >= 14).  GB/s of the
+// fused step at 6 / 7 / 8 / 9 waves, alternated in one process (streams placed 4 KiB apart modulo 8 KiB):
+// k = 8: 6,040 / 6,590 / 6,600 / 6,610; k = 9: 6,190 / 6,630 / 6,570 / 6,580; k = 12: 6,510 / 6,590 / 6,490 /
+// 6,480; k = 14: 6,550 / 6,500 / 6,430 / 6,400; k = 16: 6,480 / 6,430 / 6,340 / 6,360.
 RwTarget adamw_target(unsigned load_bytes_per_lane) {
     const unsigned per_wave = 64u * load_bytes_per_lane;
-    const int floor = rw_knobs().min_waves - (per_wave > 7168u ? 1 : 0) - (per_wave >= 10752u ? 1 : 0);
-    return RwTarget{rw_knobs().inflight_kib, floor};
+    const int floor = rw_knobs().min_waves - (per_wave > 7168u ? 1 : 0) - (per_wave >= 10240u ? 1 : 0);
+    return RwTarget{rw_knobs().inflight_kib, floor, 0};
 }
-// Reduction (its writes are a small share of the traffic): 64 KiB, at least 12 waves (k = 8: 16 waves,
-// 13 with accumulate; k = 16: 12; no cap below k = 8).
-RwTarget reduce_target() { return RwTarget{rw_knobs().reduce_inflight_kib, rw_knobs().reduce_min_waves}; }
+// Reduction (its writes are a small share of the traffic): as many waves as keep 60 KiB of the partials in
+// flight per CU, between 9 and 24; no cap up to k = 3; two more when the fp32 buffer is read too.  GB/s of the
+// reduce+norm pass by waves per CU (streams placed 4 KiB apart modulo 8 KiB): k = 4: 5,570 at 16, 6,740 at 24,
+// 6,560 at 32; k = 8: 5,830 at 10, 6,610 at 13, 6,630 at 14-16, 6,440 at 20; k = 12: 5,900 at 8, 6,395 at 10,
+// 6,300 at 13; k = 16: 5,935 at 7, 6,315 at 9, 6,145 at 12; with accumulate k = 8: 6,140 at 13, 6,460 at 16;
+// k = 16: 6,060 at 9, 6,270 at 10-12.
+RwTarget reduce_target(uint32_t k, bool accumulate) {
+    if (k <= 3) return RwTarget{0, 0, 32};
+    int waves = (int)((120u + k - 1) / k);   // ceil(60 KiB / (64 lanes x 8 k bytes))
+    waves = waves < 9 ? 9 : (waves > 24 ? 24 : waves);
+    if (accumulate && waves < 23) waves += 2;
+    return RwTarget{0, 0, waves};
+}
 
 int rw_waves_per_cu(unsigned load_bytes_per_lane, RwTarget t) {
     const unsigned per_wave = 64u * load_bytes_per_lane;
-    int waves = (int)(((unsigned)t.inflight_kib * 1024u + per_wave - 1) / per_wave);
-    if (waves < t.min_waves) waves = t.min_waves;
+    int waves = t.waves;
+    if (waves <= 0) {
+        waves = (int)(((unsigned)t.inflight_kib * 1024u + per_wave - 1) / per_wave);
+        if (waves < t.min_waves) waves = t.min_waves;
+    }
     if (forced_waves() > 0) waves = forced_waves();
     return waves > 32 ? 32 : waves;
 }
@@ -599,7 +611,7 @@ static int reduce_range(const uint16_t *const *partials, uint32_t k, uint64_t n,
         Span s = make_span(len, st, ns, kVecRW);
         const Buckets none{};
         clear_stale_error();
-        const RwLaunch L = rw_launch(s, lane_bytes, reduce_target());
+        const RwLaunch L = rw_launch(s, lane_bytes, reduce_target(k, accumulate != 0));
         if (!norm) {
             AMSP_DISPATCH_K(k, hipLaunchKernelGGL((reduce_kernel<KK, false>), L.grid, L.block, L.lds, hs, q, (int)k,
                                                   grad_out + off, accumulate, block_sums, s, none));
@@ -621,7 +633,7 @@ static int reduce_range(const uint16_t *const *partials, uint32_t k, uint64_t n,
         if (!make_buckets(len, U, st, ns, kVecRW, bk))
             return for_buckets(len, U, [&](uint64_t o, uint64_t l) { return single(off + o, l); });
         const dim3 grid((unsigned)(((len + U - 1) / U) * bk.blocks_per_bucket)), block(kRwThreads);
-        const unsigned lds = occupancy_lds(lane_bytes, reduce_target());
+        const unsigned lds = occupancy_lds(lane_bytes, reduce_target(k, accumulate != 0));
         const Span s{len, 0, 0, 0, 1};
         clear_stale_error();
         if (!norm) {
@@ -915,7 +927,7 @@ int amsp_reduce_grad_segments(const uint16_t *const *partials_flat, uint32_t k, 
     auto flush_table = [&]() -> int {
         if (tb.count == 0) return AMSP_OK;
         tb.pad();
-        const unsigned lds = occupancy_lds(8 * k + (accumulate ? 16 : 0), reduce_target());
+        const unsigned lds = occupancy_lds(8 * k + (accumulate ? 16 : 0), reduce_target(k, accumulate != 0));
         clear_stale_error();
         hipLaunchKernelGGL(reduce_table_kernel, dim3(tb.blocks), dim3(kRwThreads), lds, hs, pp, (int)k,
                            grad_f32_local, accumulate, tb.table);
