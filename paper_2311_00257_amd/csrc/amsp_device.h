@@ -100,8 +100,8 @@ __device__ __forceinline__ void st_bf16(uint16_t *base, uint64_t e, const float 
 }
 
 // ---------------------------------------------------------------- the reduced gradient
-// K > 0: k == K known at compile time (all loads issued up front); K == -1: run-time k;
-// K == 0: the gradient is already reduced, read it as fp32.
+// K > 0: k == K known at compile time (all loads issued up front); K < 0: run-time k (unrolled to a bound
+// with uniform guards, see grad_vec); K == 0: the gradient is already reduced, read it as fp32.
 // The sum runs j = 0..k-1 in fp32 in every kernel, so all of them see the same bits.
 template <int VEC, typename W>
 __device__ __forceinline__ void widen_first(const W &w, float (&g)[VEC]) {
@@ -137,14 +137,22 @@ __device__ __forceinline__ void grad_vec(const PartialPtrs &pp, int k, const flo
 #pragma unroll
         for (int j = 1; j < K; ++j) widen_add<VEC>(w[j], g);
     } else {
-        W w = ld_stream(reinterpret_cast<const W *>(pp.p[0] + e));
+        // run-time k, unrolled to a bound with wave-uniform guards, so that here too every load is in flight
+        // before the first wait (a loop that loads and adds in turn reads 3.6-4.3 TB/s in the fused step at
+        // k = 17..32).  K == -1: any k, every load guarded (the table kernels, where k is usually small);
+        // K == -20, -24, -28, -32: k in (|K| - 4, |K|], only the last four loads guarded.
+        constexpr int BOUND = K == -1 ? (int)AMSP_MAX_K : -K;
+        constexpr int SURE = K == -1 ? 0 : BOUND - 4;   // partials known to exist
+        static_assert(BOUND >= 4 && BOUND <= (int)AMSP_MAX_K, "unroll bound of the run-time k path");
+        W w[BOUND];
+#pragma unroll
+        for (int j = 0; j < BOUND; ++j)
+            if (j < SURE || j < k) w[j] = ld_stream(reinterpret_cast<const W *>(pp.p[j] + e));
         loads_issued();
-        widen_first<VEC>(w, g);
-#pragma unroll 4
-        for (int j = 1; j < k; ++j) {
-            w = ld_stream(reinterpret_cast<const W *>(pp.p[j] + e));
-            widen_add<VEC>(w, g);
-        }
+        widen_first<VEC>(w[0], g);
+#pragma unroll
+        for (int j = 1; j < BOUND; ++j)
+            if (j < SURE || j < k) widen_add<VEC>(w[j], g);
     }
 }
 

@@ -312,7 +312,7 @@ struct NormBatch {
 };
 
 // Every k up to 16 has its own instantiation (all k loads of a vector in flight at once); larger k
-// take the run-time loop.
+// share four, unrolled to 20, 24, 28 and 32 partials with the last four loads guarded.
 #define AMSP_DISPATCH_K(k, CALL)                 \
     switch (k) {                                 \
         case 1: { constexpr int KK = 1; CALL; } break;   \
@@ -331,7 +331,12 @@ struct NormBatch {
         case 14: { constexpr int KK = 14; CALL; } break;   \
         case 15: { constexpr int KK = 15; CALL; } break;   \
         case 16: { constexpr int KK = 16; CALL; } break;   \
-        default: { constexpr int KK = -1; CALL; } break; \
+        default:                                                          \
+            if (k <= 20) { constexpr int KK = -20; CALL; }                \
+            else if (k <= 24) { constexpr int KK = -24; CALL; }           \
+            else if (k <= 28) { constexpr int KK = -28; CALL; }           \
+            else { constexpr int KK = -32; CALL; }                        \
+            break;                                                        \
     }
 
 // Adds `count` block sums in index order into *out: one block when they are few, otherwise
