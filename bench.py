@@ -295,7 +295,8 @@ def run_workload(args, config_id, steps, warmup, headline):
         torch.cuda.synchronize()
         fp8_ms = e0.elapsed_time(e1) / steps
         out["fp8_payload"] = {"ms": fp8_ms, "GB/s": 9 * n / (fp8_ms * 1e-3) / 1e9, "bytes_per_element": 9,
-                              "launches": 2 * len(segs) + 2}
+                              "launches": 2 + 2 * (-(-sum(m >= (1 << 20) for _, _, m in seg_tuples) // 32)
+                                                   + (1 if any(m < (1 << 20) for _, _, m in seg_tuples) else 0))}
         # the whole step shipping FP8 instead of bf16: norm pass, update with the per-tensor maxima taken
         # inside it and no bf16 output (2k + 24 B/elt), scales and E4M3 codes (4 read + 1 written)
         amax_ws = torch.empty(B.amsp_amax_workspace_bytes(len(segs)) // 4, dtype=torch.int32, device="cuda")

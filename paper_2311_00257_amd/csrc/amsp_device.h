@@ -723,36 +723,59 @@ __global__ void __launch_bounds__(kThreads) fill_u32_kernel(uint32_t *p, uint64_
     for (uint64_t i = (uint64_t)blockIdx.x * kThreads + threadIdx.x; i < count; i += stride) p[i] = value;
 }
 
-// Largest |x| of a range into *slot (integer atomic max: deterministic).  Persistent read-only
-// grid like the norm pass.
-__global__ void __launch_bounds__(kWideThreads) absmax_kernel(const float *__restrict__ x, Span s,
-                                                              uint32_t *__restrict__ slot) {
-    constexpr int VEC = 4;
-    const uint64_t first = (uint64_t)blockIdx.x * kWideThreads + threadIdx.x;
-    const uint64_t stride = (uint64_t)gridDim.x * kWideThreads;
+// Largest |x| of up to kMaxNormSegs ranges, each into its own slot (integer atomic max: exact and order-free),
+// in one launch (a launch per tensor reads a third slower: tensors of 17-130 M elements are 10-80 us of
+// traffic each).  The shape of the norm pass: resident one-wave blocks, 8 consecutive wave pieces per trip with
+// every load in flight before the first is used.  Every range has blocks of its own, in proportion to its
+// length, which walk it like a grid of that size: one atomic per block.  (All blocks walking all ranges in
+// turn send 32 times as many; the slots share a memory channel, where each atomic takes ~11 ns, and the
+// pass then reads 5.4 TB/s instead of 7.)
+struct AbsmaxTable {
+    uint32_t first_block[kMaxNormSegs];   // unused entries: 0xFFFFFFFF
+    uint32_t blocks[kMaxNormSegs];
+    uint32_t slot[kMaxNormSegs];
+    NormSeg seg[kMaxNormSegs];
+};
+
+__global__ void __launch_bounds__(kNormThreads) absmax_kernel(const float *__restrict__ x,
+                                                              uint32_t *__restrict__ slots, AbsmaxTable t) {
+    constexpr int VEC = 4, U = 8;
+    uint32_t r = 0;
+#pragma unroll
+    for (int i = 1; i < kMaxNormSegs; ++i) r += blockIdx.x >= t.first_block[i] ? 1u : 0u;
+    const uint32_t lb = blockIdx.x - t.first_block[r], grid = t.blocks[r];
+    const Span s = t.seg[r].s;
+    const uint64_t base = t.seg[r].base;
     uint32_t m = 0;
     if (s.vectorised) {
-        for (uint64_t v = first; v < s.nvec; v += stride) {
-            float t[VEC];
-            ld_f32<VEC>(x, s.head + v * VEC, t);
+        const uint64_t first = base + s.head;
+        amsp_geom::norm_walk<U>(
+            s.nvec, grid, lb, threadIdx.x,
+            [&](uint64_t v) {
+                f32x4 a[U];
 #pragma unroll
-            for (int c = 0; c < VEC; ++c) m = max(m, abs_bits(t[c]));
-        }
-        if (blockIdx.x == 0)
-            for (uint32_t t = threadIdx.x; t < s.head + s.tail; t += kWideThreads) m = max(m, abs_bits(x[edge_elem<VEC>(s, t)]));
+                for (int u = 0; u < U; ++u)
+                    a[u] = ld_stream(reinterpret_cast<const f32x4 *>(x + first + (v + (uint64_t)u * kNormThreads) * VEC));
+                loads_issued();
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+                    m = max(max(m, max(abs_bits(a[u].x), abs_bits(a[u].y))), max(abs_bits(a[u].z), abs_bits(a[u].w)));
+            },
+            [&](uint64_t v) {
+                const f32x4 a = ld_stream(reinterpret_cast<const f32x4 *>(x + first + v * VEC));
+                m = max(max(m, max(abs_bits(a.x), abs_bits(a.y))), max(abs_bits(a.z), abs_bits(a.w)));
+            });
+        if (lb == 0)
+            for (uint32_t e = threadIdx.x; e < s.head + s.tail; e += kNormThreads)
+                m = max(m, abs_bits(x[base + edge_elem<VEC>(s, e)]));
     } else {
-        for (uint64_t i = first; i < s.n; i += stride) m = max(m, abs_bits(x[i]));
+        const uint64_t row = (uint64_t)grid * kNormThreads;
+        for (uint64_t e = (uint64_t)lb * kNormThreads + threadIdx.x; e < s.n; e += row)
+            m = max(m, abs_bits(x[base + e]));
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) m = max(m, (uint32_t)__shfl_down((int)m, off, 64));
-    __shared__ uint32_t wave_max[kWideThreads / 64];
-    if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = m;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-#pragma unroll
-        for (int w = 1; w < kWideThreads / 64; ++w) m = max(m, wave_max[w]);
-        atomicMax(slot, m);
-    }
+    if (threadIdx.x == 0 && m != 0) atomicMax(slots + t.slot[r], m);   // slots start at 0
 }
 
 // scale[i] = 448 / amax[i] in fp32 (correctly rounded division); 1 when amax is 0, Inf or NaN.
@@ -765,30 +788,90 @@ __global__ void __launch_bounds__(kThreads) fp8_scale_kernel(const float *__rest
     }
 }
 
-__global__ void __launch_bounds__(kThreads) cast_fp8_kernel(const float *__restrict__ master,
-                                                            const float *__restrict__ d_scale,
-                                                            uint8_t *__restrict__ out, Span s) {
+// E4M3 codes of up to kMaxNormSegs ranges in one launch (a launch per tensor loses a fifth of the rate to the
+// starts and ends of 10-30 us kernels).  One-wave blocks of 1024 elements, each belonging to one range, found
+// with 31 scalar compares against the table in the kernel arguments.  On the vector path: four 16-byte loads
+// per lane (four gap-free 1 KiB rows per wave), and, when the output allows 16-byte accesses (`wide`), the
+// four code words of a lane's rows are exchanged through 1 KiB of LDS so that every lane stores 16
+// consecutive codes: one gap-free 1 KiB store per wave instead of four 256-byte ones.
+constexpr int kFp8Rows = 4;   // a multiple of 4
+constexpr uint32_t kFp8BlockElems = kFp8Rows * kRwThreads * 4;
+struct Fp8CastTable {
+    uint32_t first_block[kMaxNormSegs];   // unused entries: 0xFFFFFFFF
+    uint32_t scale[kMaxNormSegs];         // index into d_scale
+    uint32_t wide;                        // bit i: range i's vector path may store 16 bytes at a time
+    uint64_t master_off[kMaxNormSegs], out_off[kMaxNormSegs];
+    Span s[kMaxNormSegs];
+};
+
+__global__ void __launch_bounds__(kRwThreads) cast_fp8_kernel(const float *__restrict__ master_all,
+                                                              const float *__restrict__ d_scale,
+                                                              uint8_t *__restrict__ out_all, Fp8CastTable t) {
     constexpr int VEC = 4;
-    const float scale = *d_scale;
-    if (s.vectorised) {
-        const uint64_t v = vector_index();
-        if (v < s.nvec) {
-            const uint64_t e = s.head + v * VEC;
-            float x[VEC];
-            ld_f32<VEC>(master, e, x);
-            uint32_t w = 0;
+    uint32_t r = 0;
 #pragma unroll
-            for (int c = 0; c < VEC; ++c) w |= f32_to_e4m3(x[c] * scale) << (8 * c);
-            st_stream(reinterpret_cast<uint32_t *>(out + e), w);
+    for (int i = 1; i < kMaxNormSegs; ++i) r += blockIdx.x >= t.first_block[i] ? 1u : 0u;
+    const uint32_t lb = blockIdx.x - t.first_block[r];
+    const Span s = t.s[r];
+    const float *__restrict__ master = master_all + t.master_off[r];
+    uint8_t *__restrict__ out = out_all + t.out_off[r];
+    const float scale = d_scale[t.scale[r]];
+    if (s.vectorised) {
+        __shared__ uint32_t tile[kFp8Rows * kRwThreads];
+        const uint64_t v0 = (uint64_t)lb * (kFp8Rows * kRwThreads);
+        float x[kFp8Rows][VEC];
+#pragma unroll
+        for (int row = 0; row < kFp8Rows; ++row) {
+            const uint64_t v = v0 + row * kRwThreads + threadIdx.x;
+            if (v < s.nvec) ld_f32<VEC>(master, s.head + v * VEC, x[row]);
         }
-        if (blockIdx.x == 0)
-            for (uint32_t t = threadIdx.x; t < s.head + s.tail; t += kRwThreads) {
-                const uint64_t i = edge_elem<VEC>(s, t);
+        loads_issued();
+        uint32_t w[kFp8Rows];
+#pragma unroll
+        for (int row = 0; row < kFp8Rows; ++row) {
+            w[row] = 0;
+            if (v0 + row * kRwThreads + threadIdx.x < s.nvec) {
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) w[row] |= f32_to_e4m3(x[row][c] * scale) << (8 * c);
+            }
+        }
+        if ((t.wide >> r) & 1u) {
+#pragma unroll
+            for (int row = 0; row < kFp8Rows; ++row) tile[row * kRwThreads + threadIdx.x] = w[row];
+            __syncthreads();   // one wave: orders the LDS writes before the reads below
+#pragma unroll
+            for (int j = 0; j < kFp8Rows / 4; ++j) {
+                const u32x4 q = reinterpret_cast<const u32x4 *>(tile)[j * kRwThreads + threadIdx.x];
+                // the lane's four vectors of this store: 16 consecutive codes, 1 KiB gap-free per wave
+                const uint64_t first = v0 + (uint64_t)(j * kRwThreads + threadIdx.x) * 4;
+                uint8_t *dst = out + s.head + first * VEC;
+                if (first + 4 <= s.nvec) {
+                    st_stream(reinterpret_cast<u32x4 *>(dst), q);
+                } else {
+#pragma unroll
+                    for (int c = 0; c < 4; ++c)
+                        if (first + c < s.nvec) st_stream(reinterpret_cast<uint32_t *>(dst + 4 * c), q[c]);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int row = 0; row < kFp8Rows; ++row) {
+                const uint64_t v = v0 + row * kRwThreads + threadIdx.x;
+                if (v < s.nvec) st_stream(reinterpret_cast<uint32_t *>(out + s.head + v * VEC), w[row]);
+            }
+        }
+        if (lb == 0)
+            for (uint32_t e = threadIdx.x; e < s.head + s.tail; e += kRwThreads) {
+                const uint64_t i = edge_elem<VEC>(s, e);
                 out[i] = (uint8_t)f32_to_e4m3(master[i] * scale);
             }
-    } else {
-        const uint64_t i = element_index();
-        if (i < s.n) out[i] = (uint8_t)f32_to_e4m3(master[i] * scale);
+    } else {   // no common 4-element phase of input and output: a code per lane, 1024 per block
+        const uint64_t i0 = (uint64_t)lb * kFp8BlockElems + threadIdx.x;
+#pragma unroll 4
+        for (uint32_t c = 0; c < kFp8BlockElems / kRwThreads; ++c) {
+            const uint64_t i = i0 + (uint64_t)c * kRwThreads;
+            if (i < s.n) out[i] = (uint8_t)f32_to_e4m3(master[i] * scale);
+        }
     }
 }
 
