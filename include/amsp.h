@@ -340,10 +340,9 @@ int amsp_cast_param_fp8_shard(const float *master, uint64_t n, const float *d_sc
  *   amax_ready      0: the maxima are computed here (one more read of the master).  1: d_amax already
  *                   holds them, as amsp_adamw_step_segments left them for this segment list
  * The maxima of 32 segments share a launch, and so do their codes, whatever the segments' lengths.
- * Codes are stored 16 bytes at a time where master_local + local_offset and param_fp8_flat +
- * flat_offset allow it (both on 16-byte boundaries at the same element, as with offsets that are
- * multiples of 16 elements into 16-byte-aligned buffers), 4 bytes at a time where the two are only
- * congruent modulo 4 elements, else byte by byte.
+ * Codes are stored 16 bytes at a time when some element of the segment has its fp32 value on a
+ * 16-byte boundary and its code on a 4-byte boundary (then that holds every 4 elements; offsets that
+ * are multiples of 4 elements into 16-byte-aligned buffers give it), else byte by byte.
  * Errors as amsp_adamw_step_segments.
  */
 int amsp_fp8_payload_segments(const float *master_local, uint64_t local_elems,

@@ -524,7 +524,14 @@ struct Fp8CastBatch {
     int add(uint64_t master_off, uint64_t out_off, uint64_t len, uint32_t scale_index) {
         return for_pieces(0, len, kMaxLaunchElems, [&](uint64_t off, uint64_t n) -> int {
             Stream16 st[2] = {{master + master_off + off, 4}, {out + out_off + off, 1}};
-            const Span s = make_span(n, st, 2, 4);
+            Span s = make_span(n, st, 2, 4);
+            if (s.vectorised && s.nvec > 4) {
+                // a head up to three vectors longer puts the first stored vector on a 16-byte boundary
+                const uint32_t more = (uint32_t)(-(reinterpret_cast<uintptr_t>(out + out_off + off) + s.head) & 15);
+                s.head += more;   // a multiple of 4: the loads stay on 16-byte boundaries
+                s.nvec = (n - s.head) / 4;
+                s.tail = (uint32_t)(n - s.head - s.nvec * 4);
+            }
             const uint64_t b = std::max<uint64_t>((n + kFp8BlockElems - 1) / kFp8BlockElems, 1);
             if (blocks + b > kMaxLaunchBlocks) {
                 const int rc = flush();

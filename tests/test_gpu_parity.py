@@ -469,6 +469,66 @@ def test_fp8_cast_sizes_and_phases(B, torch_mod, n, shift):
     assert np.all(got[:shift] == 0xA5) and np.all(got[shift + n:] == 0xA5)
 
 
+@pytest.mark.parametrize("n,mshift,oshift", [(100_003, 1, 5), (100_003, 1, 9), (300_000, 0, 4), (300_000, 3, 15),
+                                             (300_000, 1, 2), (5000, 2, 6), (1030, 0, 12)])
+def test_fp8_cast_when_input_and_output_phases_differ(B, torch_mod, n, mshift, oshift):
+    """Input and output congruent modulo 4 elements but not modulo 16 (the vector path starts a few vectors
+    later to store 16 bytes at a time), and not congruent at all (a code per lane)."""
+    torch = torch_mod
+    x = synth.fill_f32(4, 60, n, 100.0)
+    d = H.to_dev_f32(x, pad_front=mshift)
+    d_scale = torch.tensor([2.3], dtype=torch.float32, device="cuda")
+    out = torch.full((oshift + n + 40,), 0xA5, dtype=torch.uint8, device="cuda")
+    B.amsp_cast_param_fp8_shard(d, n, d_scale, out[oshift:])
+    got = out.cpu().numpy()
+    assert np.array_equal(got[oshift:oshift + n], oracle.cast_fp8(x, 2.3))
+    assert np.all(got[:oshift] == 0xA5) and np.all(got[oshift + n:] == 0xA5)
+
+
+def test_fp8_payload_of_long_and_short_segments_in_shared_launches(B, torch_mod):
+    """More long segments than one launch takes (32), of ragged lengths, at every relation of local and
+    flat phase (congruent modulo 16, modulo 4 only, not at all), with short and empty segments between
+    them: maxima, scales and codes bit for bit, and nothing written between the segments."""
+    torch = torch_mod
+    rng = np.random.default_rng(20257)
+    segs, flat, local = [], 0, 0
+    for i in range(36):
+        length = (1 << 20) + int(rng.integers(0, 3000))                    # long: not in the short-segment table
+        flat += int(rng.integers(1, 40)) if i % 3 else 16 - flat % 16 + local % 16   # i % 3 == 0: congruent modulo 16
+        if i % 3 == 1:
+            flat += (local - flat) % 4                                       # congruent modulo 4
+        segs.append((flat, local, length))
+        flat, local = flat + length, local + length
+        if i % 5 == 0:                                                       # a short one and an empty one
+            short = int(rng.integers(1, 5000))
+            segs.append((flat + 3, local, short))
+            flat, local = flat + 3 + short, local + short
+            segs.append((flat, local, 0))
+    total = flat + 64
+    master = synth.fill_f32(8, 70, local, 1.0)
+    for j, (_, l, m) in enumerate(segs):                                     # a different magnitude per segment
+        master[l:l + m] *= np.float32(2.0 ** (j % 7 - 3))
+    dp = H.to_dev_f32(master)
+    out = torch.full((total,), 0xA5, dtype=torch.uint8, device="cuda")
+    d_amax = torch.full((len(segs),), -1.0, dtype=torch.float32, device="cuda")
+    d_scale = torch.zeros(len(segs), dtype=torch.float32, device="cuda")
+    B.amsp_fp8_payload_segments(dp, local, segs, total, out, d_amax, d_scale)
+    codes, scales, amaxes = oracle.fp8_payload_segments(master, segs)
+    assert d_amax.cpu().numpy().tolist() == [float(np.float32(a)) for a in amaxes]
+    assert d_scale.cpu().numpy().tolist() == [float(np.float32(s)) for s in scales]
+    got = out.cpu().numpy()
+    assert np.array_equal(oracle.select(got, segs), codes)
+    owned = np.zeros(total, dtype=bool)
+    for f, _, m in segs:
+        owned[f:f + m] = True
+    assert np.all(got[~owned] == 0xA5)
+    # the maxima already there (amax_ready): the same scales and codes
+    out2 = torch.full((total,), 0xA5, dtype=torch.uint8, device="cuda")
+    d_scale2 = torch.zeros(len(segs), dtype=torch.float32, device="cuda")
+    B.amsp_fp8_payload_segments(dp, local, segs, total, out2, d_amax, d_scale2, amax_ready=True)
+    assert torch.equal(out, out2) and torch.equal(d_scale, d_scale2)
+
+
 def test_fp8_payload_of_inter_tensor_shard(B, torch_mod):
     """Per-tensor amax, scale and E4M3 codes of a rank's segments, after a real update."""
     torch = torch_mod
