@@ -243,18 +243,60 @@ __device__ __forceinline__ double block_sum(double acc) {
 // NORM: also sum the squares of the values written, one double per block into block_sums
 // (step 2 fused into step 1 for callers that keep the fp32 gradient): one per 256 elements on the
 // vector path (a one-wave block), a capped number on the element-wise path.
+// Vectors per lane and block: with few partials one vector per lane leaves too little in flight even at 32
+// waves per CU (k = 1, 6.7 G elements: 5,180 GB/s; two per lane 6,400, four 6,470-6,490 at 24-28 waves).
+constexpr int reduce_rows(int k) { return k == 1 ? 4 : (k == 2 || k == 3) ? 2 : 1; }
+
 template <int K, bool NORM>
 __global__ void __launch_bounds__(kThreads) reduce_kernel(PartialPtrs pp, int k, float *__restrict__ out,
                                                           int accumulate, double *__restrict__ block_sums, Span s,
                                                           Buckets bk) {
     constexpr int VEC = kVecRW;
+    constexpr int R = reduce_rows(K);
     double acc = 0.0;
     if (s.vectorised) {
         uint64_t off;
         uint32_t lb;
         block_range<VEC>(bk, s, off, lb);
+        if constexpr (R > 1) {
+            // R consecutive wave pieces per block, every load of every row issued before the first is used
+            typedef typename Bf16Words<VEC>::type W;
+            const uint64_t v0 = (uint64_t)lb * (kRwThreads * R) + threadIdx.x;
+            float o[R][VEC];
+            W w[R][K];
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const uint64_t v = v0 + (uint64_t)r * kRwThreads;
+                if (v < s.nvec) {
+                    const uint64_t e = off + s.head + v * VEC;
+                    if (accumulate) ld_f32<VEC>(out, e, o[r]);
+#pragma unroll
+                    for (int j = 0; j < K; ++j) w[r][j] = ld_stream(reinterpret_cast<const W *>(pp.p[j] + e));
+                }
+            }
+            loads_issued();
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const uint64_t v = v0 + (uint64_t)r * kRwThreads;
+                if (v < s.nvec) {
+                    float g[VEC];
+                    widen_first<VEC>(w[r][0], g);
+#pragma unroll
+                    for (int j = 1; j < K; ++j) widen_add<VEC>(w[r][j], g);
+                    if (accumulate) {
+#pragma unroll
+                        for (int c = 0; c < VEC; ++c) g[c] = o[r][c] + g[c];
+                    }
+                    st_f32<VEC>(out, off + s.head + v * VEC, g);
+                    if constexpr (NORM) {
+#pragma unroll
+                        for (int c = 0; c < VEC; ++c) acc = fma((double)g[c], (double)g[c], acc);
+                    }
+                }
+            }
+        }
         const uint64_t v = (uint64_t)lb * kRwThreads + threadIdx.x;
-        if (v < s.nvec) {
+        if (R == 1 && v < s.nvec) {
             const uint64_t e = off + s.head + v * VEC;
             float g[VEC], o[VEC];
             if (accumulate) ld_f32<VEC>(out, e, o);   // issued ahead of the partial loads

@@ -35,7 +35,8 @@ AMSP_HOST_DEVICE inline uint64_t edge_elem(const Span &s, uint32_t t, int vec) {
 }
 
 // Several buckets in one launch.  Bucket b covers [b * bucket_elems, min((b + 1) * bucket_elems, n)) and
-// is given blocks_per_bucket consecutive one-wave blocks; its own head, vector count and tail follow
+// is given blocks_per_bucket consecutive one-wave blocks (enough for its vectors at the launch's vectors per
+// lane); its own head, vector count and tail follow
 // from h0, the head of element 0, because alignment repeats every mask + 1 elements.
 // bucket_elems == 0: the launch is a single range described by a Span.
 struct Buckets {
@@ -178,12 +179,14 @@ inline int for_pieces(uint64_t begin, uint64_t n, uint64_t limit, F f) {
 
 // Geometry of one launch over the buckets of [0, n) whose streams start at `st`; false when the streams
 // have no common phase (then every bucket goes through the element-wise path, a launch each).
-inline bool make_buckets(uint64_t n, uint64_t bucket_elems, const Stream *st, int ns, int vec, Buckets &bk) {
+// `rows`: vectors per lane and block (a block covers rows consecutive wave pieces).
+inline bool make_buckets(uint64_t n, uint64_t bucket_elems, const Stream *st, int ns, int vec, Buckets &bk,
+                         int rows = 1) {
     for (int level = kAlignWave; level <= kAlignVector; ++level) {
         const int h = common_head(st, ns, vec, (AlignLevel)level);
         if (h < 0) continue;
         bk = Buckets{bucket_elems, n, (uint32_t)h, (uint32_t)align_period((AlignLevel)level, st, ns, vec) - 1u,
-                     (uint32_t)(bucket_elems / ((uint64_t)kWaveLanes * vec) + 1)};
+                     (uint32_t)(bucket_elems / ((uint64_t)kWaveLanes * vec * rows) + 1)};
         return true;
     }
     return false;

@@ -124,13 +124,16 @@ RwTarget adamw_target(unsigned load_bytes_per_lane) {
     return RwTarget{rw_knobs().inflight_kib, floor, 0};
 }
 // Reduction (its writes are a small share of the traffic): as many waves as keep 60 KiB of the partials in
-// flight per CU, between 9 and 24; no cap up to k = 3; two more when the fp32 buffer is read too.  GB/s of the
+// flight per CU, between 9 and 24; two more when the fp32 buffer is read too.  k = 1..3, where a block takes
+// reduce_rows(k) vectors per lane: 20-22 (k = 1: 6,400 at 20-24, 6,120 at 32, 5,400 at 12; k = 2: 6,260 at
+// 20, 6,370-6,415 at 24-28; k = 3: 6,495 at 20, 6,110 at 32), 16 with accumulate (6,360 / 6,270 / 6,520
+// against 6,050 / 5,870 / 5,710 at 32).  GB/s of the
 // reduce+norm pass by waves per CU (streams placed 4 KiB apart modulo 8 KiB): k = 4: 5,570 at 16, 6,740 at 24,
 // 6,560 at 32; k = 8: 5,830 at 10, 6,610 at 13, 6,630 at 14-16, 6,440 at 20; k = 12: 5,900 at 8, 6,395 at 10,
 // 6,300 at 13; k = 16: 5,935 at 7, 6,315 at 9, 6,145 at 12; with accumulate k = 8: 6,140 at 13, 6,460 at 16;
 // k = 16: 6,060 at 9, 6,270 at 10-12.
 RwTarget reduce_target(uint32_t k, bool accumulate) {
-    if (k <= 3) return RwTarget{0, 0, 32};
+    if (k <= 3) return RwTarget{0, 0, accumulate ? 16 : (k == 3 ? 20 : 22)};
     int waves = (int)((120u + k - 1) / k);   // ceil(60 KiB / (64 lanes x 8 k bytes))
     waves = waves < 9 ? 9 : (waves > 24 ? 24 : waves);
     if (accumulate && waves < 23) waves += 2;
@@ -175,10 +178,11 @@ RwLaunch rw_launch(const Span &s, unsigned load_bytes_per_lane, RwTarget t) {
 // lane on the vector path (a sum per 256 elements), a capped grid-stride grid on the element-wise path.
 constexpr int kSliceBlocks = 256;
 
-uint64_t reduce_norm_grid(const Span &s) {
+uint64_t reduce_norm_grid(const Span &s, uint32_t k) {
     uint64_t blocks;
     if (s.vectorised) {
-        blocks = (s.nvec + kRwThreads - 1) / kRwThreads;
+        const uint64_t per_block = (uint64_t)kRwThreads * reduce_rows((int)k);
+        blocks = (s.nvec + per_block - 1) / per_block;
     } else {
         blocks = (s.n + kThreads - 1) / kThreads;
         if (blocks > (uint64_t)kNormBlocks) blocks = kNormBlocks;
@@ -656,7 +660,7 @@ static int reduce_range(const uint16_t *const *partials, uint32_t k, uint64_t n,
     if (grad_out == nullptr) return AMSP_ENULL;
     if (misaligned(grad_out, 4)) return AMSP_EALIGN;
     uint64_t used = 0;   // block sums written so far, bucket after bucket
-    const unsigned lane_bytes = 8 * k + (accumulate ? 16 : 0);
+    const unsigned lane_bytes = (8 * k + (accumulate ? 16 : 0)) * reduce_rows((int)k);
     auto single = [&](uint64_t off, uint64_t len) -> int {
         PartialPtrs q = offset_partials(pp, k, off);
         Stream16 st[AMSP_MAX_K + 1];
@@ -665,13 +669,14 @@ static int reduce_range(const uint16_t *const *partials, uint32_t k, uint64_t n,
         Span s = make_span(len, st, ns, kVecRW);
         const Buckets none{};
         clear_stale_error();
-        const RwLaunch L = rw_launch(s, lane_bytes, reduce_target(k, accumulate != 0));
+        RwLaunch L = rw_launch(s, lane_bytes, reduce_target(k, accumulate != 0));
+        if (s.vectorised) L.grid = dim3((unsigned)reduce_norm_grid(s, k));   // reduce_rows(k) vectors per lane
         if (!norm) {
             AMSP_DISPATCH_K(k, hipLaunchKernelGGL((reduce_kernel<KK, false>), L.grid, L.block, L.lds, hs, q, (int)k,
                                                   grad_out + off, accumulate, block_sums, s, none));
             return launched();
         }
-        const uint64_t blocks = reduce_norm_grid(s);   // == L.grid.x on the vector path, capped on the other
+        const uint64_t blocks = reduce_norm_grid(s, k);   // == L.grid.x on the vector path, capped on the other
         AMSP_DISPATCH_K(k, hipLaunchKernelGGL((reduce_kernel<KK, true>), dim3((unsigned)blocks), L.block, L.lds, hs, q,
                                               (int)k, grad_out + off, accumulate, block_sums + used, s, none));
         used += blocks;
@@ -684,7 +689,7 @@ static int reduce_range(const uint16_t *const *partials, uint32_t k, uint64_t n,
         int ns = add_partial_streams(st, 0, q, k);
         st[ns++] = Stream16{grad_out + off, 4};
         Buckets bk;
-        if (!make_buckets(len, U, st, ns, kVecRW, bk))
+        if (!make_buckets(len, U, st, ns, kVecRW, bk, reduce_rows((int)k)))
             return for_buckets(len, U, [&](uint64_t o, uint64_t l) { return single(off + o, l); });
         const dim3 grid((unsigned)(((len + U - 1) / U) * bk.blocks_per_bucket)), block(kRwThreads);
         const unsigned lds = occupancy_lds(lane_bytes, reduce_target(k, accumulate != 0));

@@ -28,6 +28,7 @@ struct Case {
     std::vector<Stream> st;
     uint64_t n, bucket;
     int vec;
+    int rows = 1;   // vectors per lane and block: a block covers `rows` consecutive wave pieces
 };
 
 static bool aligned(const Stream &s, uint64_t elem_index, uintptr_t need) {
@@ -54,8 +55,8 @@ static int brute_head(const Case &c, int level, uint64_t from) {
 }
 
 static int fail(const Case &c, const char *what, uint64_t at) {
-    printf("FAIL: %s at %llu; n=%llu bucket=%llu vec=%d streams:", what, (unsigned long long)at,
-           (unsigned long long)c.n, (unsigned long long)c.bucket, c.vec);
+    printf("FAIL: %s at %llu; n=%llu bucket=%llu vec=%d rows=%d streams:", what, (unsigned long long)at,
+           (unsigned long long)c.n, (unsigned long long)c.bucket, c.vec, c.rows);
     for (const Stream &s : c.st) printf(" (%p,%u)", s.ptr, s.elem);
     printf("\n");
     return 1;
@@ -63,8 +64,8 @@ static int fail(const Case &c, const char *what, uint64_t at) {
 
 // Walk one range the way a kernel's blocks do; bump `seen` per element touched.
 static int walk_range(const Case &c, const Span &s, uint64_t off, uint32_t local_block, std::vector<uint8_t> &seen) {
-    for (int lane = 0; lane < kWaveLanes; ++lane) {
-        const uint64_t v = (uint64_t)local_block * kWaveLanes + lane;
+    for (int slot = 0; slot < kWaveLanes * c.rows; ++slot) {   // slot = row * 64 + lane
+        const uint64_t v = (uint64_t)local_block * kWaveLanes * c.rows + slot;
         if (v < s.nvec) {
             const uint64_t e = off + s.head + v * c.vec;
             for (const Stream &st : c.st)
@@ -103,14 +104,15 @@ static int check(const Case &c) {
         if (want < 0) return fail(c, "vector path taken though no head exists", s.head);
         if ((uint32_t)want != s.head) return fail(c, "head is not that of the best alignment level", want);
         if (s.head + s.nvec * c.vec + s.tail != c.n || s.tail >= (uint32_t)c.vec) return fail(c, "span does not add up", s.head);
-        const uint64_t blocks = (s.nvec + kWaveLanes - 1) / kWaveLanes;
+        const uint64_t per_block = (uint64_t)kWaveLanes * c.rows;
+        const uint64_t blocks = (s.nvec + per_block - 1) / per_block;
         for (uint64_t b = 0; b < (blocks ? blocks : 1); ++b)
             if (walk_range(c, s, 0, (uint32_t)b, seen)) return 1;
     } else {
         Buckets bk;
         int level = 0;
         while (level <= 2 && brute_head(c, level, 0) < 0) ++level;   // the launch's level: the best that exists at all
-        if (!make_buckets(c.n, c.bucket, st, ns, c.vec, bk)) {
+        if (!make_buckets(c.n, c.bucket, st, ns, c.vec, bk, c.rows)) {
             if (level <= 2) return fail(c, "bucket launch refused though a head exists", 0);
             return 0;
         }
@@ -127,7 +129,10 @@ static int check(const Case &c) {
             if (s.nvec > 0 && (bh < 0 || (uint32_t)bh != s.head)) return fail(c, "bucket head is not the smallest aligned one", off);
             if (s.nvec == 0 && bh >= 0 && s.n >= (uint64_t)bh + c.vec) return fail(c, "bucket left to the edge loop though a vector fits", off);
             if (s.tail >= (uint32_t)c.vec && s.nvec > 0) return fail(c, "bucket tail as long as a vector", off);
-            if ((uint64_t)bk.blocks_per_bucket * kWaveLanes < s.nvec) return fail(c, "too few blocks per bucket", off);
+            if ((uint64_t)bk.blocks_per_bucket * kWaveLanes * c.rows < s.nvec) return fail(c, "too few blocks per bucket", off);
+            const uint64_t per_block = (uint64_t)kWaveLanes * c.rows * c.vec;   // elements
+            if ((uint64_t)bk.blocks_per_bucket * per_block > c.bucket + 2 * per_block)
+                return fail(c, "more blocks per bucket than its vectors need", off);
             if (walk_range(c, s, off, lb, seen)) return 1;
         }
     }
@@ -207,6 +212,7 @@ int main() {
         c.vec = below(4) == 0 ? 8 : 4;
         c.n = below(3) == 0 ? lengths[below(sizeof lengths / sizeof *lengths)] : 1 + below(6000);
         c.bucket = c.vec == 8 ? 0 : buckets[below(sizeof buckets / sizeof *buckets)];
+        c.rows = c.vec == 8 ? 1 : (below(3) == 0 ? (below(2) ? 2 : 4) : 1);   // the reduction with few partials
         const int ns = 1 + (int)below(6);
         const int mode = (int)below(5);   // 0: unrelated small shifts; 1: a common shift plus whole lines; else: a common shift
         const uint64_t common = below(700);

@@ -42,7 +42,11 @@ MUTATIONS = [
     ("last bucket as long as the others",
      "const uint64_t len = left < bk.bucket_elems ? left : bk.bucket_elems;", "const uint64_t len = left < bk.bucket_elems ? bk.bucket_elems : bk.bucket_elems;"),
     ("one block too few per bucket",
-     "(uint32_t)(bucket_elems / ((uint64_t)kWaveLanes * vec) + 1)};", "(uint32_t)(bucket_elems / ((uint64_t)kWaveLanes * vec))};"),
+     "(uint32_t)(bucket_elems / ((uint64_t)kWaveLanes * vec * rows) + 1)};", "(uint32_t)(bucket_elems / ((uint64_t)kWaveLanes * vec * rows))};"),
+    ("blocks per bucket forget the vectors per lane",
+     "(uint32_t)(bucket_elems / ((uint64_t)kWaveLanes * vec * rows) + 1)};", "(uint32_t)(bucket_elems / ((uint64_t)kWaveLanes * vec) + 1)};"),
+    ("blocks per bucket count the vectors per lane twice",
+     "(uint32_t)(bucket_elems / ((uint64_t)kWaveLanes * vec * rows) + 1)};", "(uint32_t)(bucket_elems / ((uint64_t)kWaveLanes * vec * rows * rows) + 1)};"),
     ("tail elements start one vector early",
      "(uint64_t)s.head + s.nvec * (uint64_t)vec + (t - s.head);", "(uint64_t)s.head + (s.nvec - 1) * (uint64_t)vec + (t - s.head);"),
     ("short bucket keeps its aligned head",

@@ -138,7 +138,8 @@ def test_reduce_identical_partials_and_accumulate(B, torch_mod):
     assert torch_mod.equal(out, ref)
 
 
-@pytest.mark.parametrize("k,n,shift", [(2, 9_000_003, 0), (8, 1_000_001, 3), (3, 4099, 1), (1, 5, 0)])
+@pytest.mark.parametrize("k,n,shift", [(2, 9_000_003, 0), (8, 1_000_001, 3), (3, 4099, 1), (1, 5, 0),
+                                       (1, 1_000_003, 2), (3, 700_001, 0)])
 def test_reduce_with_fused_norm(B, torch_mod, k, n, shift):
     """Step 2 fused into step 1: same gradient bits as the plain reduce, and the squared norm of
     what was written (9M elements exceed 2048 block sums: the two-stage finish)."""
