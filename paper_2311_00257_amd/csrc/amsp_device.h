@@ -4,6 +4,7 @@
 // lives in that file's anonymous namespace.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <type_traits>
 #include <stdint.h>
 
 #include "amsp.h"
@@ -384,17 +385,25 @@ __device__ __forceinline__ double sqnorm_span(const PartialPtrs &pp, int k, cons
         constexpr int KS = K <= 0 ? 1 : K;
         typedef typename Bf16Words<VEC == 8 ? 8 : 4>::type W;
         const uint64_t first = base + s.head;
-        amsp_geom::norm_walk<U>(
-            s.nvec, gridDim.x, blockIdx.x, threadIdx.x,
-            [&](uint64_t v) {   // U vectors, every load in flight before the first is used
+        // one trip: U vectors (with `guarded`, those of them that exist), every load in flight before the first is used
+        auto trip = [&](uint64_t v, auto guarded) {
+            constexpr bool G = decltype(guarded)::value;
+            if constexpr (K < 0) {   // run-time k: U == 1
+                float g[VEC];
+                grad_vec<K, VEC>(pp, k, gf32, first + v * VEC, g);
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) acc = fma((double)g[c], (double)g[c], acc);
+            } else {
                 f32x4 a[U];
                 W w[U][KS];
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
-                    const uint64_t e = first + (v + (uint64_t)u * kNormThreads) * VEC;
+                    const uint64_t x = v + (uint64_t)u * kNormThreads;
+                    if (G && x >= s.nvec) continue;
+                    const uint64_t e = first + x * VEC;
                     if constexpr (K == 0) {
                         a[u] = ld_stream(reinterpret_cast<const f32x4 *>(gf32 + e));
-                    } else if constexpr (K > 0) {
+                    } else {
 #pragma unroll
                         for (int j = 0; j < KS; ++j) w[u][j] = ld_stream(reinterpret_cast<const W *>(pp.p[j] + e));
                     }
@@ -402,10 +411,11 @@ __device__ __forceinline__ double sqnorm_span(const PartialPtrs &pp, int k, cons
                 loads_issued();
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
+                    if (G && v + (uint64_t)u * kNormThreads >= s.nvec) continue;
                     float g[VEC];
                     if constexpr (K == 0) {
                         g[0] = a[u].x; g[1] = a[u].y; g[2] = a[u].z; g[3] = a[u].w;
-                    } else if constexpr (K > 0) {
+                    } else {
                         widen_first<VEC>(w[u][0], g);
 #pragma unroll
                         for (int j = 1; j < KS; ++j) widen_add<VEC>(w[u][j], g);
@@ -413,13 +423,11 @@ __device__ __forceinline__ double sqnorm_span(const PartialPtrs &pp, int k, cons
 #pragma unroll
                     for (int c = 0; c < VEC; ++c) acc = fma((double)g[c], (double)g[c], acc);
                 }
-            },
-            [&](uint64_t v) {
-                float g[VEC];
-                grad_vec<K, VEC>(pp, k, gf32, first + v * VEC, g);
-#pragma unroll
-                for (int c = 0; c < VEC; ++c) acc = fma((double)g[c], (double)g[c], acc);
-            });
+            }
+        };
+        amsp_geom::norm_walk<U>(
+            s.nvec, gridDim.x, blockIdx.x, threadIdx.x, [&](uint64_t v) { trip(v, std::false_type{}); },
+            [&](uint64_t v) { trip(v, std::true_type{}); });
         if (blockIdx.x == edge_block)
             for (uint32_t t = threadIdx.x; t < s.head + s.tail; t += kNormThreads) {
                 const double g = (double)grad1<K>(pp, k, gf32, base + edge_elem<VEC>(s, t));
@@ -791,22 +799,25 @@ __global__ void __launch_bounds__(kNormThreads) absmax_kernel(const float *__res
     uint32_t m = 0;
     if (s.vectorised) {
         const uint64_t first = base + s.head;
+        auto trip = [&](uint64_t v, auto guarded) {
+            constexpr bool G = decltype(guarded)::value;
+            f32x4 a[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const uint64_t y = v + (uint64_t)u * kNormThreads;
+                if (G && y >= s.nvec) continue;
+                a[u] = ld_stream(reinterpret_cast<const f32x4 *>(x + first + y * VEC));
+            }
+            loads_issued();
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (G && v + (uint64_t)u * kNormThreads >= s.nvec) continue;
+                m = max(max(m, max(abs_bits(a[u].x), abs_bits(a[u].y))), max(abs_bits(a[u].z), abs_bits(a[u].w)));
+            }
+        };
         amsp_geom::norm_walk<U>(
-            s.nvec, grid, lb, threadIdx.x,
-            [&](uint64_t v) {
-                f32x4 a[U];
-#pragma unroll
-                for (int u = 0; u < U; ++u)
-                    a[u] = ld_stream(reinterpret_cast<const f32x4 *>(x + first + (v + (uint64_t)u * kNormThreads) * VEC));
-                loads_issued();
-#pragma unroll
-                for (int u = 0; u < U; ++u)
-                    m = max(max(m, max(abs_bits(a[u].x), abs_bits(a[u].y))), max(abs_bits(a[u].z), abs_bits(a[u].w)));
-            },
-            [&](uint64_t v) {
-                const f32x4 a = ld_stream(reinterpret_cast<const f32x4 *>(x + first + v * VEC));
-                m = max(max(m, max(abs_bits(a.x), abs_bits(a.y))), max(abs_bits(a.z), abs_bits(a.w)));
-            });
+            s.nvec, grid, lb, threadIdx.x, [&](uint64_t v) { trip(v, std::false_type{}); },
+            [&](uint64_t v) { trip(v, std::true_type{}); });
         if (lb == 0)
             for (uint32_t e = threadIdx.x; e < s.head + s.tail; e += kNormThreads)
                 m = max(m, abs_bits(x[base + edge_elem<VEC>(s, e)]));

@@ -77,17 +77,19 @@ AMSP_HOST_DEVICE inline void block_range(const Buckets &bk, uint32_t block, int 
 // The read-only pass over a range's nvec vectors: a persistent grid of `grid` one-wave blocks.  Block b's
 // trip t covers the U consecutive wave pieces (kWaveLanes vectors each) that start at vector
 // (t * grid + b) * kWaveLanes * U, so that a trip of the whole grid is one contiguous window of every
-// stream.  full(v): lane's vectors v, v + kWaveLanes, ..., v + (U - 1) kWaveLanes are all inside the range
-// (their loads are issued together); one(v): a single vector, the pieces (fewer than U) of the block's
-// last, partial trip, or with U == 1 every trip.  Every vector in [0, nvec) is visited exactly once.
-template <int U, typename Full, typename One>
+// stream.  full(v): lane's vectors v, v + kWaveLanes, ..., v + (U - 1) kWaveLanes are all inside the range;
+// part(v): the block's last trip when the range ends inside it (at most once per range): of those U
+// vectors only the ones below nvec exist, the first (v) always does.  Both issue their loads together: a
+// range of a few trips (a 25 M-element bucket is six) would otherwise spend as long on the pieces of its
+// last trip, one memory round trip each, as on all the others.  Every vector in [0, nvec) is visited
+// exactly once.
+template <int U, typename Full, typename Part>
 AMSP_HOST_DEVICE inline void norm_walk(uint64_t nvec, uint32_t grid, uint32_t block, uint32_t lane, Full full,
-                                       One one) {
+                                       Part part) {
     const uint64_t row = (uint64_t)grid * kWaveLanes;   // vectors the grid takes per piece index
     uint64_t v = (uint64_t)block * (kWaveLanes * U) + lane;
-    if (U > 1)
-        for (; v + (uint64_t)(U - 1) * kWaveLanes < nvec; v += (uint64_t)U * row) full(v);
-    for (; v < nvec; v += (U > 1 ? (uint64_t)kWaveLanes : row)) one(v);
+    for (; v + (uint64_t)(U - 1) * kWaveLanes < nvec; v += (uint64_t)U * row) full(v);
+    if (U > 1 && v < nvec) part(v);
 }
 
 // ---------------------------------------------------------------- host side

@@ -147,7 +147,8 @@ static int check_norm_walk(uint64_t nvec, uint32_t grid) {
     std::vector<uint8_t> seen(nvec, 0);
     int bad = 0;
     for (uint32_t block = 0; block < grid && !bad; ++block)
-        for (uint32_t lane = 0; lane < (uint32_t)kWaveLanes && !bad; ++lane)
+        for (uint32_t lane = 0; lane < (uint32_t)kWaveLanes && !bad; ++lane) {
+            int partial_trips = 0;
             norm_walk<U>(
                 nvec, grid, block, lane,
                 [&](uint64_t v) {
@@ -159,10 +160,15 @@ static int check_norm_walk(uint64_t nvec, uint32_t grid) {
                         ++seen[x];
                     }
                 },
-                [&](uint64_t v) {
-                    if (v >= nvec || v % kWaveLanes != lane) { bad = 1; return; }
-                    ++seen[v];
+                [&](uint64_t v) {   // the block's last, partial trip: at most one per block and range
+                    if (U == 1 || v >= nvec || v % kWaveLanes != lane || ++partial_trips > 1) { bad = 1; return; }
+                    if (v + (uint64_t)(U - 1) * kWaveLanes < nvec) { bad = 1; return; }   // it was a full trip
+                    for (int u = 0; u < U; ++u) {
+                        const uint64_t x = v + (uint64_t)u * kWaveLanes;
+                        if (x < nvec) ++seen[x];
+                    }
                 });
+        }
     for (uint64_t v = 0; v < nvec && !bad; ++v)
         if (seen[v] != 1) bad = 1;
     if (bad) printf("FAIL: norm walk U=%d nvec=%llu grid=%u\n", U, (unsigned long long)nvec, grid);

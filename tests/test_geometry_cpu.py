@@ -67,8 +67,10 @@ MUTATIONS = [
      "const int rc = f(begin + off, n - off < limit ? n - off : limit);", "const int rc = f(begin + off, limit);"),
     ("long range: pieces overlap by one element",
      "for (uint64_t off = 0; off < n; off += limit) {", "for (uint64_t off = 0; off < n; off += limit - 1) {"),
-    ("norm pass: the partial last trip walks a grid row apart",
-     "v += (U > 1 ? (uint64_t)kWaveLanes : row)) one(v);", "v += row) one(v);"),
+    ("norm pass: the partial last trip dropped",
+     "if (U > 1 && v < nvec) part(v);", "if (U > 1 && v + kWaveLanes < nvec) part(v);"),
+    ("norm pass: a partial trip after a trip that was full",
+     "if (U > 1 && v < nvec) part(v);", "if (U > 1 && v < nvec + (uint64_t)U * row) part(v - (v >= (uint64_t)U * row ? (uint64_t)U * row : 0));"),
 ]
 
 
