@@ -24,7 +24,7 @@ constexpr int kRwThreads = 64;         // the kernels that read and write run on
 constexpr int kVecRW = 4;              // elements per lane per stream in the kernels that write
 constexpr int kVecNorm = 8;            // elements per lane per stream in the norm pass
 constexpr int kNormThreads = 64;       // the norm pass runs one-wave blocks, a few per CU (norm_waves_per_cu)
-constexpr int kWideThreads = 1024;     // 16-wave blocks: the short-range norm kernel and the absolute-maximum pass
+constexpr int kWideThreads = 1024;     // 16-wave blocks: the short-range norm kernel
 constexpr int kNormBlocks = 2048;      // upper bound of the norm pass's grid; sizes its workspace
 constexpr uint64_t kMaxGrid = (1ull << 31) - 1;
 

@@ -465,7 +465,8 @@ struct NormRanges {
 
 // Collects short segments for one table launch.  A segment qualifies when it is shorter than
 // kShortSegment and either has a common vector phase or is so short that the edge loop of one wave
-// takes all of it; everything else gets a launch of its own.
+// takes all of it; everything else gets a launch of its own (the update and the reduction) or shares the
+// launches of the long segments (the FP8 maxima and codes).
 struct TableBuilder {
     RangeTable table;
     uint32_t count = 0, blocks = 0;
