@@ -33,6 +33,31 @@ def test_library_exports_every_declared_symbol():
     assert declared == set(B.EXPORTS)
     synth_lib = ctypes.CDLL(build.LIB_SYNTH)
     assert hasattr(synth_lib, "amsp_synth_fill_f32") and hasattr(synth_lib, "amsp_synth_fill_bf16")
+    probe_lib = ctypes.CDLL(build.LIB_PROBE)          # bench.py's traffic-only kernels, a library of their own
+    assert hasattr(probe_lib, "amsp_probe_traffic") and not hasattr(lib, "amsp_probe_traffic")
+
+
+def test_stream_placement_helper():
+    """layout.staggered_empty: stream j starts (first_index + j) * stagger bytes into an allocation of its
+    own, with the length and type asked for; stagger 0 gives plain tensors."""
+    import torch
+
+    from paper_2311_00257_amd import layout
+
+    specs = [(1000, torch.float32), (1000, torch.int16), (0, torch.float32), (7, torch.uint8)]
+    plain = layout.staggered_empty(specs, stagger=0, device="cpu")
+    assert [t.storage_offset() for t in plain] == [0, 0, 0, 0]
+    for first in (0, 3):
+        views = layout.staggered_empty(specs, first_index=first, device="cpu")
+        assert layout.STAGGER_BYTES == 4096
+        for j, (t, (n, dtype)) in enumerate(zip(views, specs)):
+            assert t.dtype == dtype and t.numel() == n and t.is_contiguous()
+            assert t.storage_offset() * t.element_size() == (first + j) * 4096
+            assert t.untyped_storage().nbytes() == n * t.element_size() + (first + j) * 4096
+        storages = {t.untyped_storage().data_ptr() for t in views}
+        assert len(storages) == len(views)                                  # an allocation each
+    with pytest.raises(AssertionError):
+        layout.staggered_empty(specs, stagger=512, device="cpu")            # not a wave-piece multiple
 
 
 def _param_types(header: str, name: str):
