@@ -218,6 +218,28 @@ def test_sqnorm_against_oracle(B, torch_mod, k):
         assert float(d_s.item()) == pytest.approx(got, rel=1e-12)
 
 
+@pytest.mark.parametrize("k,n", [(2, 1_300_007), (8, 700_001), (3, 70)])
+def test_sqnorm_when_the_partials_have_no_common_phase(B, torch_mod, k, n):
+    """One partial an element off the others: the element-wise path of the norm pass (several grid rows per
+    trip and a remainder) against the oracle, equal to the aligned result up to the order of the fp64 sum."""
+    torch = torch_mod
+    w = workloads.get(3)
+    ws = torch.empty(B.amsp_workspace_bytes() // 8, dtype=torch.float64, device="cuda")
+    d_s = torch.full((1,), 9.0, dtype=torch.float64, device="cuda")
+    inp = H.host_inputs(w, 77, n, k=k)
+    aligned = [H.to_dev_bf16(p) for p in inp.partials]
+    B.amsp_grad_sqnorm(aligned, None, n, d_s, ws)
+    ref = float(d_s.item())
+    shifted = [H.to_dev_bf16(inp.partials[0], pad_front=1)] + aligned[1:]
+    for bucket in (0, n // 3 + 1):
+        B.amsp_grad_sqnorm(shifted, None, n, d_s, ws, bucket_elems=bucket)
+        got = float(d_s.item())
+        S = oracle.sqnorm(oracle.reduce(inp.partials))
+        assert abs(got - S) <= H.REL_TOL * S and got == pytest.approx(ref, rel=1e-12)
+        B.amsp_grad_sqnorm(shifted, None, n, d_s, ws, bucket_elems=bucket)
+        assert float(d_s.item()) == got
+
+
 def test_sqnorm_constant_and_empty(B, torch_mod):
     ws = torch_mod.empty(B.amsp_workspace_bytes() // 8, dtype=torch_mod.float64, device="cuda")
     d_s = torch_mod.full((1,), 7.0, dtype=torch_mod.float64, device="cuda")
