@@ -7,13 +7,15 @@ The device runs the whole step (norm pass, then the fused update) on the full sh
   * master / m / v / bf16 are compared with the oracle element by element: on workloads 1 and 3 over the
     WHOLE shard, chunk after chunk; workloads 2 and 4 (6.7 G and 4.1 G elements) are SAMPLED: the first
     and the last 2^20 elements, a window around every bucket border (all 162 of workload 4), and a seeded
-    sixteenth of all chunks; workload 5 (inter-tensor) over every element of its 31 segments;
+    sixteenth of all chunks (AMSP_FULLSIZE_EVERY_ELEMENT=1 compares their whole shards too: four minutes);
+    workload 5 (inter-tensor) over every element of its 31 segments;
   * two checks that need no oracle cover every element of every workload: the fused pass against the
     unfused composition (reduce with the norm -> AdamW on the fp32 gradient -> cast) on a copy of the
     state, bit for bit, and amsp_cast_param_shard of the device's own master against the bf16 the fused
     pass wrote.
 
 Coverage is printed per workload."""
+import os
 from concurrent.futures import ThreadPoolExecutor
 
 import numpy as np
@@ -203,16 +205,20 @@ def test_workload3_llama13b_factor16_full():
     _run_fullsize(3, full=True)
 
 
+# AMSP_FULLSIZE_EVERY_ELEMENT=1 compares the two sampled workloads over the whole shard too (minutes of host time)
+EVERY_ELEMENT = os.environ.get("AMSP_FULLSIZE_EVERY_ELEMENT") == "1"
+
+
 def test_workload4_llama30b_bucketed_full():
     """Sampled against the oracle (every one of the 162 bucket borders, the first and last 2^20 elements, a
     seeded sixteenth of the chunks); every element against the unfused composition."""
-    _run_fullsize(4, full=False)
+    _run_fullsize(4, full=EVERY_ELEMENT)
 
 
 def test_workload2_llama7b_full_replica_full():
     """Sampled against the oracle (the first and last 2^20 elements, a seeded sixteenth of the chunks); every
     element against the unfused composition."""
-    _run_fullsize(2, full=False)
+    _run_fullsize(2, full=EVERY_ELEMENT)
 
 
 def test_workload5_llama7b_inter_tensor_full():
